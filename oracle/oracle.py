@@ -1,0 +1,187 @@
+"""Python face of the CPU oracle (ctypes over oracle/liboracle.so).  TEST INFRASTRUCTURE ONLY.
+
+Everything is planar [channels, time].  `dtype=np.float64` (default) is the parity
+oracle; `np.float32` runs the same loops in single precision (the timed CPU baseline).
+
+Windowed decode follows the three steps of paper section 3.6: extend the target
+window by a margin on both sides, decode the extended region as if it were a whole
+clip, trim the margins so that only the frame-aligned interior remains
+(prod(strides) samples per latent frame; 1920 at 48 kHz).
+
+The receptive field is derived analytically by propagating index intervals through
+the layer stack (the paper measures it empirically for the trained model; section
+3.6 gives 8.3 frames for that model, which has a different stack).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        path = _build.build(force=False)
+        _LIB = ctypes.CDLL(path)
+    return _LIB
+
+
+def omp_threads() -> int:
+    """Number of OpenMP threads the oracle's loops will use."""
+    n = os.environ.get("OMP_NUM_THREADS")
+    if n:
+        return int(n.split(",")[0])
+    return len(os.sched_getaffinity(0))
+
+
+def _sfx(dtype):
+    dtype = np.dtype(dtype)
+    if dtype == np.float64:
+        return "_f64", ctypes.c_double
+    if dtype == np.float32:
+        return "_f32", ctypes.c_float
+    raise TypeError(dtype)
+
+
+def _ptr(a, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct)) if a is not None else None
+
+
+def snake(x, alpha, beta, dtype=np.float64):
+    sfx, ct = _sfx(dtype)
+    x = np.ascontiguousarray(x, dtype=dtype)
+    alpha = np.ascontiguousarray(alpha, dtype=dtype)
+    beta = np.ascontiguousarray(beta, dtype=dtype)
+    C, L = x.shape
+    y = np.empty_like(x)
+    getattr(_lib(), "oracle_snake" + sfx)(_ptr(x, ct), C, ctypes.c_long(L), _ptr(alpha, ct),
+                                          _ptr(beta, ct), _ptr(y, ct))
+    return y
+
+
+def conv1d(x, W, b, dilation=1, dtype=np.float64):
+    """Conv1d with odd kernel and zero 'same' padding; W [Cout, Cin, K]."""
+    sfx, ct = _sfx(dtype)
+    x = np.ascontiguousarray(x, dtype=dtype)
+    W = np.ascontiguousarray(W, dtype=dtype)
+    b = None if b is None else np.ascontiguousarray(b, dtype=dtype)
+    Cin, L = x.shape
+    Cout, Cin2, K = W.shape
+    assert Cin == Cin2 and K % 2 == 1
+    y = np.empty((Cout, L), dtype=dtype)
+    getattr(_lib(), "oracle_conv1d" + sfx)(_ptr(x, ct), Cin, ctypes.c_long(L), _ptr(W, ct), _ptr(b, ct),
+                                           Cout, K, int(dilation), _ptr(y, ct))
+    return y
+
+
+def convT1d(x, W, b, stride, padding, dtype=np.float64):
+    """ConvTranspose1d; W [Cin, Cout, K]; output length (L-1) stride - 2 padding + K."""
+    sfx, ct = _sfx(dtype)
+    x = np.ascontiguousarray(x, dtype=dtype)
+    W = np.ascontiguousarray(W, dtype=dtype)
+    b = None if b is None else np.ascontiguousarray(b, dtype=dtype)
+    Cin, L = x.shape
+    Cin2, Cout, K = W.shape
+    assert Cin == Cin2
+    Lout = (L - 1) * stride - 2 * padding + K
+    y = np.empty((Cout, Lout), dtype=dtype)
+    getattr(_lib(), "oracle_convT1d" + sfx)(_ptr(x, ct), Cin, ctypes.c_long(L), _ptr(W, ct), _ptr(b, ct),
+                                            Cout, K, int(stride), int(padding), _ptr(y, ct))
+    return y
+
+
+def decode(spec, weights, latent, dtype=np.float64):
+    """Full decode.  latent [C0, T] or [n_clips, C0, T] -> [.., out_channels, T * S]."""
+    latent = np.asarray(latent)
+    if latent.ndim == 3:
+        return np.stack([decode(spec, weights, z, dtype) for z in latent])
+    sfx, ct = _sfx(dtype)
+    w = np.ascontiguousarray(weights, dtype=dtype)
+    z = np.ascontiguousarray(latent, dtype=dtype)
+    C0, T = z.shape
+    assert C0 == spec.latent_channels
+    S = spec.total_stride
+    out = np.empty((spec.out_channels, T * S), dtype=dtype)
+    IntArr = lambda v: (ctypes.c_int * len(v))(*v)
+    rc = getattr(_lib(), "oracle_decode" + sfx)(
+        C0, len(spec.strides), IntArr(spec.strides), IntArr(spec.widths),
+        len(spec.dilations), IntArr(spec.dilations), spec.res_kernel, spec.head_kernel,
+        spec.out_channels, _ptr(w, ct), _ptr(z, ct), ctypes.c_long(T), _ptr(out, ct))
+    if rc != 0:
+        raise ValueError("oracle_decode rejected the decoder description")
+    return out
+
+
+def window_grid(frame_begin: int, frame_end: int, window: int) -> List[Tuple[int, int]]:
+    """Windows start at frame_begin and step by `window`; the last may be short."""
+    return [(b, min(b + window, frame_end)) for b in range(frame_begin, frame_end, window)]
+
+
+def decode_windowed(spec, weights, latent, window, halo, frame_begin=0, frame_end=None,
+                    dtype=np.float64):
+    """Windowed decode of frames [frame_begin, frame_end): returns [.., out_channels, (end-begin) S]."""
+    latent = np.asarray(latent)
+    if latent.ndim == 3:
+        return np.stack([decode_windowed(spec, weights, z, window, halo, frame_begin, frame_end, dtype)
+                         for z in latent])
+    T = latent.shape[1]
+    if frame_end is None:
+        frame_end = T
+    S = spec.total_stride
+    pieces = []
+    for b, e in window_grid(frame_begin, frame_end, window):
+        lo, hi = max(0, b - halo), min(T, e + halo)          # step 1: extend by the margins
+        y = decode(spec, weights, latent[:, lo:hi], dtype)   # step 2: decode the extended region
+        pieces.append(y[:, (b - lo) * S:(e - lo) * S])       # step 3: trim to the frame-aligned interior
+    return np.concatenate(pieces, axis=1)
+
+
+# ---------------------------------------------------------------- receptive field (analytic)
+
+def _layers(spec):
+    """(kind, kernel, stride_or_dilation, padding) of every layer that moves indices, input to output."""
+    out = []
+    for s in spec.strides:
+        out.append(("convT", 2 * s, s, s // 2))
+        for d in spec.dilations:
+            out.append(("conv", spec.res_kernel, d, 0))
+    out.append(("conv", spec.head_kernel, 1, 0))
+    return out
+
+
+def backward_interval(spec, a: int, b: int) -> Tuple[int, int]:
+    """Latent frames [lo, hi] that output samples [a, b] depend on (clip edges ignored)."""
+    for kind, K, sd, p in reversed(_layers(spec)):
+        if kind == "conv":
+            r = sd * (K - 1) // 2
+            a, b = a - r, b + r
+        else:
+            # output n takes input m when 0 <= n + p - m s <= K - 1
+            a, b = -((-(a + p - K + 1)) // sd), (b + p) // sd
+    return a, b
+
+
+def forward_interval(spec, a: int, b: int) -> Tuple[int, int]:
+    """Output samples [lo, hi] that latent frames [a, b] can influence (clip edges ignored)."""
+    for kind, K, sd, p in _layers(spec):
+        if kind == "conv":
+            r = sd * (K - 1) // 2
+            a, b = a - r, b + r
+        else:
+            a, b = a * sd - p, b * sd - p + K - 1
+    return a, b
+
+
+def receptive_field(spec) -> Tuple[int, int]:
+    """(halo_left, halo_right) in latent frames: context one output frame needs on each side."""
+    S = spec.total_stride
+    f = 1000                                   # any frame; the stack is shift-invariant
+    lo, hi = backward_interval(spec, f * S, (f + 1) * S - 1)
+    return f - lo, hi - f
