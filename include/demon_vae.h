@@ -1,0 +1,172 @@
+/*
+ * demon_vae.h -- C ABI of the windowed VAE decode for AMD MI355X (gfx950).
+ *
+ * The operation is the windowed decode of paper section 3.6: a temporal audio
+ * latent (25 Hz) is cut into windows, every window is extended by a halo of
+ * latent frames on both sides, the extended windows go through the 1-D
+ * convolutional audio decoder as one batch, the halos are trimmed and the
+ * frame-aligned interiors (prod(strides) samples per latent frame, 1920 at
+ * 48 kHz) are written side by side into the waveform.  With a halo at least as
+ * large as the decoder's receptive field the result equals the full decode.
+ *
+ * The decoder is the synthetic stack of the benchmark description (the paper
+ * does not list the layers of the trained model):
+ *   for each upsample block l:  Snake -> ConvTranspose1d(kernel 2 s_l, stride s_l, padding s_l/2)
+ *                               then n_res residual units  h += Conv1d_k1(Snake(Conv1d_k,dil(Snake(h))))
+ *   head:                       Snake -> Conv1d(head_kernel) -> tanh
+ *   snake(x) = x + sin(alpha_c x)^2 / (beta_c + 1e-9), per channel c.
+ *
+ * All entry points return a status and never throw or abort.  A handle may be
+ * used by one host thread at a time.  Decode calls are asynchronous on the
+ * given HIP stream and do not synchronise; they allocate nothing.
+ */
+#ifndef DEMON_VAE_H
+#define DEMON_VAE_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct demon_vae demon_vae; /* opaque; owned by the library */
+
+typedef enum {
+    DEMON_OK = 0,
+    DEMON_ERR_INVALID_ARG = 1, /* null pointer, bad range, bad layer description, wrong weight count */
+    DEMON_ERR_UNSUPPORTED = 2, /* a layer shape the kernels do not cover (see demon_vae_create) */
+    DEMON_ERR_WORKSPACE = 3,   /* the call needs more frames, clips or windows than create() sized for */
+    DEMON_ERR_HIP = 4          /* a HIP runtime call or a kernel launch failed */
+} demon_status;
+
+typedef enum {
+    DEMON_F32 = 0, /* fp32 storage and arithmetic (reference-precision path)            */
+    DEMON_BF16 = 1 /* bf16 weights/activations, fp32 MFMA accumulation and epilogues    */
+} demon_dtype;
+
+/* Layer stack and workspace limits.  Arrays are read during the call only. */
+typedef struct {
+    int latent_channels;  /* C0 */
+    int n_blocks;         /* number of upsample blocks, 1..16 */
+    const int* strides;   /* [n_blocks], each even and >= 2 */
+    const int* widths;    /* [n_blocks], output channels of each block */
+    int n_res;            /* residual units per block, 0..8 */
+    const int* dilations; /* [n_res] */
+    int res_kernel;       /* odd; 7 in the benchmark stacks */
+    int head_kernel;      /* odd */
+    int out_channels;     /* 1..8; 2 = stereo */
+    demon_dtype dtype;
+    int max_frames;       /* longest latent (frames per clip) a decode call may pass */
+    int max_clips;        /* most clips a decode call may pass */
+    long long max_extended_frames; /* most latent frames, summed over all extended windows (window + halos)
+                                      of one call, the workspace must hold; 0 = 3 * max_frames * max_clips */
+} demon_vae_config;
+
+/* One window of the grid: interior latent frames [begin, end) of clip `clip`, decoded from the
+ * extended region [lo, hi) = [max(0, begin - halo), min(n_frames, end + halo)). */
+typedef struct {
+    int clip;
+    int begin, end;
+    int lo, hi;
+} demon_window;
+
+/*
+ * Number of fp32 values demon_vae_create expects: per block up.alpha[C_in], up.beta[C_in],
+ * up.weight[C_in, C, 2s], up.bias[C]; per residual unit a1.alpha[C], a1.beta[C],
+ * c1.weight[C, C, res_kernel], c1.bias[C], a2.alpha[C], a2.beta[C], c2.weight[C, C, 1], c2.bias[C];
+ * then head.alpha[C], head.beta[C], head.weight[out_channels, C, head_kernel], head.bias[out_channels]
+ * -- in that order, each tensor C-contiguous.  Host only.  Returns 0 for an invalid description.
+ */
+size_t demon_vae_weight_count(const demon_vae_config* cfg);
+
+/*
+ * Receptive field of the layer stack in latent frames (host only, no GPU needed): output frame f
+ * depends on latent frames [f - *halo_left, f + *halo_right].  Derived by propagating index
+ * intervals backwards through the stack: a k-tap convolution of dilation d widens an interval by
+ * d (k-1)/2 on both sides; a transposed convolution (kernel k, stride s, padding p) maps output
+ * samples [a, b] to inputs [ceil((a + p - k + 1)/s), floor((b + p)/s)].  This is the analytic
+ * counterpart of the measured convergence distance of section 3.6.
+ */
+demon_status demon_vae_rf_from_config(const demon_vae_config* cfg, int* halo_left, int* halo_right);
+
+/*
+ * Output samples [*lo, *hi] that latent frames [frame_a, frame_b] can influence, ignoring clip
+ * edges (the forward cone; host only).
+ */
+demon_status demon_vae_forward_support(const demon_vae_config* cfg, int frame_a, int frame_b,
+                                       long long* lo, long long* hi);
+
+/*
+ * The window grid of section 3.6 for frames [frame_begin, frame_end) of each of n_clips clips of
+ * n_frames frames: windows start at frame_begin and step by `window`, the last one may be short;
+ * each is extended by `halo` frames, clamped to the clip.  Host only.  Writes at most `capacity`
+ * entries to `out` (may be NULL to count) and the total number to *n_windows.
+ * INVALID_ARG: n_clips < 1, n_frames < 1, frame_begin < 0, frame_end > n_frames,
+ * frame_begin >= frame_end, window < 1, halo < 0, n_windows NULL.
+ */
+demon_status demon_vae_plan_windows(int n_clips, int n_frames, int frame_begin, int frame_end,
+                                    int window, int halo, demon_window* out, int capacity,
+                                    int* n_windows);
+
+/*
+ * Builds a decoder on the current HIP device.  `host_weights` (host memory, fp32, canonical order,
+ * demon_vae_weight_count(cfg) values) is copied and repacked during the call and may be freed
+ * afterwards; for DEMON_BF16 the values are rounded to bf16 (nearest even) here.  Allocates device
+ * weights and a workspace for max_extended_frames frames of extended windows.  *out receives the handle.
+ * INVALID_ARG: null pointers, bad layer description (odd stride, even kernel, non-positive sizes),
+ * n_floats != demon_vae_weight_count.  UNSUPPORTED: head_kernel > 15; DEMON_BF16 only: latent_channels
+ * not a multiple of 16, a width not a multiple of 32, or a dilated kernel spanning more than 64 samples.  HIP: no device / allocation
+ * failure.
+ */
+demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_weights, size_t n_floats,
+                              demon_vae** out);
+
+/* Frees device memory and the handle.  NULL is ignored.  The caller must have synchronised the
+ * streams it used with this handle. */
+void demon_vae_destroy(demon_vae* vae);
+
+/* Receptive field of this decoder (same as demon_vae_rf_from_config). Host only. */
+demon_status demon_vae_receptive_field(const demon_vae* vae, int* halo_left, int* halo_right);
+
+/*
+ * Full decode (section 3.6, the un-windowed baseline): every clip is one window covering
+ * [0, n_frames) with no halo.
+ *   d_latent : device, [n_clips, latent_channels, n_frames], frames fastest; fp32 for DEMON_F32,
+ *              bf16 (16-bit) for DEMON_BF16.  Read only.
+ *   d_out    : device, fp32, [n_clips, out_channels, n_frames * S] planar, S = prod(strides).
+ *   stream   : hipStream_t (NULL = default stream).
+ */
+demon_status demon_vae_decode(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
+                              float* d_out, void* stream);
+
+/*
+ * Windowed decode of latent frames [frame_begin, frame_end) of every clip: gather the extended
+ * windows, run them through the decoder as one batch, trim the halos, write the interiors.
+ * Writes only d_out[:, :, frame_begin*S : frame_end*S); the rest of d_out is left untouched, so a
+ * partial re-decode splices into an existing waveform.  `halo` in latent frames; -1 = the analytic
+ * receptive field; a smaller halo is legal but inexact near window joins.
+ * frame_end - frame_begin <= window decodes a single playback window.
+ * Layouts as for demon_vae_decode (d_latent and d_out are whole-clip buffers).
+ * INVALID_ARG: null pointers, n_clips < 1, n_frames < 1, frame_begin < 0, frame_end > n_frames,
+ * frame_begin >= frame_end, window < 1, halo < -1.  WORKSPACE: n_frames > max_frames,
+ * n_clips > max_clips, more than 4096 windows, or extended windows that exceed the workspace.
+ */
+demon_status demon_vae_decode_windowed(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
+                                       int frame_begin, int frame_end, int window, int halo,
+                                       float* d_out, void* stream);
+
+/*
+ * Test aid: after the next decode calls, copy the activation produced by layer `layer` (0-based
+ * index into the sequence up_0, res_0_0 .. res_0_{n_res-1}, up_1, ...; -1 disables) of all
+ * extended windows to d_dst as fp32, row-major [extended samples at that level, channels].
+ * At most `capacity` floats are written.  d_dst is device memory owned by the caller.
+ */
+demon_status demon_vae_debug_tap(demon_vae* vae, int layer, float* d_dst, size_t capacity);
+
+/* Message of the last error returned on this thread (empty string if none). Never NULL. */
+const char* demon_vae_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEMON_VAE_H */

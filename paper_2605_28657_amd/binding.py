@@ -1,0 +1,232 @@
+"""Thin ctypes binding of include/demon_vae.h: argument marshalling only.
+
+Every step of the decode runs in the HIP library; PyTorch supplies device memory and
+streams.  There is no fallback: if libdemon_vae.so cannot be loaded (and cannot be
+built because hipcc is absent) importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdemon_vae.so")
+
+DEMON_OK, DEMON_ERR_INVALID_ARG, DEMON_ERR_UNSUPPORTED, DEMON_ERR_WORKSPACE, DEMON_ERR_HIP = range(5)
+DEMON_F32, DEMON_BF16 = 0, 1
+_STATUS_NAMES = {0: "OK", 1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE", 4: "HIP"}
+
+
+class DemonError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"demon_vae: {_STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+        self.message = message
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [("latent_channels", ctypes.c_int), ("n_blocks", ctypes.c_int),
+                ("strides", ctypes.POINTER(ctypes.c_int)), ("widths", ctypes.POINTER(ctypes.c_int)),
+                ("n_res", ctypes.c_int), ("dilations", ctypes.POINTER(ctypes.c_int)),
+                ("res_kernel", ctypes.c_int), ("head_kernel", ctypes.c_int), ("out_channels", ctypes.c_int),
+                ("dtype", ctypes.c_int), ("max_frames", ctypes.c_int), ("max_clips", ctypes.c_int),
+                ("max_extended_frames", ctypes.c_longlong)]
+
+
+class _Window(ctypes.Structure):
+    _fields_ = [("clip", ctypes.c_int), ("begin", ctypes.c_int), ("end", ctypes.c_int),
+                ("lo", ctypes.c_int), ("hi", ctypes.c_int)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libdemon_vae.so (building it first only if it does not exist)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    P = ctypes.POINTER
+    lib.demon_vae_weight_count.restype = ctypes.c_size_t
+    lib.demon_vae_weight_count.argtypes = [P(_Config)]
+    lib.demon_vae_rf_from_config.argtypes = [P(_Config), P(ctypes.c_int), P(ctypes.c_int)]
+    lib.demon_vae_forward_support.argtypes = [P(_Config), ctypes.c_int, ctypes.c_int, P(ctypes.c_longlong), P(ctypes.c_longlong)]
+    lib.demon_vae_plan_windows.argtypes = [ctypes.c_int] * 6 + [P(_Window), ctypes.c_int, P(ctypes.c_int)]
+    lib.demon_vae_create.argtypes = [P(_Config), P(ctypes.c_float), ctypes.c_size_t, P(ctypes.c_void_p)]
+    lib.demon_vae_destroy.argtypes = [ctypes.c_void_p]
+    lib.demon_vae_destroy.restype = None
+    lib.demon_vae_receptive_field.argtypes = [ctypes.c_void_p, P(ctypes.c_int), P(ctypes.c_int)]
+    lib.demon_vae_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    lib.demon_vae_decode_windowed.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 6 + [ctypes.c_void_p, ctypes.c_void_p]
+    lib.demon_vae_debug_tap.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t]
+    lib.demon_vae_last_error.restype = ctypes.c_char_p
+    lib.demon_vae_last_error.argtypes = []
+    _lib = lib
+    return lib
+
+
+def demon_vae_last_error() -> str:
+    return load_library().demon_vae_last_error().decode()
+
+
+def _check(status: int):
+    if status != DEMON_OK:
+        raise DemonError(status, demon_vae_last_error())
+
+
+def _make_config(latent_channels: int, strides: Sequence[int], widths: Sequence[int], dilations: Sequence[int],
+                 res_kernel: int, head_kernel: int, out_channels: int, dtype: int = DEMON_F32,
+                 max_frames: int = 1, max_clips: int = 1, max_extended_frames: int = 0):
+    """Returns (config struct, keep-alive tuple of the int arrays it points to)."""
+    s = (ctypes.c_int * max(len(strides), 1))(*strides)
+    w = (ctypes.c_int * max(len(widths), 1))(*widths)
+    d = (ctypes.c_int * max(len(dilations), 1))(*dilations)
+    if len(strides) != len(widths):
+        raise ValueError("strides and widths differ in length")
+    cfg = _Config(latent_channels, len(strides), s, w, len(dilations), d, res_kernel, head_kernel, out_channels,
+                  dtype, max_frames, max_clips, max_extended_frames)
+    return cfg, (s, w, d)
+
+
+def config_from_spec(spec, dtype: int = DEMON_F32, max_frames: int = 1, max_clips: int = 1,
+                     max_extended_frames: int = 0):
+    """Config from any object with latent_channels/strides/widths/dilations/res_kernel/head_kernel/out_channels."""
+    return _make_config(spec.latent_channels, spec.strides, spec.widths, spec.dilations, spec.res_kernel,
+                        spec.head_kernel, spec.out_channels, dtype, max_frames, max_clips, max_extended_frames)
+
+
+def demon_vae_weight_count(spec) -> int:
+    cfg, _keep = config_from_spec(spec)
+    return int(load_library().demon_vae_weight_count(ctypes.byref(cfg)))
+
+
+def demon_vae_rf_from_config(spec) -> Tuple[int, int]:
+    cfg, _keep = config_from_spec(spec)
+    l, r = ctypes.c_int(), ctypes.c_int()
+    _check(load_library().demon_vae_rf_from_config(ctypes.byref(cfg), ctypes.byref(l), ctypes.byref(r)))
+    return l.value, r.value
+
+
+def demon_vae_forward_support(spec, frame_a: int, frame_b: int) -> Tuple[int, int]:
+    cfg, _keep = config_from_spec(spec)
+    lo, hi = ctypes.c_longlong(), ctypes.c_longlong()
+    _check(load_library().demon_vae_forward_support(ctypes.byref(cfg), frame_a, frame_b, ctypes.byref(lo), ctypes.byref(hi)))
+    return lo.value, hi.value
+
+
+def demon_vae_plan_windows(n_clips: int, n_frames: int, frame_begin: int, frame_end: int, window: int,
+                           halo: int) -> List[dict]:
+    lib = load_library()
+    n = ctypes.c_int()
+    _check(lib.demon_vae_plan_windows(n_clips, n_frames, frame_begin, frame_end, window, halo, None, 0, ctypes.byref(n)))
+    arr = (_Window * max(n.value, 1))()
+    _check(lib.demon_vae_plan_windows(n_clips, n_frames, frame_begin, frame_end, window, halo, arr, n.value, ctypes.byref(n)))
+    return [dict(clip=w.clip, begin=w.begin, end=w.end, lo=w.lo, hi=w.hi) for w in arr[:n.value]]
+
+
+def demon_vae_create(spec, weights: np.ndarray, dtype: int, max_frames: int, max_clips: int = 1,
+                     max_extended_frames: int = 0) -> int:
+    """Returns the opaque handle (an integer address).  `weights`: flat fp32 host array, canonical order."""
+    cfg, _keep = config_from_spec(spec, dtype, max_frames, max_clips, max_extended_frames)
+    w = np.ascontiguousarray(weights, dtype=np.float32)
+    handle = ctypes.c_void_p()
+    _check(load_library().demon_vae_create(ctypes.byref(cfg), w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+                                           w.size, ctypes.byref(handle)))
+    return handle.value
+
+
+def demon_vae_destroy(handle: Optional[int]):
+    if handle:
+        load_library().demon_vae_destroy(handle)
+
+
+def demon_vae_receptive_field(handle: int) -> Tuple[int, int]:
+    l, r = ctypes.c_int(), ctypes.c_int()
+    _check(load_library().demon_vae_receptive_field(handle, ctypes.byref(l), ctypes.byref(r)))
+    return l.value, r.value
+
+
+def demon_vae_decode(handle: int, d_latent: int, n_clips: int, n_frames: int, d_out: int, stream: int = 0):
+    """d_latent / d_out are device addresses (tensor.data_ptr()); stream is a hipStream_t address."""
+    _check(load_library().demon_vae_decode(handle, d_latent, n_clips, n_frames, d_out, stream))
+
+
+def demon_vae_decode_windowed(handle: int, d_latent: int, n_clips: int, n_frames: int, frame_begin: int,
+                              frame_end: int, window: int, halo: int, d_out: int, stream: int = 0):
+    _check(load_library().demon_vae_decode_windowed(handle, d_latent, n_clips, n_frames, frame_begin, frame_end,
+                                                    window, halo, d_out, stream))
+
+
+def demon_vae_debug_tap(handle: int, layer: int, d_dst: int, capacity: int):
+    _check(load_library().demon_vae_debug_tap(handle, layer, d_dst, capacity))
+
+
+class DemonVAE:
+    """Convenience wrapper: owns a handle, marshals torch tensors.  No arithmetic happens here."""
+
+    def __init__(self, spec, weights: np.ndarray, dtype: str = "bf16", max_frames: int = 1500, max_clips: int = 1,
+                 max_extended_frames: int = 0):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("DemonVAE needs a HIP device; there is no CPU fallback")
+        self.spec = spec
+        self.dtype = {"bf16": DEMON_BF16, "f32": DEMON_F32}[dtype]
+        self.torch_dtype = torch.bfloat16 if self.dtype == DEMON_BF16 else torch.float32
+        self.S = 1
+        for s in spec.strides:
+            self.S *= s
+        self.handle = demon_vae_create(spec, weights, self.dtype, max_frames, max_clips, max_extended_frames)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            import torch
+            torch.cuda.synchronize()
+            demon_vae_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def receptive_field(self) -> Tuple[int, int]:
+        return demon_vae_receptive_field(self.handle)
+
+    def _prep(self, latent, out):
+        import torch
+        if latent.dim() == 2:
+            latent = latent[None]
+        assert latent.is_cuda and latent.dtype == self.torch_dtype and latent.is_contiguous()
+        n_clips, c, t = latent.shape
+        assert c == self.spec.latent_channels
+        if out is None:
+            out = torch.empty((n_clips, self.spec.out_channels, t * self.S), dtype=torch.float32, device=latent.device)
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+        assert tuple(out.shape) == (n_clips, self.spec.out_channels, t * self.S)
+        return latent, out, n_clips, t, torch.cuda.current_stream().cuda_stream
+
+    def decode(self, latent, out=None):
+        latent, out, n_clips, t, stream = self._prep(latent, out)
+        demon_vae_decode(self.handle, latent.data_ptr(), n_clips, t, out.data_ptr(), stream)
+        return out
+
+    def decode_windowed(self, latent, window: int, halo: int = -1, frame_begin: int = 0,
+                        frame_end: Optional[int] = None, out=None):
+        latent, out, n_clips, t, stream = self._prep(latent, out)
+        if frame_end is None:
+            frame_end = t
+        demon_vae_decode_windowed(self.handle, latent.data_ptr(), n_clips, t, frame_begin, frame_end, window, halo,
+                                  out.data_ptr(), stream)
+        return out
+
+    def tap(self, layer: int, dst=None):
+        demon_vae_debug_tap(self.handle, layer, dst.data_ptr() if dst is not None else 0,
+                            dst.numel() if dst is not None else 0)

@@ -1,0 +1,457 @@
+// C ABI of libdemon_vae: decoder construction (weight repacking, workspace), window plans and the
+// launch sequence of the windowed decode (paper section 3.6: extend, decode, trim).
+#include <math.h>
+#include <string.h>
+
+#include <algorithm>
+#include <memory>
+#include <new>
+
+#include "internal.h"
+
+using namespace demon;
+
+namespace {
+
+constexpr int kMaxSlots = 4096;
+constexpr int kPlanCache = 8;
+// bf16 path: blocks at least this wide carry the inputs of their transposed conv and of their 1x1
+// convs as hi + lo bf16 pairs.  There the branch gain (weight std x sqrt(fan-in)) is about one, so
+// operand rounding passes into the output at full strength, while the extra MFMA work is small
+// (these GEMMs have short K).
+constexpr int kSplitWidth = 512;
+
+struct ConvLayer {
+    int cin = 0, cout = 0, ntaps = 0, dil = 1, stride = 0, variant = -1;
+    bool split_in = false, split_out = false;
+    const void* w = nullptr;
+    const float* bias = nullptr;
+    const float* in_alpha = nullptr;   const float* in_inv_beta = nullptr;
+    const float* out_alpha = nullptr;  const float* out_inv_beta = nullptr;
+};
+
+struct ResUnit { ConvLayer dilated, pointwise; };
+struct Block { ConvLayer up; std::vector<ResUnit> res; };
+
+struct Plan {
+    bool valid = false;
+    int n_clips = 0, n_frames = 0, frame_begin = 0, frame_end = 0, window = 0, halo = 0;
+    int n_slots = 0, max_len = 0, max_int = 0;
+    long long total_frames = 0;
+    Slot* d_slots = nullptr;
+    unsigned long long last_use = 0;
+};
+
+}  // namespace
+
+struct demon_vae {
+    Stack st;
+    demon_dtype dtype = DEMON_F32;
+    int max_frames = 0, max_clips = 0;
+    long long cap_frames = 0;
+    size_t act_elems = 0;              // elements one activation buffer holds
+    int rf_left = 0, rf_right = 0;
+    int device = 0;
+
+    void* d_params = nullptr;          // one allocation: all packed weights, biases, Snake parameters
+    std::vector<Block> blocks;
+    const float* head_w = nullptr;  const float* head_bias = nullptr;
+    const float* head_alpha = nullptr;  const float* head_inv_beta = nullptr;
+    int head_cin = 0;
+
+    // fp32 path: residual stream ping/pong + Snake scratch, all fp32.
+    // bf16 path: buf[0], buf[1] fp32 residual stream ping/pong, buf[2] bf16 activated branch tensor.
+    void* buf[3] = {nullptr, nullptr, nullptr};
+    float* head_out = nullptr;                     // planar window waveforms [out_channels, cap_frames*S]
+    Slot* d_slot_arena = nullptr;
+    Plan plans[kPlanCache];
+    unsigned long long use_counter = 0;
+
+    int tap_layer = -1;
+    float* tap_dst = nullptr;
+    size_t tap_cap = 0;
+};
+
+namespace {
+
+// Host-side staging of the parameter arena: offsets are assigned while packing, pointers afterwards.
+struct Arena {
+    std::vector<unsigned char> bytes;
+    size_t reserve(size_t n) {
+        const size_t off = (bytes.size() + 255) & ~(size_t)255;
+        bytes.resize(off + n);
+        return off;
+    }
+};
+
+struct SnakeOff { size_t alpha, inv_beta; };
+
+SnakeOff pack_snake(Arena& ar, const float* alpha, const float* beta, int c, bool fast)
+{
+    SnakeOff o;
+    o.alpha = ar.reserve(sizeof(float) * c);
+    o.inv_beta = ar.reserve(sizeof(float) * c);
+    float* a = reinterpret_cast<float*>(ar.bytes.data() + o.alpha);
+    float* b = reinterpret_cast<float*>(ar.bytes.data() + o.inv_beta);
+    for (int i = 0; i < c; ++i) {
+        // the fast Snake feeds the hardware sine, which takes revolutions
+        a[i] = fast ? (float)((double)alpha[i] / (2.0 * M_PI)) : alpha[i];
+        b[i] = (float)(1.0 / ((double)beta[i] + 1e-9));
+    }
+    return o;
+}
+
+size_t pack_floats(Arena& ar, const float* src, size_t n)
+{
+    const size_t off = ar.reserve(sizeof(float) * n);
+    memcpy(ar.bytes.data() + off, src, sizeof(float) * n);
+    return off;
+}
+
+size_t pack_conv(Arena& ar, const float* w, ConvLayer& L, bool bf16)
+{
+    if (bf16) {
+        const size_t n = packed_bf16_count(L.cin, L.cout, L.ntaps, L.stride, L.variant);
+        const size_t off = ar.reserve(n * 2);
+        pack_bf16(w, L.cin, L.cout, L.ntaps, L.stride, L.variant, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
+        return off;
+    }
+    const size_t n = packed_f32_count(L.cin, L.cout, L.ntaps, L.stride);
+    const size_t off = ar.reserve(n * 4);
+    pack_f32(w, L.cin, L.cout, L.ntaps, L.stride, reinterpret_cast<float*>(ar.bytes.data() + off));
+    return off;
+}
+
+demon_status hip_fail(hipError_t e, const char* what)
+{
+    return fail(DEMON_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+void build_slots(int n_clips, int n_frames, int fb, int fe, int window, int halo, std::vector<Slot>* out,
+                 long long* total, int* max_len, int* max_int)
+{
+    long long row = 0;
+    int ml = 0, mi = 0;
+    for (int c = 0; c < n_clips; ++c)
+        for (long long b = fb; b < fe; b += window) {
+            const long long e = std::min<long long>(b + window, fe);
+            Slot s;
+            s.clip = c;
+            s.lo = (int)std::max<long long>(0, b - halo);
+            const int hi = (int)std::min<long long>(n_frames, e + halo);
+            s.len = hi - s.lo;
+            s.crop = (int)b - s.lo;
+            s.n_int = (int)(e - b);
+            s.begin = (int)b;
+            s.row0 = (int)row;
+            s.pad = 0;
+            row += s.len;
+            ml = std::max(ml, s.len);
+            mi = std::max(mi, s.n_int);
+            out->push_back(s);
+        }
+    *total = row; *max_len = ml; *max_int = mi;
+}
+
+demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, int window, int halo, Plan** out)
+{
+    ++v->use_counter;
+    Plan* victim = &v->plans[0];
+    for (Plan& p : v->plans) {
+        if (p.valid && p.n_clips == n_clips && p.n_frames == n_frames && p.frame_begin == fb && p.frame_end == fe &&
+            p.window == window && p.halo == halo) {
+            p.last_use = v->use_counter;
+            *out = &p;
+            return DEMON_OK;
+        }
+        if (!p.valid) { if (victim->valid) victim = &p; }
+        else if (victim->valid && p.last_use < victim->last_use) victim = &p;
+    }
+    const long long per_clip = ((long long)fe - fb + window - 1) / window;
+    if (per_clip * n_clips > kMaxSlots)
+        return fail(DEMON_ERR_WORKSPACE, "%lld windows exceed the limit of %d", per_clip * n_clips, kMaxSlots);
+    std::vector<Slot> slots;
+    long long total; int max_len, max_int;
+    build_slots(n_clips, n_frames, fb, fe, window, halo, &slots, &total, &max_len, &max_int);
+    if (total > v->cap_frames)
+        return fail(DEMON_ERR_WORKSPACE, "extended windows need %lld frames, the workspace holds %lld", total, v->cap_frames);
+    if (victim->valid) {
+        // the table being replaced may still be read by kernels of an earlier call
+        hipError_t e = hipDeviceSynchronize();
+        if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
+    }
+    const int idx = (int)(victim - v->plans);
+    Slot* d = v->d_slot_arena + (size_t)idx * kMaxSlots;
+    hipError_t e = hipMemcpy(d, slots.data(), sizeof(Slot) * slots.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpy(window table)");
+    victim->valid = true;
+    victim->n_clips = n_clips; victim->n_frames = n_frames; victim->frame_begin = fb; victim->frame_end = fe;
+    victim->window = window; victim->halo = halo;
+    victim->n_slots = (int)slots.size(); victim->max_len = max_len; victim->max_int = max_int;
+    victim->total_frames = total; victim->d_slots = d; victim->last_use = v->use_counter;
+    *out = victim;
+    return DEMON_OK;
+}
+
+#define HIP_TRY(expr, what) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_fail(e_, what); } while (0)
+
+demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_frames, int fb, int fe,
+                        int window, int halo, float* d_out, hipStream_t stream)
+{
+    Plan* plan = nullptr;
+    demon_status rc = get_plan(v, n_clips, n_frames, fb, fe, window, halo, &plan);
+    if (rc != DEMON_OK) return rc;
+    const bool bf = v->dtype == DEMON_BF16;
+    const Slot* slots = plan->d_slots;
+    const int ns = plan->n_slots, ml = plan->max_len;
+
+    void* cur = v->buf[0];
+    void* other = v->buf[1];
+    HIP_TRY(launch_gather(d_latent, (float*)cur, v->st.c0, n_frames, bf, slots, ns, ml, stream), "gather");
+
+    int r = 1, layer_id = 0;
+    auto conv_args = [&](const ConvLayer& L, const void* x, void* y, const void* res) {
+        ConvArgs a;
+        a.x = x; a.y = y; a.res = res; a.w = L.w; a.bias = L.bias;
+        a.in_alpha = L.in_alpha; a.in_inv_beta = L.in_inv_beta;
+        a.out_alpha = L.out_alpha; a.out_inv_beta = L.out_inv_beta;
+        a.slots = slots; a.n_slots = ns; a.max_len = ml; a.r_in = r;
+        a.cin = L.cin; a.cout = L.cout; a.ntaps = L.ntaps; a.dil = L.dil; a.stride = L.stride;
+        a.split_in = L.split_in; a.split_out = L.split_out;
+        a.in_lo_off = a.out_lo_off = (long long)v->act_elems;    // lo plane of the split branch tensor in buf[2]
+        return a;
+    };
+    auto tap = [&](const void* x, int c) -> hipError_t {
+        const int id = layer_id++;
+        if (id != v->tap_layer || !v->tap_dst) return hipSuccess;
+        const size_t n = std::min<size_t>(v->tap_cap, (size_t)plan->total_frames * r * c);
+        return launch_to_f32(x, v->tap_dst, n, false, stream);
+    };
+    // fp32 path: Snake on a layer's input runs as its own kernel into buf[2]
+    auto run_conv = [&](const ConvLayer& L, const void* x, void* y, const void* res) -> hipError_t {
+        if (bf) return launch_conv_bf16(conv_args(L, x, y, res), L.variant, stream);
+        ConvArgs a = conv_args(L, x, y, res);
+        if (L.in_alpha) {
+            hipError_t e = launch_snake_f32((const float*)x, (float*)v->buf[2], L.in_alpha, L.in_inv_beta, L.cin,
+                                            (size_t)plan->total_frames * r * L.cin, stream);
+            if (e != hipSuccess) return e;
+            a.x = v->buf[2];
+            a.in_alpha = a.in_inv_beta = nullptr;
+        }
+        return launch_conv_f32(a, stream);
+    };
+
+    for (const Block& B : v->blocks) {
+        HIP_TRY(run_conv(B.up, cur, other, nullptr), "transposed convolution");
+        std::swap(cur, other);
+        r *= B.up.stride;
+        HIP_TRY(tap(cur, B.up.cout), "debug tap");
+        void* mid = bf ? v->buf[2] : other;
+        for (const ResUnit& U : B.res) {
+            HIP_TRY(run_conv(U.dilated, cur, mid, nullptr), "dilated convolution");
+            HIP_TRY(run_conv(U.pointwise, mid, cur, cur), "pointwise convolution");   // in place on the residual stream
+            HIP_TRY(tap(cur, U.pointwise.cout), "debug tap");
+        }
+    }
+    const long long total_rows = plan->total_frames * r;
+    HIP_TRY(launch_head((const float*)cur, v->head_out, v->head_w, v->head_bias, v->head_alpha, v->head_inv_beta, v->head_cin,
+                        v->st.out_channels, v->st.head_kernel, r, total_rows, bf, slots, ns, ml, stream), "head");
+    HIP_TRY(launch_stitch(v->head_out, d_out, v->st.out_channels, r, n_frames, total_rows, slots, ns, plan->max_int, stream), "stitch");
+    return DEMON_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_weights, size_t n_floats, demon_vae** out)
+{
+    clear_error();
+    if (!out) return fail(DEMON_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!host_weights) return fail(DEMON_ERR_INVALID_ARG, "host_weights is NULL");
+    Stack st;
+    demon_status rc = stack_from_config(cfg, &st);
+    if (rc != DEMON_OK) return rc;
+    if (cfg->dtype != DEMON_F32 && cfg->dtype != DEMON_BF16) return fail(DEMON_ERR_INVALID_ARG, "unknown dtype %d", (int)cfg->dtype);
+    if (cfg->max_frames < 1 || cfg->max_clips < 1) return fail(DEMON_ERR_INVALID_ARG, "max_frames and max_clips must be >= 1");
+    const size_t need = stack_weight_count(st);
+    if (n_floats != need) return fail(DEMON_ERR_INVALID_ARG, "got %zu weights, the layer stack needs %zu", n_floats, need);
+    const bool bf = cfg->dtype == DEMON_BF16;
+    if (bf) {
+        if (st.c0 % 16) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: latent_channels %d is not a multiple of 16", st.c0);
+        for (int c : st.widths)
+            if (c % 32) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: width %d is not a multiple of 32", c);
+        for (int d : st.dilations)
+            if ((st.res_kernel - 1) * d > 64)
+                return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: kernel %d with dilation %d spans more than 64 samples", st.res_kernel, d);
+    }
+    if (st.head_kernel > 15) return fail(DEMON_ERR_UNSUPPORTED, "head_kernel %d exceeds 15", st.head_kernel);
+
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(DEMON_ERR_HIP, "no HIP device available");
+
+    std::unique_ptr<demon_vae> v(new (std::nothrow) demon_vae);
+    if (!v) return fail(DEMON_ERR_HIP, "out of host memory");
+
+    v->st = st; v->dtype = cfg->dtype; v->max_frames = cfg->max_frames; v->max_clips = cfg->max_clips;
+    if (cfg->max_extended_frames < 0) return fail(DEMON_ERR_INVALID_ARG, "max_extended_frames must be >= 0");
+    v->cap_frames = cfg->max_extended_frames > 0 ? cfg->max_extended_frames : 3ll * cfg->max_frames * cfg->max_clips;
+    stack_receptive_field(st, &v->rf_left, &v->rf_right);
+    (void)hipGetDevice(&v->device);
+
+    // ---- pack parameters (offsets first, device pointers after the upload)
+    Arena ar;
+    struct Pending { ConvLayer* L; size_t w, bias; SnakeOff in, outp; bool has_in, has_out; };
+    std::vector<Pending> pend;
+    v->blocks.resize(st.strides.size());
+    for (size_t l = 0; l < st.strides.size(); ++l) v->blocks[l].res.resize(st.dilations.size());
+
+    const float* w = host_weights;
+    int cin = st.c0;
+    long long per_frame = st.c0, rate = 1;
+    for (size_t l = 0; l < st.strides.size(); ++l) {
+        const int s = st.strides[l], c = st.widths[l];
+        Block& B = v->blocks[l];
+        {
+            ConvLayer& L = B.up;
+            L.cin = cin; L.cout = c; L.ntaps = 2; L.stride = s;
+            if (bf) {
+                L.variant = choose_variant_bf16(cin, s * c);
+                if (L.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for a %d -> %d stride-%d upsampling", cin, c, s);
+            }
+            L.split_in = bf && c >= kSplitWidth;
+            Pending p{&L, 0, 0, {}, {}, true, false};
+            p.in = pack_snake(ar, w, w + cin, cin, bf);  w += 2 * cin;
+            p.w = pack_conv(ar, w, L, bf);               w += (size_t)cin * c * 2 * s;
+            p.bias = pack_floats(ar, w, c);              w += c;
+            pend.push_back(p);
+        }
+        for (size_t j = 0; j < st.dilations.size(); ++j) {
+            ResUnit& U = B.res[j];
+            ConvLayer& D = U.dilated;
+            D.cin = c; D.cout = c; D.ntaps = st.res_kernel; D.dil = st.dilations[j];
+            ConvLayer& P = U.pointwise;
+            P.cin = c; P.cout = c; P.ntaps = 1; P.dil = 1;
+            if (bf) {
+                D.variant = P.variant = choose_variant_bf16(c, c);
+                if (D.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for %d channels", c);
+            }
+            D.split_out = P.split_in = bf && c >= kSplitWidth;
+            Pending pd{&D, 0, 0, {}, {}, true, true};
+            pd.in = pack_snake(ar, w, w + c, c, bf);     w += 2 * c;
+            pd.w = pack_conv(ar, w, D, bf);              w += (size_t)c * c * st.res_kernel;
+            pd.bias = pack_floats(ar, w, c);             w += c;
+            pd.outp = pack_snake(ar, w, w + c, c, bf);   w += 2 * c;      // Snake between the two convolutions
+            Pending pp{&P, 0, 0, {}, {}, false, false};
+            pp.w = pack_conv(ar, w, P, bf);              w += (size_t)c * c;
+            pp.bias = pack_floats(ar, w, c);             w += c;
+            pend.push_back(pd);
+            pend.push_back(pp);
+        }
+        cin = c;
+        rate *= s;
+        per_frame = std::max(per_frame, rate * c);
+    }
+    // head: weights as [tap][cin][out_channel] fp32
+    const SnakeOff hs = pack_snake(ar, w, w + cin, cin, bf);  w += 2 * cin;
+    const int oc = st.out_channels, hk = st.head_kernel;
+    const size_t hw = ar.reserve(sizeof(float) * (size_t)hk * cin * oc);
+    {
+        float* dst = reinterpret_cast<float*>(ar.bytes.data() + hw);
+        for (int o = 0; o < oc; ++o)
+            for (int i = 0; i < cin; ++i)
+                for (int t = 0; t < hk; ++t) {
+                    float val = w[((size_t)o * cin + i) * hk + t];
+                    if (bf) { const uint32_t u = (uint32_t)f32_to_bf16_rne(val) << 16; memcpy(&val, &u, 4); }
+                    dst[((size_t)t * cin + i) * oc + o] = val;
+                }
+    }
+    w += (size_t)oc * cin * hk;
+    const size_t hb = pack_floats(ar, w, oc);
+    w += oc;
+    v->head_cin = cin;
+
+    // ---- device memory
+    const size_t act_elems = (size_t)v->cap_frames * (size_t)per_frame;
+    v->act_elems = act_elems;
+    const size_t head_bytes = (size_t)v->cap_frames * (size_t)rate * oc * sizeof(float);
+    auto cleanup = [&]() {
+        if (v->d_params) (void)hipFree(v->d_params);
+        for (void* b : v->buf) if (b) (void)hipFree(b);
+        if (v->head_out) (void)hipFree(v->head_out);
+        if (v->d_slot_arena) (void)hipFree(v->d_slot_arena);
+    };
+    hipError_t e = hipMalloc(&v->d_params, ar.bytes.size());
+    for (int i = 0; e == hipSuccess && i < 3; ++i) e = hipMalloc(&v->buf[i], act_elems * 4);   // buf[2] (bf16): hi and lo planes
+    if (e == hipSuccess) e = hipMalloc((void**)&v->head_out, head_bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&v->d_slot_arena, sizeof(Slot) * kMaxSlots * kPlanCache);
+    if (e == hipSuccess) e = hipMemcpy(v->d_params, ar.bytes.data(), ar.bytes.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { cleanup(); return hip_fail(e, "allocating decoder memory"); }
+
+    const unsigned char* base = static_cast<const unsigned char*>(v->d_params);
+    auto fptr = [&](size_t off) { return reinterpret_cast<const float*>(base + off); };
+    for (const Pending& p : pend) {
+        p.L->w = base + p.w;
+        p.L->bias = fptr(p.bias);
+        if (p.has_in) { p.L->in_alpha = fptr(p.in.alpha); p.L->in_inv_beta = fptr(p.in.inv_beta); }
+        if (p.has_out) { p.L->out_alpha = fptr(p.outp.alpha); p.L->out_inv_beta = fptr(p.outp.inv_beta); }
+    }
+    v->head_alpha = fptr(hs.alpha); v->head_inv_beta = fptr(hs.inv_beta);
+    v->head_w = fptr(hw); v->head_bias = fptr(hb);
+
+    *out = v.release();
+    return DEMON_OK;
+}
+
+void demon_vae_destroy(demon_vae* v)
+{
+    if (!v) return;
+    (void)hipFree(v->d_params);
+    for (void* b : v->buf) if (b) (void)hipFree(b);
+    (void)hipFree(v->head_out);
+    (void)hipFree(v->d_slot_arena);
+    delete v;
+}
+
+demon_status demon_vae_receptive_field(const demon_vae* v, int* halo_left, int* halo_right)
+{
+    if (!v || !halo_left || !halo_right) return fail(DEMON_ERR_INVALID_ARG, "NULL argument");
+    *halo_left = v->rf_left; *halo_right = v->rf_right;
+    return DEMON_OK;
+}
+
+demon_status demon_vae_decode_windowed(demon_vae* v, const void* d_latent, int n_clips, int n_frames,
+                                       int frame_begin, int frame_end, int window, int halo,
+                                       float* d_out, void* stream)
+{
+    clear_error();
+    if (!v || !d_latent || !d_out) return fail(DEMON_ERR_INVALID_ARG, "NULL argument");
+    if (n_clips < 1) return fail(DEMON_ERR_INVALID_ARG, "n_clips must be >= 1");
+    if (n_frames < 1) return fail(DEMON_ERR_INVALID_ARG, "n_frames must be >= 1");
+    if (frame_begin < 0) return fail(DEMON_ERR_INVALID_ARG, "frame_begin must be >= 0");
+    if (frame_end > n_frames) return fail(DEMON_ERR_INVALID_ARG, "frame_end %d exceeds n_frames %d", frame_end, n_frames);
+    if (frame_begin >= frame_end) return fail(DEMON_ERR_INVALID_ARG, "empty frame range [%d, %d)", frame_begin, frame_end);
+    if (window < 1) return fail(DEMON_ERR_INVALID_ARG, "window must be >= 1");
+    if (halo < -1) return fail(DEMON_ERR_INVALID_ARG, "halo must be >= -1");
+    if (n_frames > v->max_frames) return fail(DEMON_ERR_WORKSPACE, "n_frames %d exceeds max_frames %d", n_frames, v->max_frames);
+    if (n_clips > v->max_clips) return fail(DEMON_ERR_WORKSPACE, "n_clips %d exceeds max_clips %d", n_clips, v->max_clips);
+    if (halo == -1) halo = std::max(v->rf_left, v->rf_right);
+    return run_decode(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, d_out, (hipStream_t)stream);
+}
+
+demon_status demon_vae_decode(demon_vae* v, const void* d_latent, int n_clips, int n_frames, float* d_out, void* stream)
+{
+    // one window per clip covering [0, n_frames), no halo: the same kernels as the windowed decode
+    return demon_vae_decode_windowed(v, d_latent, n_clips, n_frames, 0, n_frames, n_frames > 0 ? n_frames : 1, 0, d_out, stream);
+}
+
+demon_status demon_vae_debug_tap(demon_vae* v, int layer, float* d_dst, size_t capacity)
+{
+    if (!v) return fail(DEMON_ERR_INVALID_ARG, "NULL handle");
+    if (layer >= 0 && !d_dst) return fail(DEMON_ERR_INVALID_ARG, "d_dst is NULL");
+    v->tap_layer = layer; v->tap_dst = d_dst; v->tap_cap = capacity;
+    return DEMON_OK;
+}
+
+}  // extern "C"

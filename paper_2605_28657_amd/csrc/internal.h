@@ -1,0 +1,103 @@
+// Internal declarations shared by the host code and the kernel launchers of libdemon_vae.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/demon_vae.h"
+
+namespace demon {
+
+// ---- error reporting -------------------------------------------------------------------------
+demon_status fail(demon_status st, const char* fmt, ...);   // records the thread-local message
+void clear_error();
+
+// ---- layer stack (host) ----------------------------------------------------------------------
+struct Stack {
+    int c0 = 0;
+    std::vector<int> strides, widths, dilations;
+    int res_kernel = 7, head_kernel = 7, out_channels = 2;
+    int total_stride() const { int s = 1; for (int v : strides) s *= v; return s; }
+};
+
+// Validates the description and copies it. Returns DEMON_OK or INVALID_ARG (message recorded).
+demon_status stack_from_config(const demon_vae_config* cfg, Stack* out);
+size_t stack_weight_count(const Stack& st);
+void stack_receptive_field(const Stack& st, int* left, int* right);
+void stack_forward_support(const Stack& st, long long a, long long b, long long* lo, long long* hi);
+
+// ---- windows ---------------------------------------------------------------------------------
+// One extended window ("slot") as the kernels see it.  Frames are latent frames; at a level with
+// R samples per frame the slot owns workspace rows [row0*R, (row0+len)*R).
+struct Slot {
+    int row0;     // first workspace frame of the slot (prefix sum of len)
+    int len;      // extended length hi - lo
+    int clip;
+    int lo;       // first latent frame of the extended region
+    int crop;     // begin - lo: frames trimmed on the left
+    int n_int;    // end - begin: interior frames
+    int begin;    // interior start (absolute frame)
+    int pad;
+};
+
+// ---- kernels (launchers; all asynchronous on `stream`) -----------------------------------------
+// Activations live in "row-major time x channels" layout: element (row, c) at row*C + c.
+
+struct ConvArgs {
+    const void* x;        // input activation [rows_in, cin]
+    void* y;              // output activation [rows_out, cout]
+    const void* res;      // residual (same layout as y) or nullptr
+    const void* w;        // packed weights (layout private to each kernel family)
+    const float* bias;    // [cout]
+    const float* in_alpha;   const float* in_inv_beta;    // Snake on the input, or nullptr
+    const float* out_alpha;  const float* out_inv_beta;   // Snake on the output, or nullptr
+    const Slot* slots;    // device
+    int n_slots;
+    int max_len;          // longest slot (frames)
+    int r_in;             // samples per frame of the input level
+    int cin, cout;
+    int ntaps;            // conv: kernel size; convT: 2
+    int dil;              // conv: dilation; convT: unused
+    int stride;           // 0 = Conv1d; s > 0 = ConvTranspose1d(kernel 2s, stride s, padding s/2)
+    // bf16 path only: operands carried as hi + lo bf16 pairs (see kernels_bf16.hip)
+    bool split_in = false, split_out = false;
+    long long in_lo_off = 0, out_lo_off = 0;
+};
+
+hipError_t launch_conv_f32(const ConvArgs& a, hipStream_t stream);   // in_alpha must be nullptr (see launch_snake_f32)
+hipError_t launch_snake_f32(const float* x, float* y, const float* alpha, const float* inv_beta, int C,
+                            size_t n, hipStream_t stream);
+// bf16 MFMA implicit GEMM.  `variant` is the tile configuration chosen when the weights were packed.
+hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream);
+
+// Packed weight sizes / packing (host).  w_src is the PyTorch layout: conv [cout, cin, k]; convT [cin, cout, 2s].
+size_t packed_f32_count(int cin, int cout, int ntaps, int stride);
+void pack_f32(const float* w_src, int cin, int cout, int ntaps, int stride, float* dst);
+int  choose_variant_bf16(int cin, int m);                 // -1 if unsupported
+size_t packed_bf16_count(int cin, int cout, int ntaps, int stride, int variant);
+void pack_bf16(const float* w_src, int cin, int cout, int ntaps, int stride, int variant, uint16_t* dst);
+uint16_t f32_to_bf16_rne(float v);
+
+struct IoArgs {
+    const Slot* slots; int n_slots; int max_len;
+};
+// latent [n_clips, c0, n_frames] (fp32 or bf16) -> level-0 activation [frames, c0] fp32
+hipError_t launch_gather(const void* latent, float* x0, int c0, int n_frames, bool bf16,
+                         const Slot* slots, int n_slots, int max_len, hipStream_t stream);
+// head: Snake -> Conv1d(k, cin -> oc) -> tanh; output planar fp32 [oc, total_rows]
+// `fast` selects the hardware-sine Snake (alpha given in revolutions) used by the bf16 path.
+hipError_t launch_head(const float* x, float* y, const float* w /*[k][cin][oc]*/, const float* bias,
+                       const float* alpha, const float* inv_beta, int cin, int oc, int k, int r,
+                       long long total_rows, bool fast, const Slot* slots, int n_slots, int max_len,
+                       hipStream_t stream);
+// crop + stitch: planar slot waveform -> d_out [n_clips, oc, n_frames*S]
+hipError_t launch_stitch(const float* y, float* out, int oc, int S, int n_frames, long long total_rows,
+                         const Slot* slots, int n_slots, int max_int, hipStream_t stream);
+// debug tap: activation -> fp32 copy
+hipError_t launch_to_f32(const void* x, float* dst, size_t n, bool bf16, hipStream_t stream);
+
+}  // namespace demon

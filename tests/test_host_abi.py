@@ -1,0 +1,104 @@
+"""Host logic and the C ABI without a GPU: exported symbols, receptive field, window grid, argument errors."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import demon_inputs as di
+import oracle
+import paper_2605_28657_amd as pa
+from paper_2605_28657_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "demon_vae.h")).read()
+    names = set(re.findall(r"\b(demon_vae_[a-z_]+)\s*\(", header))
+    assert {"demon_vae_create", "demon_vae_destroy", "demon_vae_decode", "demon_vae_decode_windowed",
+            "demon_vae_receptive_field", "demon_vae_rf_from_config", "demon_vae_plan_windows",
+            "demon_vae_weight_count", "demon_vae_last_error"} <= names
+    lib = pa.load_library()
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in demon_vae.h but not exported"
+
+
+def test_weight_count_matches_layout():
+    for spec in (di.TINY, di.FULL, di.DecoderSpec(8, (2, 6), (16, 8), (1, 2, 4, 8), 5, 3, 1)):
+        assert pa.demon_vae_weight_count(spec) == di.n_weights(spec)
+
+
+def test_receptive_field_matches_oracle_derivation():
+    specs = [di.TINY, di.FULL, di.DecoderSpec(4, (4, 2), (8, 6), (1, 3), 7),
+             di.DecoderSpec(4, (2, 2, 2), (8, 8, 8), (1, 2, 4), 5, 9), di.DecoderSpec(4, (10,), (8,), (), 7, 1)]
+    for spec in specs:
+        assert pa.demon_vae_rf_from_config(spec) == oracle.receptive_field(spec)
+        for a, b in ((0, 0), (3, 7)):
+            assert pa.demon_vae_forward_support(spec, a, b) == oracle.forward_interval(spec, a, b)
+    assert pa.demon_vae_rf_from_config(di.TINY) == (15, 15)
+    assert pa.demon_vae_rf_from_config(di.FULL) == (6, 6)
+
+
+@pytest.mark.parametrize("T,fb,fe,window,halo", [(1500, 0, 1500, 64, 6), (250, 0, 250, 64, 6), (6000, 1984, 2112, 64, 6),
+                                                   (50, 0, 50, 16, 15), (50, 11, 37, 8, 0), (7, 0, 7, 100, 3), (9, 4, 5, 1, 2)])
+def test_window_grid_matches_oracle(T, fb, fe, window, halo):
+    got = pa.demon_vae_plan_windows(2, T, fb, fe, window, halo)
+    want = []
+    for clip in range(2):
+        for b, e in oracle.window_grid(fb, fe, window):
+            want.append(dict(clip=clip, begin=b, end=e, lo=max(0, b - halo), hi=min(T, e + halo)))
+    assert got == want
+
+
+def test_window_counts_of_the_benchmark_shapes():
+    assert len(pa.demon_vae_plan_windows(1, 1500, 0, 1500, 64, 6)) == 24
+    assert len(pa.demon_vae_plan_windows(4, 1500, 0, 1500, 64, 6)) == 96
+    assert len(pa.demon_vae_plan_windows(1, 6000, 0, 6000, 64, 6)) == 94
+    w = pa.demon_vae_plan_windows(1, 6000, 1984, 2112, 64, 6)
+    assert [(x["begin"], x["end"], x["lo"], x["hi"]) for x in w] == [(1984, 2048, 1978, 2054), (2048, 2112, 2042, 2118)]
+
+
+@pytest.mark.parametrize("args", [(0, 10, 0, 10, 4, 1), (1, 0, 0, 1, 4, 1), (1, 10, -1, 10, 4, 1), (1, 10, 0, 11, 4, 1),
+                                  (1, 10, 5, 5, 4, 1), (1, 10, 6, 5, 4, 1), (1, 10, 0, 10, 0, 1), (1, 10, 0, 10, 4, -1)])
+def test_plan_windows_rejects_bad_arguments(args):
+    with pytest.raises(pa.DemonError) as e:
+        pa.demon_vae_plan_windows(*args)
+    assert e.value.status == pa.DEMON_ERR_INVALID_ARG and e.value.message
+
+
+def _create_status(spec, weights, dtype=pa.DEMON_F32, max_frames=8, max_clips=1):
+    try:
+        h = pa.demon_vae_create(spec, weights, dtype, max_frames, max_clips)
+    except pa.DemonError as e:
+        return e.status
+    pa.demon_vae_destroy(h)
+    return pa.DEMON_OK
+
+
+def test_create_rejects_bad_descriptions_before_touching_the_gpu():
+    good = di.make_weights(di.TINY)
+    bad_specs = [di.DecoderSpec(16, (4, 3), (128, 64)),               # odd stride
+                 di.DecoderSpec(16, (4,), (128,), res_kernel=6),      # even kernel
+                 di.DecoderSpec(16, (4,), (128,), head_kernel=4),
+                 di.DecoderSpec(16, (4,), (128,), dilations=(1, 0)),
+                 di.DecoderSpec(0, (4,), (128,)),
+                 di.DecoderSpec(16, (4,), (128,), out_channels=9)]
+    for spec in bad_specs:
+        assert _create_status(spec, good) == pa.DEMON_ERR_INVALID_ARG
+    assert _create_status(di.TINY, good[:-1]) == pa.DEMON_ERR_INVALID_ARG      # wrong weight count
+    assert _create_status(di.TINY, good, max_frames=0) == pa.DEMON_ERR_INVALID_ARG
+    # the bf16 kernels need 16/32-multiples
+    spec = di.DecoderSpec(16, (4,), (24,))
+    assert _create_status(spec, di.make_weights(spec), dtype=pa.DEMON_BF16) == pa.DEMON_ERR_UNSUPPORTED
+    assert "multiple" in pa.demon_vae_last_error()
+
+
+def test_null_handle_calls_return_invalid_arg():
+    lib = pa.load_library()
+    assert lib.demon_vae_decode(None, None, 1, 1, None, None) == pa.DEMON_ERR_INVALID_ARG
+    assert lib.demon_vae_decode_windowed(None, None, 1, 1, 0, 1, 1, 0, None, None) == pa.DEMON_ERR_INVALID_ARG
+    l = ctypes.c_int()
+    assert lib.demon_vae_receptive_field(None, ctypes.byref(l), ctypes.byref(l)) == pa.DEMON_ERR_INVALID_ARG
+    lib.demon_vae_destroy(None)      # ignored
