@@ -1,0 +1,162 @@
+#!/usr/bin/env python3
+"""Benchmark of the windowed VAE decode on one MI355X.
+
+One step = one windowed decode (gather -> transposed/dilated/1x1 convolutions -> head -> stitch) of the
+60 s, 48 kHz stereo workload: a 64 x 1500 latent cut into 24 windows of 64 frames plus a 6-frame halo,
+all windows in one batch.  Inputs are synthetic (seeded) and resident in HBM before the timed region.
+Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def conv_flops_per_frame(spec):
+    """Algorithmic FLOPs (2 x MAC, no halo, no tile padding) per latent frame: (convolutions, head)."""
+    cin, rate, conv = spec.latent_channels, 1, 0
+    for s, c in zip(spec.strides, spec.widths):
+        rate *= s
+        conv += rate * 2 * cin * c                                   # transposed conv: 2 taps reach each output
+        conv += rate * len(spec.dilations) * (spec.res_kernel * c * c + c * c)
+        cin = c
+    head = rate * spec.head_kernel * cin * spec.out_channels
+    return 2 * conv, 2 * head
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="full_60s_bf16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--detail", action="store_true", help="add per-launch timings (one extra instrumented step)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
+                 "(windows and clips shard without communication, see DESIGN.md)")
+
+    import numpy as np
+    import torch
+    import demon_inputs as di
+    from paper_2605_28657_amd import DemonVAE
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    wl = di.WORKLOADS[args.workload]
+    spec = wl.spec
+    dtype = "bf16" if wl.bf16 else "f32"
+    weights, lat = di.workload_inputs(wl)
+    S = spec.total_stride
+    halo = 6 if spec is di.FULL else 15
+    n_windows = wl.n_clips * -(-wl.n_frames // wl.window)
+    ext = n_windows * (wl.window + 2 * halo)
+    vae = DemonVAE(spec, weights, dtype=dtype, max_frames=wl.n_frames, max_clips=wl.n_clips,
+                   max_extended_frames=max(ext, wl.n_frames * wl.n_clips))
+    assert max(vae.receptive_field()) == halo
+    z = torch.from_numpy(lat).to("cuda:0")
+    z = z.to(torch.bfloat16).contiguous() if wl.bf16 else z.contiguous()
+    out = torch.empty((wl.n_clips, spec.out_channels, wl.n_frames * S), dtype=torch.float32, device="cuda:0")
+
+    def step():
+        vae.decode_windowed(z, window=wl.window, halo=-1, out=out)
+
+    # group-level HIP events (5 per step, on the decode stream) stay on during the timed region
+    vae.set_timing(1)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    vae.get_timing()                                   # drop the warm-up steps from the event average
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    groups = np.array(vae.get_timing())                # average over the timed steps (the last 32 at most)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    audio_s = wl.n_clips * wl.n_frames / 25.0
+
+    conv_f, head_f = conv_flops_per_frame(spec)
+    frames = wl.n_clips * wl.n_frames
+    n_conv_launches = sum(1 + 2 * len(spec.dilations) for _ in spec.strides)
+    conv_ms = float(groups[1])
+    achieved = conv_f * frames / (conv_ms * 1e-3) / 1e12
+    result = {
+        "metric": "audio_seconds_decoded_per_second",
+        "value": audio_s / (ms_per_step * 1e-3),
+        "unit": "audio-s/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "ms_per_60s_clip": ms_per_step * 60.0 / audio_s,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "latent": [wl.n_clips, spec.latent_channels, wl.n_frames],
+                   "window": wl.window, "halo": halo, "n_windows": n_windows,
+                   "strides": list(spec.strides), "widths": list(spec.widths)},
+        "roofline": {
+            "kernel": "conv_mfma_kernel (all %d convolution launches of a step)" % n_conv_launches,
+            "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+            "flop_per_launch": conv_f * frames / n_conv_launches,
+            "avg_launch_ms": conv_ms / n_conv_launches,
+        },
+        "stage_ms": {"gather": float(groups[0]), "convolutions": conv_ms, "head": float(groups[2]),
+                     "stitch": float(groups[3])},
+    }
+    # HBM-bound kernels: algorithmic bytes = what must be read plus what must be written
+    ext_rows = ext * S
+    head_bytes = ext_rows * spec.widths[-1] * 4 + ext_rows * spec.out_channels * 4
+    stitch_bytes = 2 * frames * S * spec.out_channels * 4
+    result["hbm_kernels"] = {
+        "head": {"GB/s": head_bytes / (groups[2] * 1e-3) / 1e9, "frac": head_bytes / (groups[2] * 1e-3) / 1e9 / PEAK_HBM_GBS},
+        "stitch": {"GB/s": stitch_bytes / (groups[3] * 1e-3) / 1e9, "frac": stitch_bytes / (groups[3] * 1e-3) / 1e9 / PEAK_HBM_GBS},
+    }
+
+    if args.detail:
+        vae.set_timing(2)
+        step()
+        torch.cuda.synchronize()
+        t = vae.get_timing()
+        names = ["gather"]
+        for l in range(len(spec.strides)):
+            names.append(f"b{l}.up")
+            for j in range(len(spec.dilations)):
+                names += [f"b{l}.r{j}.conv{spec.res_kernel}", f"b{l}.r{j}.conv1"]
+        names += ["head", "stitch"]
+        result["launch_ms"] = dict(zip(names, [round(x, 4) for x in t]))
+    vae.set_timing(0)
+
+    if not args.no_cpu_baseline:
+        # The oracle (fp32 build, as it stands) on a bounded sample: the first windows with their halo.
+        import oracle
+        e = min(8 * wl.window, wl.n_frames)
+        hi = min(wl.n_frames, e + halo)
+        zs = lat[0][:, :hi]
+        c0 = time.perf_counter()
+        ref = oracle.decode(spec, weights, zs, dtype=np.float32)
+        c1 = time.perf_counter()
+        g = out[0, :, :e * S].cpu().numpy()
+        err = float(np.abs(g - ref[:, :e * S]).max())
+        result["cpu_baseline"] = {
+            "value": (hi / 25.0) / (c1 - c0), "unit": "audio-s/s", "cores": oracle.omp_threads(), "kind": "oracle",
+            "sample": f"fp32 oracle, full decode of the first 8 windows with the halo (latent frames 0..{hi - 1}, "
+                      f"{hi / 25.0:.2f} s of audio) in {c1 - c0:.2f} s",
+            "gpu_vs_oracle_max_abs_on_sample": err,
+        }
+    vae.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -163,6 +163,23 @@ demon_status demon_vae_decode_windowed(demon_vae* vae, const void* d_latent, int
  */
 demon_status demon_vae_debug_tap(demon_vae* vae, int layer, float* d_dst, size_t capacity);
 
+/*
+ * Benchmark instrumentation.  level 0 = off (default); 1 = HIP events on the decode stream at the
+ * boundaries gather | convolutions | head | stitch; 2 = an event after every kernel launch.  The
+ * events are created here, not in the decode calls.
+ */
+demon_status demon_vae_set_timing(demon_vae* vae, int level);
+
+/*
+ * Elapsed milliseconds between consecutive events, averaged over the decode calls made since the last
+ * demon_vae_set_timing / demon_vae_get_timing (at most the last 32; all of them must have had the same
+ * layer count); the caller must have synchronised the stream.  Level 1 yields 4 values (gather, all convolutions, head, stitch); level 2
+ * yields one value per launch in launch order (gather, then per block the transposed conv and per
+ * residual unit the dilated and the 1x1 conv, then head, stitch).  Writes at most `capacity` values
+ * to `ms` (host memory) and the number available to *n.
+ */
+demon_status demon_vae_get_timing(demon_vae* vae, float* ms, int capacity, int* n);
+
 /* Message of the last error returned on this thread (empty string if none). Never NULL. */
 const char* demon_vae_last_error(void);
 

@@ -3,5 +3,6 @@ from .binding import (DemonVAE, DemonError, load_library, demon_vae_create, demo
                       demon_vae_decode, demon_vae_decode_windowed, demon_vae_receptive_field,
                       demon_vae_rf_from_config, demon_vae_forward_support, demon_vae_plan_windows,
                       demon_vae_weight_count, demon_vae_debug_tap, demon_vae_last_error,
+                      demon_vae_set_timing, demon_vae_get_timing,
                       DEMON_OK, DEMON_ERR_INVALID_ARG, DEMON_ERR_UNSUPPORTED, DEMON_ERR_WORKSPACE, DEMON_ERR_HIP,
                       DEMON_F32, DEMON_BF16)

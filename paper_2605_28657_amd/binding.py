@@ -66,6 +66,8 @@ def load_library() -> ctypes.CDLL:
     lib.demon_vae_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     lib.demon_vae_decode_windowed.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 6 + [ctypes.c_void_p, ctypes.c_void_p]
     lib.demon_vae_debug_tap.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t]
+    lib.demon_vae_set_timing.argtypes = [ctypes.c_void_p, ctypes.c_int]
+    lib.demon_vae_get_timing.argtypes = [ctypes.c_void_p, P(ctypes.c_float), ctypes.c_int, P(ctypes.c_int)]
     lib.demon_vae_last_error.restype = ctypes.c_char_p
     lib.demon_vae_last_error.argtypes = []
     _lib = lib
@@ -168,6 +170,19 @@ def demon_vae_debug_tap(handle: int, layer: int, d_dst: int, capacity: int):
     _check(load_library().demon_vae_debug_tap(handle, layer, d_dst, capacity))
 
 
+def demon_vae_set_timing(handle: int, level: int):
+    _check(load_library().demon_vae_set_timing(handle, level))
+
+
+def demon_vae_get_timing(handle: int) -> List[float]:
+    lib = load_library()
+    n = ctypes.c_int()
+    _check(lib.demon_vae_get_timing(handle, None, 0, ctypes.byref(n)))
+    arr = (ctypes.c_float * max(n.value, 1))()
+    _check(lib.demon_vae_get_timing(handle, arr, n.value, ctypes.byref(n)))
+    return [float(x) for x in arr[:n.value]]
+
+
 class DemonVAE:
     """Convenience wrapper: owns a handle, marshals torch tensors.  No arithmetic happens here."""
 
@@ -226,6 +241,12 @@ class DemonVAE:
         demon_vae_decode_windowed(self.handle, latent.data_ptr(), n_clips, t, frame_begin, frame_end, window, halo,
                                   out.data_ptr(), stream)
         return out
+
+    def set_timing(self, level: int):
+        demon_vae_set_timing(self.handle, level)
+
+    def get_timing(self) -> List[float]:
+        return demon_vae_get_timing(self.handle)
 
     def tap(self, layer: int, dst=None):
         demon_vae_debug_tap(self.handle, layer, dst.data_ptr() if dst is not None else 0,

@@ -15,6 +15,7 @@ namespace {
 
 constexpr int kMaxSlots = 4096;
 constexpr int kPlanCache = 8;
+constexpr int kTimingRing = 32;        // decode calls whose events are kept for demon_vae_get_timing
 // bf16 path: blocks at least this wide carry the inputs of their transposed conv and of their 1x1
 // convs as hi + lo bf16 pairs.  There the branch gain (weight std x sqrt(fan-in)) is about one, so
 // operand rounding passes into the output at full strength, while the extra MFMA work is small
@@ -66,6 +67,12 @@ struct demon_vae {
     Slot* d_slot_arena = nullptr;
     Plan plans[kPlanCache];
     unsigned long long use_counter = 0;
+
+    int timing = 0;                    // 0 off, 1 group boundaries, 2 every launch
+    std::vector<hipEvent_t> events;    // kTimingRing sets of marks_per_call events
+    int marks_per_call = 0;
+    int n_marks = 0;                   // marks recorded by the current/last call
+    int timed_calls = 0;               // calls recorded since the last set_timing / get_timing
 
     int tap_layer = -1;
     float* tap_dst = nullptr;
@@ -205,9 +212,20 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
     const Slot* slots = plan->d_slots;
     const int ns = plan->n_slots, ml = plan->max_len;
 
+    v->n_marks = 0;
+    const int ring_base = (v->timed_calls % kTimingRing) * v->marks_per_call;
+    auto mark = [&](int level) -> hipError_t {
+        if (v->timing < level || v->n_marks >= v->marks_per_call) return hipSuccess;
+        return hipEventRecord(v->events[ring_base + v->n_marks++], stream);
+    };
+    // level 1 marks: start, after gather, after the last convolution, after head, after stitch.
+    // level 2 adds a mark after every convolution launch.
+    HIP_TRY(mark(1), "event");
+
     void* cur = v->buf[0];
     void* other = v->buf[1];
     HIP_TRY(launch_gather(d_latent, (float*)cur, v->st.c0, n_frames, bf, slots, ns, ml, stream), "gather");
+    HIP_TRY(mark(1), "event");
 
     int r = 1, layer_id = 0;
     auto conv_args = [&](const ConvLayer& L, const void* x, void* y, const void* res) {
@@ -241,22 +259,32 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
         return launch_conv_f32(a, stream);
     };
 
-    for (const Block& B : v->blocks) {
+    const size_t n_blocks = v->blocks.size();
+    for (size_t bi = 0; bi < n_blocks; ++bi) {
+        const Block& B = v->blocks[bi];
+        const bool last_block = bi + 1 == n_blocks;
         HIP_TRY(run_conv(B.up, cur, other, nullptr), "transposed convolution");
+        HIP_TRY(mark(last_block && B.res.empty() ? 1 : 2), "event");
         std::swap(cur, other);
         r *= B.up.stride;
         HIP_TRY(tap(cur, B.up.cout), "debug tap");
         void* mid = bf ? v->buf[2] : other;
-        for (const ResUnit& U : B.res) {
+        for (size_t ui = 0; ui < B.res.size(); ++ui) {
+            const ResUnit& U = B.res[ui];
             HIP_TRY(run_conv(U.dilated, cur, mid, nullptr), "dilated convolution");
+            HIP_TRY(mark(2), "event");
             HIP_TRY(run_conv(U.pointwise, mid, cur, cur), "pointwise convolution");   // in place on the residual stream
+            HIP_TRY(mark(last_block && ui + 1 == B.res.size() ? 1 : 2), "event");
             HIP_TRY(tap(cur, U.pointwise.cout), "debug tap");
         }
     }
     const long long total_rows = plan->total_frames * r;
     HIP_TRY(launch_head((const float*)cur, v->head_out, v->head_w, v->head_bias, v->head_alpha, v->head_inv_beta, v->head_cin,
                         v->st.out_channels, v->st.head_kernel, r, total_rows, bf, slots, ns, ml, stream), "head");
+    HIP_TRY(mark(1), "event");
     HIP_TRY(launch_stitch(v->head_out, d_out, v->st.out_channels, r, n_frames, total_rows, slots, ns, plan->max_int, stream), "stitch");
+    HIP_TRY(mark(1), "event");
+    if (v->timing > 0) ++v->timed_calls;
     return DEMON_OK;
 }
 
@@ -411,6 +439,7 @@ void demon_vae_destroy(demon_vae* v)
     for (void* b : v->buf) if (b) (void)hipFree(b);
     (void)hipFree(v->head_out);
     (void)hipFree(v->d_slot_arena);
+    for (hipEvent_t e : v->events) (void)hipEventDestroy(e);
     delete v;
 }
 
@@ -444,6 +473,47 @@ demon_status demon_vae_decode(demon_vae* v, const void* d_latent, int n_clips, i
 {
     // one window per clip covering [0, n_frames), no halo: the same kernels as the windowed decode
     return demon_vae_decode_windowed(v, d_latent, n_clips, n_frames, 0, n_frames, n_frames > 0 ? n_frames : 1, 0, d_out, stream);
+}
+
+demon_status demon_vae_set_timing(demon_vae* v, int level)
+{
+    if (!v) return fail(DEMON_ERR_INVALID_ARG, "NULL handle");
+    if (level < 0 || level > 2) return fail(DEMON_ERR_INVALID_ARG, "timing level must be 0, 1 or 2");
+    size_t launches = 3;                                    // gather, head, stitch
+    for (const Block& B : v->blocks) launches += 1 + 2 * B.res.size();
+    v->marks_per_call = (int)launches + 1;
+    while (level > 0 && v->events.size() < (size_t)v->marks_per_call * kTimingRing) {
+        hipEvent_t e;
+        hipError_t rc = hipEventCreate(&e);
+        if (rc != hipSuccess) return hip_fail(rc, "hipEventCreate");
+        v->events.push_back(e);
+    }
+    v->timing = level;
+    v->n_marks = 0;
+    v->timed_calls = 0;
+    return DEMON_OK;
+}
+
+demon_status demon_vae_get_timing(demon_vae* v, float* ms, int capacity, int* n)
+{
+    if (!v || !n) return fail(DEMON_ERR_INVALID_ARG, "NULL argument");
+    const int avail = v->n_marks > 0 ? v->n_marks - 1 : 0;
+    *n = avail;
+    const int calls = v->timed_calls < kTimingRing ? v->timed_calls : kTimingRing;
+    if (!ms || calls == 0) return DEMON_OK;
+    for (int i = 0; i < avail && i < capacity; ++i) {
+        double sum = 0;
+        for (int c = 0; c < calls; ++c) {
+            float t = 0;
+            const int base = c * v->marks_per_call;
+            hipError_t rc = hipEventElapsedTime(&t, v->events[base + i], v->events[base + i + 1]);
+            if (rc != hipSuccess) return hip_fail(rc, "hipEventElapsedTime");
+            sum += t;
+        }
+        ms[i] = (float)(sum / calls);
+    }
+    v->timed_calls = 0;
+    return DEMON_OK;
 }
 
 demon_status demon_vae_debug_tap(demon_vae* v, int layer, float* d_dst, size_t capacity)
