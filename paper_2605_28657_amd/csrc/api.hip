@@ -25,6 +25,7 @@ constexpr int kSplitWidth = 512;
 struct ConvLayer {
     int cin = 0, cout = 0, ntaps = 0, dil = 1, stride = 0, variant = -1;
     bool split_in = false, split_out = false;
+    int margin = 0;                    // output rows beyond the interior that later layers read
     const void* w = nullptr;
     const float* bias = nullptr;
     const float* in_alpha = nullptr;   const float* in_inv_beta = nullptr;
@@ -233,7 +234,7 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
         a.x = x; a.y = y; a.res = res; a.w = L.w; a.bias = L.bias;
         a.in_alpha = L.in_alpha; a.in_inv_beta = L.in_inv_beta;
         a.out_alpha = L.out_alpha; a.out_inv_beta = L.out_inv_beta;
-        a.slots = slots; a.n_slots = ns; a.max_len = ml; a.r_in = r;
+        a.slots = slots; a.n_slots = ns; a.max_len = ml; a.max_int = plan->max_int; a.margin = L.margin; a.r_in = r;
         a.cin = L.cin; a.cout = L.cout; a.ntaps = L.ntaps; a.dil = L.dil; a.stride = L.stride;
         a.split_in = L.split_in; a.split_out = L.split_out;
         a.in_lo_off = a.out_lo_off = (long long)v->act_elems;    // lo plane of the split branch tensor in buf[2]
@@ -280,7 +281,7 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
     }
     const long long total_rows = plan->total_frames * r;
     HIP_TRY(launch_head((const float*)cur, v->head_out, v->head_w, v->head_bias, v->head_alpha, v->head_inv_beta, v->head_cin,
-                        v->st.out_channels, v->st.head_kernel, r, total_rows, bf, slots, ns, ml, stream), "head");
+                        v->st.out_channels, v->st.head_kernel, r, total_rows, bf, slots, ns, plan->max_int, stream), "head");
     HIP_TRY(mark(1), "event");
     HIP_TRY(launch_stitch(v->head_out, d_out, v->st.out_channels, r, n_frames, total_rows, slots, ns, plan->max_int, stream), "stitch");
     HIP_TRY(mark(1), "event");
@@ -380,6 +381,22 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
         cin = c;
         rate *= s;
         per_frame = std::max(per_frame, rate * c);
+    }
+    // Rows each layer must produce beyond a window's interior (the receptive-field cone, walked from the
+    // head back to the first block): a k-tap conv of dilation d reads d(k-1)/2 rows further out than it
+    // writes; a transposed conv writing margin m reads inputs up to (m + p)/s + 1 rows out.
+    {
+        int m = (st.head_kernel - 1) / 2;
+        for (int l = (int)st.strides.size() - 1; l >= 0; --l) {
+            Block& B = v->blocks[l];
+            for (int j = (int)st.dilations.size() - 1; j >= 0; --j) {
+                B.res[j].pointwise.margin = m;
+                B.res[j].dilated.margin = m;
+                m += st.dilations[j] * ((st.res_kernel - 1) / 2);
+            }
+            B.up.margin = m;
+            m = (m + st.strides[l] / 2) / st.strides[l] + 1;
+        }
     }
     // head: weights as [tap][cin][out_channel] fp32
     const SnakeOff hs = pack_snake(ar, w, w + cin, cin, bf);  w += 2 * cin;

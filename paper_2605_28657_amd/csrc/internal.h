@@ -58,6 +58,9 @@ struct ConvArgs {
     const Slot* slots;    // device
     int n_slots;
     int max_len;          // longest slot (frames)
+    int max_int;          // longest interior (frames)
+    int margin;           // rows of the OUTPUT level beyond each window's interior that later layers still
+                          // read (the shrinking cone of the receptive field); rows further out are not computed
     int r_in;             // samples per frame of the input level
     int cin, cout;
     int ntaps;            // conv: kernel size; convT: 2
@@ -92,7 +95,7 @@ hipError_t launch_gather(const void* latent, float* x0, int c0, int n_frames, bo
 // `fast` selects the hardware-sine Snake (alpha given in revolutions) used by the bf16 path.
 hipError_t launch_head(const float* x, float* y, const float* w /*[k][cin][oc]*/, const float* bias,
                        const float* alpha, const float* inv_beta, int cin, int oc, int k, int r,
-                       long long total_rows, bool fast, const Slot* slots, int n_slots, int max_len,
+                       long long total_rows, bool fast, const Slot* slots, int n_slots, int max_int,
                        hipStream_t stream);
 // crop + stitch: planar slot waveform -> d_out [n_clips, oc, n_frames*S]
 hipError_t launch_stitch(const float* y, float* out, int oc, int S, int n_frames, long long total_rows,

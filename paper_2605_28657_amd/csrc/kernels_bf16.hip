@@ -11,6 +11,8 @@
 // chunk, halo rows included, Snake applied while staging, rows outside the window read as zero).
 // Accumulation is fp32 in a fixed order (chunk-major, then tap, then channel), independent of where
 // the tile sits in the window, so a windowed decode reproduces the full decode bit for bit.
+#include <algorithm>
+
 #include "device_common.h"
 
 namespace demon {
@@ -35,7 +37,7 @@ struct MfmaParams {
     const float* in_alpha; const float* in_inv_beta;
     const float* out_alpha; const float* out_inv_beta;
     const Slot* slots;
-    int r_in, cin, cout, ntaps, tap0, tap_step, stride, nchunks;
+    int r_in, cin, cout, ntaps, tap0, tap_step, stride, nchunks, margin;
     long long in_lo_off, out_lo_off;     // element offset of the lo plane of a split bf16 tensor
 };
 
@@ -112,8 +114,15 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams p)
 
     const Slot s = p.slots[blockIdx.y];
     const int nrows = s.len * p.r_in;                       // valid input rows of this window
-    const int ncols = (MODE == MODE_UP) ? nrows + 1 : nrows;
-    const int n0 = blockIdx.x * NT;
+    // output rows that later layers read: the interior widened by `margin`, clamped to the window
+    const int r_out = (MODE == MODE_UP) ? p.r_in * p.stride : p.r_in;
+    const int nrows_o = s.len * r_out;
+    const int out_lo = max(0, s.crop * r_out - p.margin);
+    const int out_hi = min(nrows_o, (s.crop + s.n_int) * r_out + p.margin);
+    // GEMM columns: output rows (conv) or input positions m whose s outputs m s - p .. m s - p + s - 1 touch them
+    const int col_lo = (MODE == MODE_UP) ? (out_lo + p.stride / 2) / p.stride : out_lo;
+    const int ncols = (MODE == MODE_UP) ? (out_hi - 1 + p.stride / 2) / p.stride + 1 : out_hi;
+    const int n0 = col_lo + blockIdx.x * NT;
     if (n0 >= ncols) return;
     const int m0 = blockIdx.z * MT;
     const long long rowbase = (long long)s.row0 * p.r_in;
@@ -341,7 +350,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     p.out_alpha = a.out_alpha; p.out_inv_beta = a.out_inv_beta;
     p.slots = a.slots;
     p.r_in = a.r_in; p.cin = a.cin; p.cout = a.cout; p.ntaps = a.ntaps; p.stride = a.stride;
-    p.nchunks = a.cin / v.KC;
+    p.nchunks = a.cin / v.KC; p.margin = a.margin;
     p.in_lo_off = a.in_lo_off; p.out_lo_off = a.out_lo_off;
     int mode;
     if (a.stride > 0) { p.tap0 = 0; p.tap_step = -1; mode = MODE_UP; }
@@ -352,8 +361,11 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     if (mode == MODE_ACT && (!a.in_alpha || !a.out_alpha)) return hipErrorInvalidValue;
     if (mode == MODE_UP && !a.in_alpha) return hipErrorInvalidValue;
     if (a.split_out && mode != MODE_ACT) return hipErrorInvalidValue;
-    const long long ncols = (long long)a.max_len * a.r_in + (a.stride > 0 ? 1 : 0);
-    if (ncols * (a.stride > 0 ? a.stride : 1) > 0x7fffffffll) return hipErrorInvalidValue;
+    if ((long long)a.max_len * a.r_in * (a.stride > 0 ? a.stride : 1) > 0x3fffffffll || a.margin < 0) return hipErrorInvalidValue;
+    // most columns any window needs: interior plus margins, never more than the longest window
+    const long long r_out = (long long)a.r_in * (a.stride > 0 ? a.stride : 1);
+    long long out_rows = std::min((long long)a.max_int * r_out + 2ll * a.margin, (long long)a.max_len * r_out);
+    const long long ncols = a.stride > 0 ? out_rows / a.stride + 2 : out_rows;
     dim3 grid((unsigned)((ncols + v.NT - 1) / v.NT), (unsigned)a.n_slots, (unsigned)(M / v.MT));
     switch (variant) {
         case 0: return launch_variant<128, 128, 64, 2, 2>(p, mode, a.split_in, a.split_out, grid, stream);

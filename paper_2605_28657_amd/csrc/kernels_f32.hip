@@ -2,6 +2,8 @@
 // Same layer semantics as the bf16 path (decoder layers of the benchmark description):
 //   conv  : y[n, o] = b[o] + sum_t sum_i W[o,i,t] x[n + (t - (k-1)/2) d, i]      (x = 0 outside the slot)
 //   convT : y[m s - p + phi, o] = b[o] + sum_j sum_i W[i,o,phi + j s] x[m - j, i],  j in {0,1}, p = s/2
+#include <algorithm>
+
 #include "device_common.h"
 
 namespace demon {
@@ -55,11 +57,16 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(ConvArgs a)
     const Slot s = a.slots[blockIdx.y];
     const int M = a.stride > 0 ? a.stride * a.cout : a.cout;
     const long long nrows_in = (long long)s.len * a.r_in;
-    const long long ncols = a.stride > 0 ? nrows_in + 1 : nrows_in;
+    // output rows that later layers read: the interior widened by `margin`, clamped to the window
+    const long long r_out = a.stride > 0 ? (long long)a.r_in * a.stride : a.r_in;
+    const long long out_lo = max(0ll, s.crop * r_out - a.margin);
+    const long long out_hi = min(s.len * r_out, (s.crop + s.n_int) * r_out + a.margin);
+    const long long col_lo = a.stride > 0 ? (out_lo + a.stride / 2) / a.stride : out_lo;
+    const long long col_hi = a.stride > 0 ? (out_hi - 1 + a.stride / 2) / a.stride + 1 : out_hi;
     const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (e >= ncols * M) return;
-    const long long col = e / M;
-    const int mu = (int)(e - col * M);
+    if (e >= (col_hi - col_lo) * M) return;
+    const long long col = col_lo + e / M;
+    const int mu = (int)(e % M);
     const long long rowbase_in = (long long)s.row0 * a.r_in;
     const float* __restrict__ x = (const float*)a.x;
     const float* __restrict__ w = (const float*)a.w;
@@ -94,7 +101,9 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(ConvArgs a)
 hipError_t launch_conv_f32(const ConvArgs& a, hipStream_t stream)
 {
     const long long M = a.stride > 0 ? (long long)a.stride * a.cout : a.cout;
-    const long long ncols = (long long)a.max_len * a.r_in + (a.stride > 0 ? 1 : 0);
+    const long long r_out = (long long)a.r_in * (a.stride > 0 ? a.stride : 1);
+    const long long out_rows = std::min((long long)a.max_int * r_out + 2ll * a.margin, (long long)a.max_len * r_out);
+    const long long ncols = a.stride > 0 ? out_rows / a.stride + 2 : out_rows;
     const long long blocks = (ncols * M + 255) / 256;
     if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
     hipLaunchKernelGGL(conv_f32_kernel, dim3((unsigned)blocks, (unsigned)a.n_slots), dim3(256), 0, stream, a);

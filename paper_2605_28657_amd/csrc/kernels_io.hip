@@ -37,50 +37,146 @@ hipError_t launch_gather(const void* latent, float* x0, int c0, int n_frames, bo
 }
 
 // ---------------------------------------------------------------------------------- head
-// One workgroup = 256 consecutive samples of one slot.  Channels are staged through LDS in chunks
-// of HEAD_KC (Snake applied while staging, rows outside the slot read as zero = the conv's zero
-// padding); each thread then owns one sample and all output channels.
-constexpr int HEAD_NT = 256;
-constexpr int HEAD_KC = 32;
+// Only the interior rows of every window are produced (the halo is trimmed right after).  Rows outside
+// the window read as zero (the conv's zero padding at a clip edge); Snake is applied while staging.
+//
+// Fast kernel (OC output channels, K taps as template arguments): a workgroup owns HEAD_NT = 1024
+// consecutive samples, each thread 4 of them.  Channels go through LDS in chunks of 16, transposed to
+// [channel][row] so that a thread's 4 + K - 1 input rows are consecutive words (three 16-byte reads per
+// channel for K = 7) and feed 4*K*OC FMAs; the weights are wave-uniform (scalar loads).  The row
+// length HEAD_LDR = 4 mod 16 keeps both the transposing stores and the reads free of bank conflicts.
+constexpr int HEAD_SPT = 4;                    // samples per thread
+constexpr int HEAD_NT = 256 * HEAD_SPT;
+constexpr int HEAD_KC = 16;
 constexpr int HEAD_MAXK = 15;
 constexpr int HEAD_MAXOC = 8;
+constexpr int HEAD_LDR = 1044;                 // >= HEAD_NT + HEAD_MAXK - 1, = 4 (mod 16)
 
-template <bool FAST>
-__global__ __launch_bounds__(256) void head_kernel(const float* __restrict__ x, float* __restrict__ y,
-                                                   const float* __restrict__ w, const float* __restrict__ bias,
-                                                   const float* __restrict__ alpha, const float* __restrict__ inv_beta,
-                                                   int cin, int oc, int k, int r, long long total_rows,
-                                                   const Slot* __restrict__ slots)
+template <bool FAST, int OC, int K>
+__global__ __launch_bounds__(256) void head_fast_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                        const float* __restrict__ w, const float* __restrict__ bias,
+                                                        const float* __restrict__ alpha, const float* __restrict__ inv_beta,
+                                                        int cin, int r, long long total_rows,
+                                                        const Slot* __restrict__ slots)
 {
-    __shared__ float xs[(HEAD_NT + HEAD_MAXK - 1) * (HEAD_KC + 1)];
+    __shared__ __attribute__((aligned(16))) float xs[HEAD_KC * HEAD_LDR];
+    constexpr int HALF = (K - 1) / 2;
+    constexpr int XR = HEAD_NT + K - 1;
+    constexpr int NV = (HEAD_SPT + K - 1 + 3) / 4;          // float4 reads per channel
     const Slot s = slots[blockIdx.y];
     const long long nrows = (long long)s.len * r;
-    const long long n0 = (long long)blockIdx.x * HEAD_NT;
-    if (n0 >= nrows) return;
+    const long long lo = (long long)s.crop * r, hi = (long long)(s.crop + s.n_int) * r;
+    const long long n0 = lo + (long long)blockIdx.x * HEAD_NT;
+    if (n0 >= hi) return;
+    const long long rowbase = (long long)s.row0 * r;
+    const int tid = threadIdx.x;
+    const int q = tid & 3, r0 = tid >> 2;                   // staging: 4 lanes per row, 4 channels each
+
+    float acc[HEAD_SPT][OC];
+#pragma unroll
+    for (int i = 0; i < HEAD_SPT; ++i)
+#pragma unroll
+        for (int o = 0; o < OC; ++o) acc[i][o] = 0.f;
+
+    for (int c0 = 0; c0 < cin; c0 += HEAD_KC) {
+        const float4 al = *reinterpret_cast<const float4*>(alpha + c0 + 4 * q);
+        const float4 ib = *reinterpret_cast<const float4*>(inv_beta + c0 + 4 * q);
+        __syncthreads();
+        for (int row = r0; row < XR; row += 64) {
+            const long long n = n0 - HALF + row;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (n >= 0 && n < nrows) {
+                v = *reinterpret_cast<const float4*>(x + (size_t)(rowbase + n) * cin + c0 + 4 * q);
+                if (FAST) {
+                    v.x = snake_fast(v.x, al.x, ib.x); v.y = snake_fast(v.y, al.y, ib.y);
+                    v.z = snake_fast(v.z, al.z, ib.z); v.w = snake_fast(v.w, al.w, ib.w);
+                } else {
+                    v.x = snake_precise(v.x, al.x, ib.x); v.y = snake_precise(v.y, al.y, ib.y);
+                    v.z = snake_precise(v.z, al.z, ib.z); v.w = snake_precise(v.w, al.w, ib.w);
+                }
+            }
+            xs[(4 * q + 0) * HEAD_LDR + row] = v.x;
+            xs[(4 * q + 1) * HEAD_LDR + row] = v.y;
+            xs[(4 * q + 2) * HEAD_LDR + row] = v.z;
+            xs[(4 * q + 3) * HEAD_LDR + row] = v.w;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int c = 0; c < HEAD_KC; ++c) {
+            float xv[NV * 4];
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const float4 t4 = *reinterpret_cast<const float4*>(&xs[c * HEAD_LDR + HEAD_SPT * tid + 4 * i]);
+                xv[4 * i] = t4.x; xv[4 * i + 1] = t4.y; xv[4 * i + 2] = t4.z; xv[4 * i + 3] = t4.w;
+            }
+#pragma unroll
+            for (int t = 0; t < K; ++t)
+#pragma unroll
+                for (int o = 0; o < OC; ++o) {
+                    const float wv = w[((size_t)t * cin + c0 + c) * OC + o];
+#pragma unroll
+                    for (int i = 0; i < HEAD_SPT; ++i) acc[i][o] = fmaf(wv, xv[i + t], acc[i][o]);
+                }
+        }
+    }
+    const long long n = n0 + HEAD_SPT * tid;
+#pragma unroll
+    for (int o = 0; o < OC; ++o) {
+        const float b = bias[o];
+        float* dst = y + (size_t)o * total_rows + rowbase + n;
+        if (n + HEAD_SPT <= hi && (r % 4) == 0) {
+            *reinterpret_cast<float4*>(dst) = make_float4(tanhf(acc[0][o] + b), tanhf(acc[1][o] + b),
+                                                          tanhf(acc[2][o] + b), tanhf(acc[3][o] + b));
+        } else {
+#pragma unroll
+            for (int i = 0; i < HEAD_SPT; ++i)
+                if (n + i < hi) dst[i] = tanhf(acc[i][o] + b);
+        }
+    }
+}
+
+// Generic kernel (any out_channels <= 8, any odd kernel <= 15, any channel count): one sample per
+// thread, channels staged through LDS in chunks of 32.
+constexpr int HEADG_NT = 256;
+constexpr int HEADG_KC = 32;
+
+template <bool FAST>
+__global__ __launch_bounds__(256) void head_generic_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                           const float* __restrict__ w, const float* __restrict__ bias,
+                                                           const float* __restrict__ alpha, const float* __restrict__ inv_beta,
+                                                           int cin, int oc, int k, int r, long long total_rows,
+                                                           const Slot* __restrict__ slots)
+{
+    __shared__ float xs[(HEADG_NT + HEAD_MAXK - 1) * (HEADG_KC + 1)];
+    const Slot s = slots[blockIdx.y];
+    const long long nrows = (long long)s.len * r;
+    const long long lo = (long long)s.crop * r, hi = (long long)(s.crop + s.n_int) * r;
+    const long long n0 = lo + (long long)blockIdx.x * HEADG_NT;
+    if (n0 >= hi) return;
     const long long rowbase = (long long)s.row0 * r;
     const int half = (k - 1) / 2;
-    const int xr = HEAD_NT + k - 1;
+    const int xr = HEADG_NT + k - 1;
 
     float acc[HEAD_MAXOC];
 #pragma unroll
     for (int o = 0; o < HEAD_MAXOC; ++o) acc[o] = 0.f;
 
-    for (int c0 = 0; c0 < cin; c0 += HEAD_KC) {
-        const int kc = min(HEAD_KC, cin - c0);
+    for (int c0 = 0; c0 < cin; c0 += HEADG_KC) {
+        const int kc = min(HEADG_KC, cin - c0);
         __syncthreads();
-        for (int e = threadIdx.x; e < xr * HEAD_KC; e += 256) {
-            const int row = e / HEAD_KC, c = e - row * HEAD_KC;
+        for (int e = threadIdx.x; e < xr * HEADG_KC; e += 256) {
+            const int row = e / HEADG_KC, c = e - row * HEADG_KC;
             const long long n = n0 - half + row;
             float v = 0.f;
             if (c < kc && n >= 0 && n < nrows) {
                 v = x[(size_t)(rowbase + n) * cin + c0 + c];
                 v = FAST ? snake_fast(v, alpha[c0 + c], inv_beta[c0 + c]) : snake_precise(v, alpha[c0 + c], inv_beta[c0 + c]);
             }
-            xs[row * (HEAD_KC + 1) + c] = v;
+            xs[row * (HEADG_KC + 1) + c] = v;
         }
         __syncthreads();
         for (int t = 0; t < k; ++t) {
-            const float* xrow = xs + (threadIdx.x + t) * (HEAD_KC + 1);
+            const float* xrow = xs + (threadIdx.x + t) * (HEADG_KC + 1);
             const float* wt = w + ((size_t)t * cin + c0) * oc;
             for (int c = 0; c < kc; ++c) {
                 const float v = xrow[c];
@@ -91,7 +187,7 @@ __global__ __launch_bounds__(256) void head_kernel(const float* __restrict__ x, 
         }
     }
     const long long n = n0 + threadIdx.x;
-    if (n < nrows) {
+    if (n < hi) {
 #pragma unroll
         for (int o = 0; o < HEAD_MAXOC; ++o)
             if (o < oc) y[(size_t)o * total_rows + rowbase + n] = tanhf(acc[o] + bias[o]);
@@ -100,14 +196,23 @@ __global__ __launch_bounds__(256) void head_kernel(const float* __restrict__ x, 
 
 hipError_t launch_head(const float* x, float* y, const float* w, const float* bias, const float* alpha,
                        const float* inv_beta, int cin, int oc, int k, int r, long long total_rows,
-                       bool fast, const Slot* slots, int n_slots, int max_len, hipStream_t stream)
+                       bool fast, const Slot* slots, int n_slots, int max_int, hipStream_t stream)
 {
     if (k > HEAD_MAXK || oc > HEAD_MAXOC) return hipErrorInvalidValue;
-    dim3 grid((unsigned)(((long long)max_len * r + HEAD_NT - 1) / HEAD_NT), (unsigned)n_slots);
+    const long long rows = (long long)max_int * r;
+    if (oc == 2 && k == 7 && cin % HEAD_KC == 0) {
+        dim3 grid((unsigned)((rows + HEAD_NT - 1) / HEAD_NT), (unsigned)n_slots);
+        if (fast)
+            hipLaunchKernelGGL((head_fast_kernel<true, 2, 7>), grid, dim3(256), 0, stream, x, y, w, bias, alpha, inv_beta, cin, r, total_rows, slots);
+        else
+            hipLaunchKernelGGL((head_fast_kernel<false, 2, 7>), grid, dim3(256), 0, stream, x, y, w, bias, alpha, inv_beta, cin, r, total_rows, slots);
+        return hipGetLastError();
+    }
+    dim3 grid((unsigned)((rows + HEADG_NT - 1) / HEADG_NT), (unsigned)n_slots);
     if (fast)
-        hipLaunchKernelGGL(head_kernel<true>, grid, dim3(256), 0, stream, x, y, w, bias, alpha, inv_beta, cin, oc, k, r, total_rows, slots);
+        hipLaunchKernelGGL(head_generic_kernel<true>, grid, dim3(256), 0, stream, x, y, w, bias, alpha, inv_beta, cin, oc, k, r, total_rows, slots);
     else
-        hipLaunchKernelGGL(head_kernel<false>, grid, dim3(256), 0, stream, x, y, w, bias, alpha, inv_beta, cin, oc, k, r, total_rows, slots);
+        hipLaunchKernelGGL(head_generic_kernel<false>, grid, dim3(256), 0, stream, x, y, w, bias, alpha, inv_beta, cin, oc, k, r, total_rows, slots);
     return hipGetLastError();
 }
 
