@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdemon_vae.so")
-SOURCES = ["host_plan.cpp", "api.hip", "kernels_io.hip", "kernels_f32.hip", "kernels_bf16.hip"]
+SOURCES = ["host_plan.cpp", "api.hip", "kernels_io.hip", "kernels_f32.hip", "kernels_bf16.hip", "kernels_bf16_fused.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

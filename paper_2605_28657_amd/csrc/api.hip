@@ -1,6 +1,7 @@
 // C ABI of libdemon_vae: decoder construction (weight repacking, workspace), window plans and the
 // launch sequence of the windowed decode (paper section 3.6: extend, decode, trim).
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -21,6 +22,8 @@ constexpr int kTimingRing = 32;        // decode calls whose events are kept for
 // operand rounding passes into the output at full strength, while the extra MFMA work is small
 // (these GEMMs have short K).
 constexpr int kSplitWidth = 512;
+// DEMON_VAE_NO_FUSED=1 in the environment keeps every residual unit on the two-kernel path (A/B timing).
+const bool g_allow_fused = getenv("DEMON_VAE_NO_FUSED") == nullptr;
 
 struct ConvLayer {
     int cin = 0, cout = 0, ntaps = 0, dil = 1, stride = 0, variant = -1;
@@ -32,7 +35,7 @@ struct ConvLayer {
     const float* out_alpha = nullptr;  const float* out_inv_beta = nullptr;
 };
 
-struct ResUnit { ConvLayer dilated, pointwise; };
+struct ResUnit { ConvLayer dilated, pointwise; bool fused = false; const uint16_t* w1_fused = nullptr; };
 struct Block { ConvLayer up; std::vector<ResUnit> res; };
 
 struct Plan {
@@ -272,6 +275,22 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
         void* mid = bf ? v->buf[2] : other;
         for (size_t ui = 0; ui < B.res.size(); ++ui) {
             const ResUnit& U = B.res[ui];
+            if (U.fused) {
+                FusedArgs f;
+                f.x = (const float*)cur; f.y = (float*)other;
+                f.w7 = (const uint16_t*)U.dilated.w; f.w1 = U.w1_fused;
+                f.b7 = U.dilated.bias; f.b1 = U.pointwise.bias;
+                f.a1 = U.dilated.in_alpha; f.ib1 = U.dilated.in_inv_beta;
+                f.a2 = U.dilated.out_alpha; f.ib2 = U.dilated.out_inv_beta;
+                f.slots = slots; f.n_slots = ns; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
+                f.r = r; f.c = U.dilated.cin; f.ntaps = U.dilated.ntaps; f.dil = U.dilated.dil;
+                HIP_TRY(launch_res_unit_fused(f, stream), "fused residual unit");
+                std::swap(cur, other);
+                HIP_TRY(mark(2), "event");
+                HIP_TRY(mark(last_block && ui + 1 == B.res.size() ? 1 : 2), "event");
+                HIP_TRY(tap(cur, U.pointwise.cout), "debug tap");
+                continue;
+            }
             HIP_TRY(run_conv(U.dilated, cur, mid, nullptr), "dilated convolution");
             HIP_TRY(mark(2), "event");
             HIP_TRY(run_conv(U.pointwise, mid, cur, cur), "pointwise convolution");   // in place on the residual stream
@@ -333,6 +352,8 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
     Arena ar;
     struct Pending { ConvLayer* L; size_t w, bias; SnakeOff in, outp; bool has_in, has_out; };
     std::vector<Pending> pend;
+    struct FusedFix { ResUnit* U; size_t off; };
+    std::vector<FusedFix> fused_fix;
     v->blocks.resize(st.strides.size());
     for (size_t l = 0; l < st.strides.size(); ++l) v->blocks[l].res.resize(st.dilations.size());
 
@@ -367,12 +388,19 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
                 if (D.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for %d channels", c);
             }
             D.split_out = P.split_in = bf && c >= kSplitWidth;
+            U.fused = bf && (c == 64 || c == 128) && (st.res_kernel - 1) * st.dilations[j] <= 64 && !D.split_out && g_allow_fused;
+            if (U.fused) D.variant = (c == 64) ? 1 : 0;      // weight blocks of C x 64
             Pending pd{&D, 0, 0, {}, {}, true, true};
             pd.in = pack_snake(ar, w, w + c, c, bf);     w += 2 * c;
             pd.w = pack_conv(ar, w, D, bf);              w += (size_t)c * c * st.res_kernel;
             pd.bias = pack_floats(ar, w, c);             w += c;
             pd.outp = pack_snake(ar, w, w + c, c, bf);   w += 2 * c;      // Snake between the two convolutions
             Pending pp{&P, 0, 0, {}, {}, false, false};
+            if (U.fused) {
+                const size_t off = ar.reserve((size_t)c * c * 2);
+                pack_w1_fused(w, c, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
+                fused_fix.push_back({&U, off});
+            }
             pp.w = pack_conv(ar, w, P, bf);              w += (size_t)c * c;
             pp.bias = pack_floats(ar, w, c);             w += c;
             pend.push_back(pd);
@@ -442,6 +470,7 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
         if (p.has_in) { p.L->in_alpha = fptr(p.in.alpha); p.L->in_inv_beta = fptr(p.in.inv_beta); }
         if (p.has_out) { p.L->out_alpha = fptr(p.outp.alpha); p.L->out_inv_beta = fptr(p.outp.inv_beta); }
     }
+    for (const FusedFix& f : fused_fix) f.U->w1_fused = reinterpret_cast<const uint16_t*>(base + f.off);
     v->head_alpha = fptr(hs.alpha); v->head_inv_beta = fptr(hs.inv_beta);
     v->head_w = fptr(hw); v->head_bias = fptr(hb);
 

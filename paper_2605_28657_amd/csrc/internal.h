@@ -85,6 +85,19 @@ size_t packed_bf16_count(int cin, int cout, int ntaps, int stride, int variant);
 void pack_bf16(const float* w_src, int cin, int cout, int ntaps, int stride, int variant, uint16_t* dst);
 uint16_t f32_to_bf16_rne(float v);
 
+// Fused residual unit (bf16 path, C = 64 or 128): y = x + W1 snake2(W7 (*) snake1(x) + b7) + b1, x != y.
+struct FusedArgs {
+    const float* x; float* y;
+    const uint16_t* w7;      // packed as pack_bf16 does for an MT = C, KC = 64 tile
+    const uint16_t* w1;      // packed by pack_w1_fused
+    const float* b7; const float* b1;
+    const float* a1; const float* ib1; const float* a2; const float* ib2;
+    const Slot* slots; int n_slots, max_len, max_int, margin;
+    int r, c, ntaps, dil;
+};
+hipError_t launch_res_unit_fused(const FusedArgs& a, hipStream_t stream);
+void pack_w1_fused(const float* w, int C, uint16_t* dst);
+
 struct IoArgs {
     const Slot* slots; int n_slots; int max_len;
 };
