@@ -65,8 +65,9 @@ struct demon_vae {
     int head_cin = 0;
 
     // fp32 path: residual stream ping/pong + Snake scratch, all fp32.
-    // bf16 path: buf[0], buf[1] fp32 residual stream ping/pong, buf[2] bf16 activated branch tensor.
-    void* buf[3] = {nullptr, nullptr, nullptr};
+    // bf16 path: buf[0], buf[1] fp32 residual stream ping/pong, buf[2] bf16 activated branch tensor,
+    // buf[3], buf[4] bf16 activated operand of the next layer (each bf16 buffer: hi plane + lo plane).
+    void* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     float* head_out = nullptr;                     // planar window waveforms [out_channels, cap_frames*S]
     Slot* d_slot_arena = nullptr;
     Plan plans[kPlanCache];
@@ -228,10 +229,15 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
 
     void* cur = v->buf[0];
     void* other = v->buf[1];
-    HIP_TRY(launch_gather(d_latent, (float*)cur, v->st.c0, n_frames, bf, slots, ns, ml, stream), "gather");
-    HIP_TRY(mark(1), "event");
-
     int r = 1, layer_id = 0;
+    const size_t n_blocks = v->blocks.size();
+    const long long lo_off = (long long)v->act_elems;        // lo plane of a split bf16 tensor
+    auto tap = [&](const void* x, int c) -> hipError_t {
+        const int id = layer_id++;
+        if (id != v->tap_layer || !v->tap_dst) return hipSuccess;
+        const size_t n = std::min<size_t>(v->tap_cap, (size_t)plan->total_frames * r * c);
+        return launch_to_f32(x, v->tap_dst, n, false, stream);
+    };
     auto conv_args = [&](const ConvLayer& L, const void* x, void* y, const void* res) {
         ConvArgs a;
         a.x = x; a.y = y; a.res = res; a.w = L.w; a.bias = L.bias;
@@ -240,62 +246,105 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
         a.slots = slots; a.n_slots = ns; a.max_len = ml; a.max_int = plan->max_int; a.margin = L.margin; a.r_in = r;
         a.cin = L.cin; a.cout = L.cout; a.ntaps = L.ntaps; a.dil = L.dil; a.stride = L.stride;
         a.split_in = L.split_in; a.split_out = L.split_out;
-        a.in_lo_off = a.out_lo_off = (long long)v->act_elems;    // lo plane of the split branch tensor in buf[2]
+        a.in_lo_off = a.out_lo_off = lo_off;
         return a;
     };
-    auto tap = [&](const void* x, int c) -> hipError_t {
-        const int id = layer_id++;
-        if (id != v->tap_layer || !v->tap_dst) return hipSuccess;
-        const size_t n = std::min<size_t>(v->tap_cap, (size_t)plan->total_frames * r * c);
-        return launch_to_f32(x, v->tap_dst, n, false, stream);
-    };
-    // fp32 path: Snake on a layer's input runs as its own kernel into buf[2]
-    auto run_conv = [&](const ConvLayer& L, const void* x, void* y, const void* res) -> hipError_t {
-        if (bf) return launch_conv_bf16(conv_args(L, x, y, res), L.variant, stream);
-        ConvArgs a = conv_args(L, x, y, res);
-        if (L.in_alpha) {
-            hipError_t e = launch_snake_f32((const float*)x, (float*)v->buf[2], L.in_alpha, L.in_inv_beta, L.cin,
-                                            (size_t)plan->total_frames * r * L.cin, stream);
-            if (e != hipSuccess) return e;
-            a.x = v->buf[2];
-            a.in_alpha = a.in_inv_beta = nullptr;
-        }
-        return launch_conv_f32(a, stream);
-    };
 
-    const size_t n_blocks = v->blocks.size();
-    for (size_t bi = 0; bi < n_blocks; ++bi) {
-        const Block& B = v->blocks[bi];
-        const bool last_block = bi + 1 == n_blocks;
-        HIP_TRY(run_conv(B.up, cur, other, nullptr), "transposed convolution");
-        HIP_TRY(mark(last_block && B.res.empty() ? 1 : 2), "event");
-        std::swap(cur, other);
-        r *= B.up.stride;
-        HIP_TRY(tap(cur, B.up.cout), "debug tap");
-        void* mid = bf ? v->buf[2] : other;
-        for (size_t ui = 0; ui < B.res.size(); ++ui) {
-            const ResUnit& U = B.res[ui];
-            if (U.fused) {
-                FusedArgs f;
-                f.x = (const float*)cur; f.y = (float*)other;
-                f.w7 = (const uint16_t*)U.dilated.w; f.w1 = U.w1_fused;
-                f.b7 = U.dilated.bias; f.b1 = U.pointwise.bias;
-                f.a1 = U.dilated.in_alpha; f.ib1 = U.dilated.in_inv_beta;
-                f.a2 = U.dilated.out_alpha; f.ib2 = U.dilated.out_inv_beta;
-                f.slots = slots; f.n_slots = ns; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
-                f.r = r; f.c = U.dilated.cin; f.ntaps = U.dilated.ntaps; f.dil = U.dilated.dil;
-                HIP_TRY(launch_res_unit_fused(f, stream), "fused residual unit");
-                std::swap(cur, other);
+    if (!bf) {
+        // ---- fp32 path: Snake on a layer's input runs as its own kernel into buf[2]
+        HIP_TRY(launch_gather(d_latent, (float*)cur, v->st.c0, n_frames, false, slots, ns, ml, stream), "gather");
+        HIP_TRY(mark(1), "event");
+        auto run_conv = [&](const ConvLayer& L, const void* x, void* y, const void* res) -> hipError_t {
+            ConvArgs a = conv_args(L, x, y, res);
+            if (L.in_alpha) {
+                hipError_t e = launch_snake_f32((const float*)x, (float*)v->buf[2], L.in_alpha, L.in_inv_beta, L.cin,
+                                                (size_t)plan->total_frames * r * L.cin, stream);
+                if (e != hipSuccess) return e;
+                a.x = v->buf[2];
+                a.in_alpha = a.in_inv_beta = nullptr;
+            }
+            return launch_conv_f32(a, stream);
+        };
+        for (size_t bi = 0; bi < n_blocks; ++bi) {
+            const Block& B = v->blocks[bi];
+            const bool last_block = bi + 1 == n_blocks;
+            HIP_TRY(run_conv(B.up, cur, other, nullptr), "transposed convolution");
+            HIP_TRY(mark(last_block && B.res.empty() ? 1 : 2), "event");
+            std::swap(cur, other);
+            r *= B.up.stride;
+            HIP_TRY(tap(cur, B.up.cout), "debug tap");
+            for (size_t ui = 0; ui < B.res.size(); ++ui) {
+                const ResUnit& U = B.res[ui];
+                HIP_TRY(run_conv(U.dilated, cur, other, nullptr), "dilated convolution");
                 HIP_TRY(mark(2), "event");
+                HIP_TRY(run_conv(U.pointwise, other, cur, cur), "pointwise convolution");   // in place on the residual stream
                 HIP_TRY(mark(last_block && ui + 1 == B.res.size() ? 1 : 2), "event");
                 HIP_TRY(tap(cur, U.pointwise.cout), "debug tap");
-                continue;
             }
-            HIP_TRY(run_conv(U.dilated, cur, mid, nullptr), "dilated convolution");
-            HIP_TRY(mark(2), "event");
-            HIP_TRY(run_conv(U.pointwise, mid, cur, cur), "pointwise convolution");   // in place on the residual stream
-            HIP_TRY(mark(last_block && ui + 1 == B.res.size() ? 1 : 2), "event");
-            HIP_TRY(tap(cur, U.pointwise.cout), "debug tap");
+        }
+    } else {
+        // ---- bf16 path.  h (fp32) ping-pongs between buf[0] and buf[1]; the activated bf16 operand `a` of the
+        // next unfused layer ping-pongs between buf[3] and buf[4]; buf[2] holds the activated branch tensor
+        // between the dilated and the 1x1 conv.  Each producer writes `a` with its consumer's Snake.
+        uint16_t* acur = (uint16_t*)v->buf[3];
+        uint16_t* aoth = (uint16_t*)v->buf[4];
+        uint16_t* mid = (uint16_t*)v->buf[2];
+        // the layer that consumes the output of block bi's unit ui (ui = -1: of its transposed conv);
+        // nullptr when that layer reads the fp32 stream itself (fused unit, head)
+        auto consumer = [&](size_t bi, int ui) -> const ConvLayer* {
+            const Block& B = v->blocks[bi];
+            if (ui + 1 < (int)B.res.size()) return B.res[ui + 1].fused ? nullptr : &B.res[ui + 1].dilated;
+            return bi + 1 < n_blocks ? &v->blocks[bi + 1].up : nullptr;
+        };
+        {
+            const ConvLayer& U0 = v->blocks[0].up;
+            HIP_TRY(launch_gather(d_latent, nullptr, v->st.c0, n_frames, true, slots, ns, ml, stream, acur,
+                                  U0.split_in ? lo_off : 0, U0.in_alpha, U0.in_inv_beta), "gather");
+            HIP_TRY(mark(1), "event");
+        }
+        for (size_t bi = 0; bi < n_blocks; ++bi) {
+            const Block& B = v->blocks[bi];
+            const bool last_block = bi + 1 == n_blocks;
+            {
+                ConvArgs a = conv_args(B.up, acur, other, nullptr);
+                const ConvLayer* C = consumer(bi, -1);
+                if (C) { a.ya = aoth; a.out_alpha = C->in_alpha; a.out_inv_beta = C->in_inv_beta; a.split_out = C->split_in; }
+                HIP_TRY(launch_conv_bf16(a, B.up.variant, stream), "transposed convolution");
+                if (C) std::swap(acur, aoth);
+            }
+            HIP_TRY(mark(last_block && B.res.empty() ? 1 : 2), "event");
+            std::swap(cur, other);
+            r *= B.up.stride;
+            HIP_TRY(tap(cur, B.up.cout), "debug tap");
+            for (size_t ui = 0; ui < B.res.size(); ++ui) {
+                const ResUnit& U = B.res[ui];
+                const ConvLayer* C = consumer(bi, (int)ui);
+                if (U.fused) {
+                    FusedArgs f;
+                    f.x = (const float*)cur; f.y = (float*)other;
+                    if (C) { f.ya = acur; f.a3 = C->in_alpha; f.ib3 = C->in_inv_beta; }
+                    f.w7 = (const uint16_t*)U.dilated.w; f.w1 = U.w1_fused;
+                    f.b7 = U.dilated.bias; f.b1 = U.pointwise.bias;
+                    f.a1 = U.dilated.in_alpha; f.ib1 = U.dilated.in_inv_beta;
+                    f.a2 = U.dilated.out_alpha; f.ib2 = U.dilated.out_inv_beta;
+                    f.slots = slots; f.n_slots = ns; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
+                    f.r = r; f.c = U.dilated.cin; f.ntaps = U.dilated.ntaps; f.dil = U.dilated.dil;
+                    if (C && C->split_in) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a split-operand layer");
+                    HIP_TRY(launch_res_unit_fused(f, stream), "fused residual unit");
+                    std::swap(cur, other);
+                    HIP_TRY(mark(2), "event");
+                } else {
+                    ConvArgs d = conv_args(U.dilated, acur, nullptr, nullptr);
+                    d.ya = mid;                                   // Snake between the convolutions: the layer's own out_alpha
+                    HIP_TRY(launch_conv_bf16(d, U.dilated.variant, stream), "dilated convolution");
+                    HIP_TRY(mark(2), "event");
+                    ConvArgs q = conv_args(U.pointwise, mid, cur, cur);   // in place on the residual stream
+                    if (C) { q.ya = acur; q.out_alpha = C->in_alpha; q.out_inv_beta = C->in_inv_beta; q.split_out = C->split_in; }
+                    HIP_TRY(launch_conv_bf16(q, U.pointwise.variant, stream), "pointwise convolution");
+                }
+                HIP_TRY(mark(last_block && ui + 1 == B.res.size() ? 1 : 2), "event");
+                HIP_TRY(tap(cur, U.pointwise.cout), "debug tap");
+            }
         }
     }
     const long long total_rows = plan->total_frames * r;
@@ -456,7 +505,7 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
         if (v->d_slot_arena) (void)hipFree(v->d_slot_arena);
     };
     hipError_t e = hipMalloc(&v->d_params, ar.bytes.size());
-    for (int i = 0; e == hipSuccess && i < 3; ++i) e = hipMalloc(&v->buf[i], act_elems * 4);   // buf[2] (bf16): hi and lo planes
+    for (int i = 0; e == hipSuccess && i < (bf ? 5 : 3); ++i) e = hipMalloc(&v->buf[i], act_elems * 4);   // bf16 buffers: hi and lo planes
     if (e == hipSuccess) e = hipMalloc((void**)&v->head_out, head_bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&v->d_slot_arena, sizeof(Slot) * kMaxSlots * kPlanCache);
     if (e == hipSuccess) e = hipMemcpy(v->d_params, ar.bytes.data(), ar.bytes.size(), hipMemcpyHostToDevice);

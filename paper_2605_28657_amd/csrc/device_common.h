@@ -13,6 +13,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
@@ -33,6 +34,13 @@ __device__ __forceinline__ float snake_fast(float x, float alpha_rev, float inv_
 {
     const float s = __builtin_amdgcn_sinf(__builtin_amdgcn_fractf(alpha_rev * x));
     return fmaf(s * s, inv_beta, x);
+}
+
+// Raw buffer descriptor over [base, base + bytes): loads outside return zero, stores outside are dropped.
+// Dword 3 selects 32-bit raw addressing on gfx9-family parts.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
 
 }  // namespace demon

@@ -48,9 +48,10 @@ struct Slot {
 // Activations live in "row-major time x channels" layout: element (row, c) at row*C + c.
 
 struct ConvArgs {
-    const void* x;        // input activation [rows_in, cin]
-    void* y;              // output activation [rows_out, cout]
-    const void* res;      // residual (same layout as y) or nullptr
+    const void* x;        // input activation [rows_in, cin] (fp32 path: fp32; bf16 path: activated bf16 operand)
+    void* y;              // output activation [rows_out, cout] (fp32); bf16 dilated conv: unused
+    void* ya = nullptr;   // bf16 path: activated bf16 copy of the output for the next layer (Snake out_alpha/out_inv_beta)
+    const void* res;      // residual (same layout as y) or nullptr; bf16 path: must equal y (in place)
     const void* w;        // packed weights (layout private to each kernel family)
     const float* bias;    // [cout]
     const float* in_alpha;   const float* in_inv_beta;    // Snake on the input, or nullptr
@@ -88,6 +89,8 @@ uint16_t f32_to_bf16_rne(float v);
 // Fused residual unit (bf16 path, C = 64 or 128): y = x + W1 snake2(W7 (*) snake1(x) + b7) + b1, x != y.
 struct FusedArgs {
     const float* x; float* y;
+    uint16_t* ya = nullptr;  // optional: bf16(snake(y; a3, ib3)) for an unfused consumer
+    const float* a3 = nullptr; const float* ib3 = nullptr;
     const uint16_t* w7;      // packed as pack_bf16 does for an MT = C, KC = 64 tile
     const uint16_t* w1;      // packed by pack_w1_fused
     const float* b7; const float* b1;
@@ -101,9 +104,12 @@ void pack_w1_fused(const float* w, int C, uint16_t* dst);
 struct IoArgs {
     const Slot* slots; int n_slots; int max_len;
 };
-// latent [n_clips, c0, n_frames] (fp32 or bf16) -> level-0 activation [frames, c0] fp32
+// latent [n_clips, c0, n_frames] (fp32 or bf16) -> level-0 activation [frames, c0] fp32; with `xa` (bf16 path) the
+// activated operand bf16(snake(x; alpha, inv_beta)) instead, as hi plane and (xa_lo_off != 0) lo plane
 hipError_t launch_gather(const void* latent, float* x0, int c0, int n_frames, bool bf16,
-                         const Slot* slots, int n_slots, int max_len, hipStream_t stream);
+                         const Slot* slots, int n_slots, int max_len, hipStream_t stream,
+                         uint16_t* xa = nullptr, long long xa_lo_off = 0, const float* alpha = nullptr,
+                         const float* inv_beta = nullptr);
 // head: Snake -> Conv1d(k, cin -> oc) -> tanh; output planar fp32 [oc, total_rows]
 // `fast` selects the hardware-sine Snake (alpha given in revolutions) used by the bf16 path.
 hipError_t launch_head(const float* x, float* y, const float* w /*[k][cin][oc]*/, const float* bias,

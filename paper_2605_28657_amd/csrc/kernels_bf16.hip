@@ -6,11 +6,26 @@
 //                                     taps j in {0,1} with off_j = -j and weight W[i, o, phi + j s];
 //                                     column m, row mu lands on output sample m s - p + phi, channel o,
 //                                     i.e. on the contiguous run ((m s - p) cout + mu) of the time-major output.
-// Activations are time-major [rows, channels] bf16, so the 8 consecutive K values an MFMA lane needs
-// are 16 contiguous bytes and a tap is a row offset into the same LDS tile (staged once per channel
-// chunk, halo rows included, Snake applied while staging, rows outside the window read as zero).
-// Accumulation is fp32 in a fixed order (chunk-major, then tap, then channel), independent of where
-// the tile sits in the window, so a windowed decode reproduces the full decode bit for bit.
+//
+// Data flow.  The residual stream h is fp32 in HBM (rounding it to bf16 after every layer alone would
+// use up the error budget of the bf16 path).  MFMA operands are bf16 and are produced exactly once, by
+// the kernel that computes the value: every epilogue that writes h also writes a = bf16(snake(h)) with
+// the Snake parameters of the layer that will consume it, so the GEMM kernels stage their activation
+// operand with plain 16-byte copies (no transcendental work in the K loop, none repeated per row tile
+// or per halo).  Activations are time-major [rows, channels]: the 8 consecutive K values an MFMA lane
+// needs are 16 contiguous bytes, and a tap is a row offset into the same LDS tile.
+//
+// Split operands: where rounding an operand to bf16 costs too much accuracy (the wide, low-rate levels,
+// whose branch gain is about one), it is carried as hi + lo, hi = bf16(v), lo = bf16(v - hi), in two
+// planes, and every k-step issues two MFMAs against the same weight fragment.
+//
+// All global accesses go through buffer descriptors that cover exactly one window (rows of other
+// windows, rows before the window and rows past the part of the cone being computed are out of range:
+// loads return zero = the convolution's zero padding at a clip edge, stores are dropped), so the
+// kernel has no per-row branches and all offsets are 32-bit.
+//
+// Accumulation is fp32 in a fixed order (chunk-major, then tap, then channel), independent of where the
+// tile sits in the window, so a windowed decode reproduces the full decode bit for bit.
 #include <algorithm>
 
 #include "device_common.h"
@@ -19,26 +34,22 @@ namespace demon {
 
 constexpr int MAXSPAN = 64;    // largest (max tap offset - min tap offset) the LDS tile is sized for
 
-// The residual stream h is kept in fp32 in HBM (rounding it to bf16 after every layer alone would use
-// up the error budget of the bf16 path); only MFMA operands are bf16: Snake(h) is rounded while it is
-// staged into LDS, and the activated output of the dilated conv is stored as bf16.
-// Split operands: where the rounding of an activation operand to bf16 costs too much accuracy (the
-// wide, low-rate levels, whose branch gain is about one), the operand is carried as hi + lo with
-// hi = bf16(v), lo = bf16(v - hi), and every k-step issues two MFMAs against the same weight
-// fragment.  SPLIT_IN: the B operand is split (staged from fp32 by the kernel itself, or read as two
-// bf16 planes in MODE_RES).  SPLIT_OUT (MODE_ACT): the activated output is stored as two planes.
-enum { MODE_ACT = 0,   // fp32 in, Snake on input;  bias + Snake on output, bf16 out   (dilated conv of a residual unit)
-       MODE_RES = 1,   // bf16 in (already activated); bias + fp32 residual add, fp32 out (1x1 conv of a residual unit)
-       MODE_UP  = 2 }; // fp32 in, Snake on input;  bias, polyphase scatter, fp32 out  (ConvTranspose1d)
+enum { MODE_ACT = 0,   // bias + Snake, bf16 out only                     (dilated conv of a residual unit)
+       MODE_RES = 1,   // bias + fp32 residual add, fp32 out in place     (1x1 conv of a residual unit)
+       MODE_UP  = 2 }; // bias, polyphase scatter, fp32 out               (ConvTranspose1d)
+// MODE_RES and MODE_UP may in addition emit the activated bf16 copy for the next layer (EMIT > 0).
 
 struct MfmaParams {
-    const void* x; void* y; const float* res; const uint16_t* w;
+    const uint16_t* xa;      // activated input, bf16 [rows][cin]; lo plane at xa + in_lo_off
+    const uint16_t* w;       // packed weight blocks
     const float* bias;
-    const float* in_alpha; const float* in_inv_beta;
-    const float* out_alpha; const float* out_inv_beta;
+    float* y;                // fp32 output; MODE_RES: also the residual source (in place); unused in MODE_ACT
+    uint16_t* ya;            // bf16 activated output; lo plane at ya + out_lo_off
+    const float* out_alpha; const float* out_inv_beta;   // Snake applied before writing ya
     const Slot* slots;
     int r_in, cin, cout, ntaps, tap0, tap_step, stride, nchunks, margin;
-    long long in_lo_off, out_lo_off;     // element offset of the lo plane of a split bf16 tensor
+    unsigned w_bytes;
+    long long in_lo_off, out_lo_off;     // element offsets of the lo planes
 };
 
 struct Variant { int MT, NT, KC; };
@@ -92,7 +103,7 @@ void pack_bf16(const float* w, int cin, int cout, int ntaps, int stride, int var
                     }
 }
 
-template <int MT, int NT, int KC, int WM, int WN, int MODE, bool SPLIT_IN, bool SPLIT_OUT>
+template <int MT, int NT, int KC, int WM, int WN, int MODE, bool SPLIT_IN, int EMIT>
 __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams p)
 {
     constexpr int LDK = KC + 8;                 // padded LDS row (bf16 elements): 16-byte multiple, bank-spread
@@ -104,10 +115,9 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams p)
     constexpr int A_CH = MT * SEGS;             // 16-byte chunks of an A block
     constexpr int A_ITERS = (A_CH + 255) / 256;
     constexpr int X_ITERS = (XR_MAX + RPP - 1) / RPP;
-    constexpr bool SNAKE_IN = (MODE != MODE_RES);     // these modes read the fp32 residual stream
-    constexpr int XV = (SNAKE_IN || SPLIT_IN) ? 2 : 1; // 16-byte loads per staged 8-channel segment
-    constexpr int NP = SPLIT_IN ? 2 : 1;              // operand planes (hi, lo)
+    constexpr int NP = SPLIT_IN ? 2 : 1;        // operand planes (hi, lo)
     static_assert(WM * WN == 4, "four waves per workgroup");
+    static_assert(MODE != MODE_ACT || EMIT > 0, "the dilated conv only has the activated output");
 
     __shared__ __attribute__((aligned(16))) uint16_t As[2][MT * LDK];
     __shared__ __attribute__((aligned(16))) uint16_t Xs[NP][XR_MAX * LDK];
@@ -126,6 +136,7 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams p)
     if (n0 >= ncols) return;
     const int m0 = blockIdx.z * MT;
     const long long rowbase = (long long)s.row0 * p.r_in;
+    const long long rowbase_o = (long long)s.row0 * r_out;
 
     const int last_off = p.tap0 + (p.ntaps - 1) * p.tap_step;
     const int minoff = min(p.tap0, last_off);
@@ -137,20 +148,26 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams p)
     const int j = lane & 31, h = lane >> 5;
     const int seg = tid % SEGS, xr0 = tid / SEGS;
 
+    // ---- descriptors (uniform)
+    const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(p.w, p.w_bytes);
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.xa + rowbase * p.cin, (unsigned)nrows * p.cin * 2u);
+    const __amdgpu_buffer_rsrc_t rs_xl = make_rsrc(p.xa + p.in_lo_off + rowbase * p.cin, SPLIT_IN ? (unsigned)nrows * p.cin * 2u : 0u);
+
     const int nstages = p.nchunks * p.ntaps;
-    const u32x4* wblk = reinterpret_cast<const u32x4*>(p.w) + (size_t)blockIdx.z * nstages * (A_CH);
+    const unsigned w_tile0 = (unsigned)blockIdx.z * nstages * (A_CH * 16u);
+    const unsigned a_voff = tid * 16u;
+    const unsigned x_voff = ((unsigned)((n0 + minoff + xr0) * p.cin) + seg * 8u) * 2u;    // may wrap "negative": out of range
+    const unsigned x_row_step = (unsigned)(RPP * p.cin) * 2u;
 
     u32x4 ra[A_ITERS];
-    u32x4 rx[X_ITERS][XV];
-    float al[8], ib[8];
+    u32x4 rx[X_ITERS][NP];
 
     auto load_a = [&](int stage) __attribute__((always_inline)) {
-        const u32x4* src = wblk + (size_t)stage * A_CH;
+        const unsigned base = w_tile0 + (unsigned)stage * (A_CH * 16u);
 #pragma unroll
-        for (int it = 0; it < A_ITERS; ++it) {
-            const int q = tid + it * 256;
-            if (A_CH % 256 == 0 || q < A_CH) ra[it] = src[q];
-        }
+        for (int it = 0; it < A_ITERS; ++it)
+            if (A_CH % 256 == 0 || tid + it * 256 < A_CH)
+                ra[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, a_voff, base + it * 4096u, 0);
     };
     auto store_a = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
@@ -161,48 +178,23 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams p)
         }
     };
     auto load_x = [&](int chunk) __attribute__((always_inline)) {
-        const int cbase = chunk * KC + seg * 8;
+        const unsigned coff = x_voff + (unsigned)(chunk * KC) * 2u;
 #pragma unroll
         for (int it = 0; it < X_ITERS; ++it) {
-            const int xr = xr0 + it * RPP;
-            const int srow = n0 + minoff + xr;
-            const bool ok = xr < XR && srow >= 0 && srow < nrows;
-            const size_t e0 = (size_t)(rowbase + srow) * p.cin + cbase;
-#pragma unroll
-            for (int q = 0; q < XV; ++q) {
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (ok) v = SNAKE_IN ? reinterpret_cast<const u32x4*>(static_cast<const float*>(p.x) + e0)[q]
-                                     : *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.x) + e0 + (q ? p.in_lo_off : 0));
-                rx[it][q] = v;
-            }
-        }
-        if (SNAKE_IN) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) { al[e] = p.in_alpha[cbase + e]; ib[e] = p.in_inv_beta[cbase + e]; }
+            if (it * RPP >= XR) break;                        // uniform
+            const unsigned off = coff + it * x_row_step;
+            rx[it][0] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, off, 0, 0);
+            if (SPLIT_IN) rx[it][NP - 1] = __builtin_amdgcn_raw_buffer_load_b128(rs_xl, off, 0, 0);
         }
     };
     auto store_x = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < X_ITERS; ++it) {
+            if (it * RPP >= XR) break;                        // uniform
             const int xr = xr0 + it * RPP;
             if (xr >= XR_MAX) continue;
-            u32x4 v = rx[it][0], vlo = rx[it][XV - 1];
-            if (SNAKE_IN) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float e0 = __uint_as_float(rx[it][q >> 1][(2 * q) & 3]), e1 = __uint_as_float(rx[it][q >> 1][(2 * q + 1) & 3]);
-                    e0 = snake_fast(e0, al[2 * q], ib[2 * q]);
-                    e1 = snake_fast(e1, al[2 * q + 1], ib[2 * q + 1]);
-                    const uint32_t h0 = f32_to_bf16_bits(e0), h1 = f32_to_bf16_bits(e1);
-                    v[q] = h0 | (h1 << 16);
-                    if (SPLIT_IN) {
-                        const float r0 = e0 - __uint_as_float(h0 << 16), r1 = e1 - __uint_as_float(h1 << 16);
-                        vlo[q] = (uint32_t)f32_to_bf16_bits(r0) | ((uint32_t)f32_to_bf16_bits(r1) << 16);
-                    }
-                }
-            }
-            *reinterpret_cast<u32x4*>(&Xs[0][xr * LDK + seg * 8]) = v;
-            if (SPLIT_IN) *reinterpret_cast<u32x4*>(&Xs[NP - 1][xr * LDK + seg * 8]) = vlo;
+            *reinterpret_cast<u32x4*>(&Xs[0][xr * LDK + seg * 8]) = rx[it][0];
+            if (SPLIT_IN) *reinterpret_cast<u32x4*>(&Xs[NP - 1][xr * LDK + seg * 8]) = rx[it][NP - 1];
         }
     };
 
@@ -263,9 +255,13 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams p)
     }
 
     // ---- epilogue: lane (j, h) of a 32x32 tile holds column j, rows 8g + 4h + {0..3}, g = 0..3 ----
+    // Stores past out_hi (and, for the transposed conv, before row 0) are out of range of the descriptors.
+    const unsigned out_rows = (unsigned)out_hi;
+    const __amdgpu_buffer_rsrc_t rs_y = make_rsrc(MODE == MODE_ACT ? nullptr : p.y + rowbase_o * p.cout,
+                                                  MODE == MODE_ACT ? 0u : out_rows * p.cout * 4u);
+    const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.ya + rowbase_o * p.cout, EMIT > 0 ? out_rows * p.cout * 2u : 0u);
+    const __amdgpu_buffer_rsrc_t rs_al = make_rsrc(p.ya + p.out_lo_off + rowbase_o * p.cout, EMIT > 1 ? out_rows * p.cout * 2u : 0u);
     const int s_up = p.stride, p_up = p.stride / 2;
-    const long long nrows_out = (long long)nrows * (MODE == MODE_UP ? s_up : 1);
-    const long long rowbase_out = rowbase * (MODE == MODE_UP ? s_up : 1);
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi) {
 #pragma unroll
@@ -275,46 +271,41 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams p)
             if (MODE == MODE_UP) { phi = mu / p.cout; o = mu - phi * p.cout; }
             const float4 b4 = *reinterpret_cast<const float4*>(p.bias + o);
             float4 oa = make_float4(0, 0, 0, 0), ob = oa;
-            if (MODE == MODE_ACT) {
+            if (EMIT > 0) {
                 oa = *reinterpret_cast<const float4*>(p.out_alpha + o);
                 ob = *reinterpret_cast<const float4*>(p.out_inv_beta + o);
             }
 #pragma unroll
             for (int ni = 0; ni < TN; ++ni) {
                 const int col = n0 + wn * WTN + ni * 32 + j;
-                if (col >= ncols) continue;
                 float v0 = acc[mi][ni][4 * g + 0] + b4.x, v1 = acc[mi][ni][4 * g + 1] + b4.y;
                 float v2 = acc[mi][ni][4 * g + 2] + b4.z, v3 = acc[mi][ni][4 * g + 3] + b4.w;
-                long long n = col;
-                if (MODE == MODE_UP) {
-                    n = (long long)col * s_up - p_up + phi;
-                    if (n < 0 || n >= nrows_out) continue;
+                const int n = (MODE == MODE_UP) ? col * s_up - p_up + phi : col;
+                // element index inside the window; a negative row wraps to a huge offset = out of range
+                const unsigned e = (unsigned)(n * p.cout + o);
+                if (MODE == MODE_RES) {
+                    const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rs_y, e * 4u, 0, 0);
+                    v0 += __uint_as_float(r[0]); v1 += __uint_as_float(r[1]);
+                    v2 += __uint_as_float(r[2]); v3 += __uint_as_float(r[3]);
                 }
-                const size_t idx = (size_t)(rowbase_out + n) * p.cout + o;
-                if (MODE == MODE_ACT) {
+                if (MODE != MODE_ACT) {
+                    const u32x4 st = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2), __float_as_uint(v3)};
+                    __builtin_amdgcn_raw_buffer_store_b128(st, rs_y, e * 4u, 0, 0);
+                }
+                if (EMIT > 0) {
                     v0 = snake_fast(v0, oa.x, ob.x); v1 = snake_fast(v1, oa.y, ob.y);
                     v2 = snake_fast(v2, oa.z, ob.z); v3 = snake_fast(v3, oa.w, ob.w);
-                }
-                if (MODE == MODE_RES) {
-                    const float4 r = *reinterpret_cast<const float4*>(p.res + idx);
-                    v0 += r.x; v1 += r.y; v2 += r.z; v3 += r.w;
-                }
-                if (MODE == MODE_ACT) {
                     const uint32_t h0 = f32_to_bf16_bits(v0), h1 = f32_to_bf16_bits(v1);
                     const uint32_t h2 = f32_to_bf16_bits(v2), h3 = f32_to_bf16_bits(v3);
-                    uint2 st;
-                    st.x = h0 | (h1 << 16);
-                    st.y = h2 | (h3 << 16);
-                    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.y) + idx) = st;
-                    if (SPLIT_OUT) {
-                        st.x = (uint32_t)f32_to_bf16_bits(v0 - __uint_as_float(h0 << 16)) |
-                               ((uint32_t)f32_to_bf16_bits(v1 - __uint_as_float(h1 << 16)) << 16);
-                        st.y = (uint32_t)f32_to_bf16_bits(v2 - __uint_as_float(h2 << 16)) |
-                               ((uint32_t)f32_to_bf16_bits(v3 - __uint_as_float(h3 << 16)) << 16);
-                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.y) + p.out_lo_off + idx) = st;
+                    const u32x2 sh = {h0 | (h1 << 16), h2 | (h3 << 16)};
+                    __builtin_amdgcn_raw_buffer_store_b64(sh, rs_a, e * 2u, 0, 0);
+                    if (EMIT > 1) {
+                        const u32x2 sl = {(uint32_t)f32_to_bf16_bits(v0 - __uint_as_float(h0 << 16)) |
+                                              ((uint32_t)f32_to_bf16_bits(v1 - __uint_as_float(h1 << 16)) << 16),
+                                          (uint32_t)f32_to_bf16_bits(v2 - __uint_as_float(h2 << 16)) |
+                                              ((uint32_t)f32_to_bf16_bits(v3 - __uint_as_float(h3 << 16)) << 16)};
+                        __builtin_amdgcn_raw_buffer_store_b64(sl, rs_al, e * 2u, 0, 0);
                     }
-                } else {
-                    *reinterpret_cast<float4*>(static_cast<float*>(p.y) + idx) = make_float4(v0, v1, v2, v3);
                 }
             }
         }
@@ -322,18 +313,19 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams p)
 }
 
 template <int MT, int NT, int KC, int WM, int WN>
-static hipError_t launch_variant(const MfmaParams& p, int mode, bool split_in, bool split_out, dim3 grid, hipStream_t stream)
+static hipError_t launch_variant(const MfmaParams& p, int mode, bool split_in, int emit, dim3 grid, hipStream_t stream)
 {
-#define DEMON_LAUNCH(MODE_, SI_, SO_) \
-    hipLaunchKernelGGL((conv_mfma_kernel<MT, NT, KC, WM, WN, MODE_, SI_, SO_>), grid, dim3(256), 0, stream, p)
+#define DEMON_LAUNCH(MODE_, SI_, EM_) \
+    hipLaunchKernelGGL((conv_mfma_kernel<MT, NT, KC, WM, WN, MODE_, SI_, EM_>), grid, dim3(256), 0, stream, p)
+#define DEMON_LAUNCH_SI(MODE_, EM_) do { if (split_in) DEMON_LAUNCH(MODE_, true, EM_); else DEMON_LAUNCH(MODE_, false, EM_); } while (0)
     if (mode == MODE_ACT) {
-        if (split_in) { if (split_out) DEMON_LAUNCH(MODE_ACT, true, true); else DEMON_LAUNCH(MODE_ACT, true, false); }
-        else          { if (split_out) DEMON_LAUNCH(MODE_ACT, false, true); else DEMON_LAUNCH(MODE_ACT, false, false); }
+        if (emit == 2) DEMON_LAUNCH_SI(MODE_ACT, 2); else DEMON_LAUNCH_SI(MODE_ACT, 1);
     } else if (mode == MODE_RES) {
-        if (split_in) DEMON_LAUNCH(MODE_RES, true, false); else DEMON_LAUNCH(MODE_RES, false, false);
+        if (emit == 2) DEMON_LAUNCH_SI(MODE_RES, 2); else if (emit == 1) DEMON_LAUNCH_SI(MODE_RES, 1); else DEMON_LAUNCH_SI(MODE_RES, 0);
     } else {
-        if (split_in) DEMON_LAUNCH(MODE_UP, true, false); else DEMON_LAUNCH(MODE_UP, false, false);
+        if (emit == 2) DEMON_LAUNCH_SI(MODE_UP, 2); else if (emit == 1) DEMON_LAUNCH_SI(MODE_UP, 1); else DEMON_LAUNCH_SI(MODE_UP, 0);
     }
+#undef DEMON_LAUNCH_SI
 #undef DEMON_LAUNCH
     return hipGetLastError();
 }
@@ -344,33 +336,40 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     const Variant v = kVariants[variant];
     const int M = a.stride > 0 ? a.stride * a.cout : a.cout;
     MfmaParams p;
-    p.x = a.x; p.y = a.y; p.res = (const float*)a.res; p.w = (const uint16_t*)a.w;
-    p.bias = a.bias;
-    p.in_alpha = a.in_alpha; p.in_inv_beta = a.in_inv_beta;
+    p.xa = (const uint16_t*)a.x; p.w = (const uint16_t*)a.w; p.bias = a.bias;
+    p.y = (float*)a.y; p.ya = (uint16_t*)a.ya;
     p.out_alpha = a.out_alpha; p.out_inv_beta = a.out_inv_beta;
     p.slots = a.slots;
     p.r_in = a.r_in; p.cin = a.cin; p.cout = a.cout; p.ntaps = a.ntaps; p.stride = a.stride;
     p.nchunks = a.cin / v.KC; p.margin = a.margin;
     p.in_lo_off = a.in_lo_off; p.out_lo_off = a.out_lo_off;
+    const size_t wb = (size_t)M * a.ntaps * a.cin * 2;
+    if (wb > 0xffffffffull) return hipErrorInvalidValue;
+    p.w_bytes = (unsigned)wb;
     int mode;
     if (a.stride > 0) { p.tap0 = 0; p.tap_step = -1; mode = MODE_UP; }
     else { p.tap0 = -((a.ntaps - 1) / 2) * a.dil; p.tap_step = a.dil; mode = a.res ? MODE_RES : MODE_ACT; }
+    const int emit = a.ya ? (a.split_out ? 2 : 1) : 0;
     const int span = (a.ntaps - 1) * (a.stride > 0 ? 1 : a.dil);
     // shape checks: everything the kernel's indexing assumes
-    if (span > MAXSPAN || M % v.MT != 0 || a.cin % v.KC != 0 || a.cout % 4 != 0) return hipErrorInvalidValue;
-    if (mode == MODE_ACT && (!a.in_alpha || !a.out_alpha)) return hipErrorInvalidValue;
-    if (mode == MODE_UP && !a.in_alpha) return hipErrorInvalidValue;
-    if (a.split_out && mode != MODE_ACT) return hipErrorInvalidValue;
-    if ((long long)a.max_len * a.r_in * (a.stride > 0 ? a.stride : 1) > 0x3fffffffll || a.margin < 0) return hipErrorInvalidValue;
-    // most columns any window needs: interior plus margins, never more than the longest window
+    if (span > MAXSPAN || M % v.MT != 0 || a.cin % v.KC != 0 || a.cout % 4 != 0 || a.margin < 0) return hipErrorInvalidValue;
+    if (mode == MODE_ACT && emit == 0) return hipErrorInvalidValue;
+    if (emit > 0 && (!a.out_alpha || !a.out_inv_beta)) return hipErrorInvalidValue;
+    if (mode != MODE_ACT && !a.y) return hipErrorInvalidValue;
+    if (mode == MODE_RES && a.res != a.y) return hipErrorInvalidValue;            // the residual add is in place
+    // one window's activation plane must fit a 32-bit byte offset (buffer descriptors)
     const long long r_out = (long long)a.r_in * (a.stride > 0 ? a.stride : 1);
+    const long long max_in_bytes = (long long)a.max_len * a.r_in * a.cin * 2;
+    const long long max_out_bytes = (long long)a.max_len * r_out * a.cout * 4;
+    if (max_in_bytes > 0xf0000000ll || max_out_bytes > 0xf0000000ll) return hipErrorInvalidValue;
+    // most columns any window needs: interior plus margins, never more than the longest window
     long long out_rows = std::min((long long)a.max_int * r_out + 2ll * a.margin, (long long)a.max_len * r_out);
     const long long ncols = a.stride > 0 ? out_rows / a.stride + 2 : out_rows;
     dim3 grid((unsigned)((ncols + v.NT - 1) / v.NT), (unsigned)a.n_slots, (unsigned)(M / v.MT));
     switch (variant) {
-        case 0: return launch_variant<128, 128, 64, 2, 2>(p, mode, a.split_in, a.split_out, grid, stream);
-        case 1: return launch_variant<64, 256, 64, 1, 4>(p, mode, a.split_in, a.split_out, grid, stream);
-        default: return launch_variant<32, 128, 16, 1, 4>(p, mode, a.split_in, a.split_out, grid, stream);
+        case 0: return launch_variant<128, 128, 64, 2, 2>(p, mode, a.split_in, emit, grid, stream);
+        case 1: return launch_variant<64, 256, 64, 1, 4>(p, mode, a.split_in, emit, grid, stream);
+        default: return launch_variant<32, 128, 16, 1, 4>(p, mode, a.split_in, emit, grid, stream);
     }
 }
 
