@@ -415,11 +415,11 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
         {
             ConvLayer& L = B.up;
             L.cin = cin; L.cout = c; L.ntaps = 2; L.stride = s;
+            L.split_in = bf && c >= kSplitWidth;
             if (bf) {
-                L.variant = choose_variant_bf16(cin, s * c);
+                L.variant = choose_variant_bf16(cin, s * c, L.split_in);
                 if (L.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for a %d -> %d stride-%d upsampling", cin, c, s);
             }
-            L.split_in = bf && c >= kSplitWidth;
             Pending p{&L, 0, 0, {}, {}, true, false};
             p.in = pack_snake(ar, w, w + cin, cin, bf);  w += 2 * cin;
             p.w = pack_conv(ar, w, L, bf);               w += (size_t)cin * c * 2 * s;
@@ -432,11 +432,12 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
             D.cin = c; D.cout = c; D.ntaps = st.res_kernel; D.dil = st.dilations[j];
             ConvLayer& P = U.pointwise;
             P.cin = c; P.cout = c; P.ntaps = 1; P.dil = 1;
-            if (bf) {
-                D.variant = P.variant = choose_variant_bf16(c, c);
-                if (D.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for %d channels", c);
-            }
             D.split_out = P.split_in = bf && c >= kSplitWidth;
+            if (bf) {
+                D.variant = choose_variant_bf16(c, c, D.split_in);
+                P.variant = choose_variant_bf16(c, c, P.split_in);
+                if (D.variant < 0 || P.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for %d channels", c);
+            }
             U.fused = bf && (c == 64 || c == 128) && (st.res_kernel - 1) * st.dilations[j] <= 64 && !D.split_out && g_allow_fused;
             if (U.fused) D.variant = (c == 64) ? 1 : 0;      // weight blocks of C x 64
             Pending pd{&D, 0, 0, {}, {}, true, true};

@@ -81,7 +81,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream);
 // Packed weight sizes / packing (host).  w_src is the PyTorch layout: conv [cout, cin, k]; convT [cin, cout, 2s].
 size_t packed_f32_count(int cin, int cout, int ntaps, int stride);
 void pack_f32(const float* w_src, int cin, int cout, int ntaps, int stride, float* dst);
-int  choose_variant_bf16(int cin, int m);                 // -1 if unsupported
+int  choose_variant_bf16(int cin, int m, bool split_in);   // -1 if unsupported
 size_t packed_bf16_count(int cin, int cout, int ntaps, int stride, int variant);
 void pack_bf16(const float* w_src, int cin, int cout, int ntaps, int stride, int variant, uint16_t* dst);
 uint16_t f32_to_bf16_rne(float v);

@@ -26,6 +26,8 @@
 //
 // Accumulation is fp32 in a fixed order (chunk-major, then tap, then channel), independent of where the
 // tile sits in the window, so a windowed decode reproduces the full decode bit for bit.
+#include <stdlib.h>
+
 #include <algorithm>
 
 #include "device_common.h"
@@ -55,8 +57,9 @@ struct MfmaParams {
 struct Variant { int MT, NT, KC; };
 static const Variant kVariants[3] = {{128, 128, 64}, {64, 256, 64}, {32, 128, 16}};
 
-int choose_variant_bf16(int cin, int m)
+int choose_variant_bf16(int cin, int m, bool split_in)
 {
+    (void)split_in;
     if (cin % 64 == 0 && m % 128 == 0) return 0;
     if (cin % 64 == 0 && m % 64 == 0) return 1;
     if (cin % 16 == 0 && m % 32 == 0) return 2;
@@ -104,23 +107,30 @@ void pack_bf16(const float* w, int cin, int cout, int ntaps, int stride, int var
 }
 
 template <int MT, int NT, int KC, int WM, int WN, int MODE, bool SPLIT_IN, int EMIT>
-__global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams p)
+__global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
 {
+    constexpr int NTH = 64 * WM * WN;           // threads per workgroup
     constexpr int LDK = KC + 8;                 // padded LDS row (bf16 elements): 16-byte multiple, bank-spread
     constexpr int XR_MAX = NT + MAXSPAN;
     constexpr int WTM = MT / WM, WTN = NT / WN; // tile of one wave
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int SEGS = KC / 8;                // 16-byte segments per row
-    constexpr int RPP = 256 / SEGS;             // rows staged per pass
+    constexpr int RPP = NTH / SEGS;             // rows staged per pass
     constexpr int A_CH = MT * SEGS;             // 16-byte chunks of an A block
-    constexpr int A_ITERS = (A_CH + 255) / 256;
+    constexpr int A_ITERS = (A_CH + NTH - 1) / NTH;
     constexpr int X_ITERS = (XR_MAX + RPP - 1) / RPP;
     constexpr int NP = SPLIT_IN ? 2 : 1;        // operand planes (hi, lo)
-    static_assert(WM * WN == 4, "four waves per workgroup");
+    static_assert(WM * WN == 4 || WM * WN == 8, "four or eight waves per workgroup");
     static_assert(MODE != MODE_ACT || EMIT > 0, "the dilated conv only has the activated output");
 
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][MT * LDK];
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[NP][XR_MAX * LDK];
+    // epilogue staging: every wave transposes its accumulators through a private 32-column block
+    constexpr int LDT = WTM + 4;                // padded row (floats) of the staging block
+    constexpr int STG_BYTES = WM * WN * 32 * LDT * 4;
+    constexpr int AS_BYTES = 2 * MT * LDK * 2, XS_BYTES = NP * XR_MAX * LDK * 2;
+    constexpr int SMEM_BYTES = (AS_BYTES + XS_BYTES > STG_BYTES) ? AS_BYTES + XS_BYTES : STG_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
+    uint16_t (*As)[MT * LDK] = reinterpret_cast<uint16_t (*)[MT * LDK]>(smem);
+    uint16_t (*Xs)[XR_MAX * LDK] = reinterpret_cast<uint16_t (*)[XR_MAX * LDK]>(smem + AS_BYTES);
 
     const Slot s = p.slots[blockIdx.y];
     const int nrows = s.len * p.r_in;                       // valid input rows of this window
@@ -166,14 +176,14 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams p)
         const unsigned base = w_tile0 + (unsigned)stage * (A_CH * 16u);
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it)
-            if (A_CH % 256 == 0 || tid + it * 256 < A_CH)
-                ra[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, a_voff, base + it * 4096u, 0);
+            if (A_CH % NTH == 0 || tid + it * NTH < A_CH)
+                ra[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, a_voff, base + it * (NTH * 16u), 0);
     };
     auto store_a = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it) {
-            const int q = tid + it * 256;
-            if (A_CH % 256 == 0 || q < A_CH)
+            const int q = tid + it * NTH;
+            if (A_CH % NTH == 0 || q < A_CH)
                 *reinterpret_cast<u32x4*>(&As[buf][(q / SEGS) * LDK + (q % SEGS) * 8]) = ra[it];
         }
     };
@@ -254,58 +264,71 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams p)
         tap = ntap; chunk = nchunk;
     }
 
-    // ---- epilogue: lane (j, h) of a 32x32 tile holds column j, rows 8g + 4h + {0..3}, g = 0..3 ----
-    // Stores past out_hi (and, for the transposed conv, before row 0) are out of range of the descriptors.
+    // ---- epilogue.  A lane of a 32x32 accumulator tile holds ONE time column and rows 8g + 4h + {0..3}:
+    // stored as is, every instruction would touch 32 different rows with 16-32 bytes each.  Instead each
+    // wave transposes 32 columns at a time through a private LDS block and then handles whole rows:
+    // a lane owns 4 consecutive channels, WTM/4 consecutive lanes cover a row, so residual loads and all
+    // stores are full contiguous runs.  Rows past out_hi (and, for the transposed conv, before row 0) are
+    // out of range of the descriptors and dropped.
+    __syncthreads();                                   // all waves are done with the operand tiles
+    float* stage = reinterpret_cast<float*>(smem) + wave * (32 * LDT);
+    constexpr int LPR = WTM / 4;                       // lanes per row
+    constexpr int RPI = 64 / LPR;                      // rows per instruction
+    const int cl = lane % LPR, rl = lane / LPR;
     const unsigned out_rows = (unsigned)out_hi;
     const __amdgpu_buffer_rsrc_t rs_y = make_rsrc(MODE == MODE_ACT ? nullptr : p.y + rowbase_o * p.cout,
                                                   MODE == MODE_ACT ? 0u : out_rows * p.cout * 4u);
     const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.ya + rowbase_o * p.cout, EMIT > 0 ? out_rows * p.cout * 2u : 0u);
     const __amdgpu_buffer_rsrc_t rs_al = make_rsrc(p.ya + p.out_lo_off + rowbase_o * p.cout, EMIT > 1 ? out_rows * p.cout * 2u : 0u);
+    const int mu = m0 + wm * WTM + 4 * cl;             // this lane's 4 GEMM rows
+    const int o = (MODE == MODE_UP) ? mu % p.cout : mu;   // ... are 4 consecutive output channels
+    const float4 b4 = *reinterpret_cast<const float4*>(p.bias + o);
+    float4 oa = make_float4(0, 0, 0, 0), ob = oa;
+    if (EMIT > 0) {
+        oa = *reinterpret_cast<const float4*>(p.out_alpha + o);
+        ob = *reinterpret_cast<const float4*>(p.out_inv_beta + o);
+    }
     const int s_up = p.stride, p_up = p.stride / 2;
 #pragma unroll
-    for (int mi = 0; mi < TM; ++mi) {
+    for (int ni = 0; ni < TN; ++ni) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int mu = m0 + wm * WTM + mi * 32 + 8 * g + 4 * h;
-            int o = mu, phi = 0;
-            if (MODE == MODE_UP) { phi = mu / p.cout; o = mu - phi * p.cout; }
-            const float4 b4 = *reinterpret_cast<const float4*>(p.bias + o);
-            float4 oa = make_float4(0, 0, 0, 0), ob = oa;
-            if (EMIT > 0) {
-                oa = *reinterpret_cast<const float4*>(p.out_alpha + o);
-                ob = *reinterpret_cast<const float4*>(p.out_inv_beta + o);
+        for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<float4*>(&stage[j * LDT + mi * 32 + 8 * g + 4 * h]) =
+                    make_float4(acc[mi][ni][4 * g + 0], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2], acc[mi][ni][4 * g + 3]);
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int row = it * RPI + rl;
+            const float4 t4 = *reinterpret_cast<const float4*>(&stage[row * LDT + 4 * cl]);
+            float v0 = t4.x + b4.x, v1 = t4.y + b4.y, v2 = t4.z + b4.z, v3 = t4.w + b4.w;
+            const int col = n0 + wn * WTN + ni * 32 + row;
+            // element index inside the window: conv (col, mu); transposed conv: column m, row mu = phi*cout + o
+            // lands on sample m s - p + phi, i.e. on the run starting at (m s - p) cout + mu.  A negative row
+            // wraps to a huge offset = out of range.
+            const unsigned e = (MODE == MODE_UP) ? (unsigned)((col * s_up - p_up) * p.cout + mu) : (unsigned)(col * p.cout + mu);
+            if (MODE == MODE_RES) {
+                const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rs_y, e * 4u, 0, 0);
+                v0 += __uint_as_float(r[0]); v1 += __uint_as_float(r[1]);
+                v2 += __uint_as_float(r[2]); v3 += __uint_as_float(r[3]);
             }
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni) {
-                const int col = n0 + wn * WTN + ni * 32 + j;
-                float v0 = acc[mi][ni][4 * g + 0] + b4.x, v1 = acc[mi][ni][4 * g + 1] + b4.y;
-                float v2 = acc[mi][ni][4 * g + 2] + b4.z, v3 = acc[mi][ni][4 * g + 3] + b4.w;
-                const int n = (MODE == MODE_UP) ? col * s_up - p_up + phi : col;
-                // element index inside the window; a negative row wraps to a huge offset = out of range
-                const unsigned e = (unsigned)(n * p.cout + o);
-                if (MODE == MODE_RES) {
-                    const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rs_y, e * 4u, 0, 0);
-                    v0 += __uint_as_float(r[0]); v1 += __uint_as_float(r[1]);
-                    v2 += __uint_as_float(r[2]); v3 += __uint_as_float(r[3]);
-                }
-                if (MODE != MODE_ACT) {
-                    const u32x4 st = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2), __float_as_uint(v3)};
-                    __builtin_amdgcn_raw_buffer_store_b128(st, rs_y, e * 4u, 0, 0);
-                }
-                if (EMIT > 0) {
-                    v0 = snake_fast(v0, oa.x, ob.x); v1 = snake_fast(v1, oa.y, ob.y);
-                    v2 = snake_fast(v2, oa.z, ob.z); v3 = snake_fast(v3, oa.w, ob.w);
-                    const uint32_t h0 = f32_to_bf16_bits(v0), h1 = f32_to_bf16_bits(v1);
-                    const uint32_t h2 = f32_to_bf16_bits(v2), h3 = f32_to_bf16_bits(v3);
-                    const u32x2 sh = {h0 | (h1 << 16), h2 | (h3 << 16)};
-                    __builtin_amdgcn_raw_buffer_store_b64(sh, rs_a, e * 2u, 0, 0);
-                    if (EMIT > 1) {
-                        const u32x2 sl = {(uint32_t)f32_to_bf16_bits(v0 - __uint_as_float(h0 << 16)) |
-                                              ((uint32_t)f32_to_bf16_bits(v1 - __uint_as_float(h1 << 16)) << 16),
-                                          (uint32_t)f32_to_bf16_bits(v2 - __uint_as_float(h2 << 16)) |
-                                              ((uint32_t)f32_to_bf16_bits(v3 - __uint_as_float(h3 << 16)) << 16)};
-                        __builtin_amdgcn_raw_buffer_store_b64(sl, rs_al, e * 2u, 0, 0);
-                    }
+            if (MODE != MODE_ACT) {
+                const u32x4 st = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2), __float_as_uint(v3)};
+                __builtin_amdgcn_raw_buffer_store_b128(st, rs_y, e * 4u, 0, 0);
+            }
+            if (EMIT > 0) {
+                v0 = snake_fast(v0, oa.x, ob.x); v1 = snake_fast(v1, oa.y, ob.y);
+                v2 = snake_fast(v2, oa.z, ob.z); v3 = snake_fast(v3, oa.w, ob.w);
+                const uint32_t h0 = f32_to_bf16_bits(v0), h1 = f32_to_bf16_bits(v1);
+                const uint32_t h2 = f32_to_bf16_bits(v2), h3 = f32_to_bf16_bits(v3);
+                const u32x2 sh = {h0 | (h1 << 16), h2 | (h3 << 16)};
+                __builtin_amdgcn_raw_buffer_store_b64(sh, rs_a, e * 2u, 0, 0);
+                if (EMIT > 1) {
+                    const u32x2 sl = {(uint32_t)f32_to_bf16_bits(v0 - __uint_as_float(h0 << 16)) |
+                                          ((uint32_t)f32_to_bf16_bits(v1 - __uint_as_float(h1 << 16)) << 16),
+                                      (uint32_t)f32_to_bf16_bits(v2 - __uint_as_float(h2 << 16)) |
+                                          ((uint32_t)f32_to_bf16_bits(v3 - __uint_as_float(h3 << 16)) << 16)};
+                    __builtin_amdgcn_raw_buffer_store_b64(sl, rs_al, e * 2u, 0, 0);
                 }
             }
         }
@@ -316,8 +339,10 @@ template <int MT, int NT, int KC, int WM, int WN>
 static hipError_t launch_variant(const MfmaParams& p, int mode, bool split_in, int emit, dim3 grid, hipStream_t stream)
 {
 #define DEMON_LAUNCH(MODE_, SI_, EM_) \
-    hipLaunchKernelGGL((conv_mfma_kernel<MT, NT, KC, WM, WN, MODE_, SI_, EM_>), grid, dim3(256), 0, stream, p)
-#define DEMON_LAUNCH_SI(MODE_, EM_) do { if (split_in) DEMON_LAUNCH(MODE_, true, EM_); else DEMON_LAUNCH(MODE_, false, EM_); } while (0)
+    hipLaunchKernelGGL((conv_mfma_kernel<MT, NT, KC, WM, WN, MODE_, SI_, EM_>), grid, dim3(64 * WM * WN), 0, stream, p)
+#define DEMON_LAUNCH_SI(MODE_, EM_) do { \
+        if (!split_in) DEMON_LAUNCH(MODE_, false, EM_); \
+        else DEMON_LAUNCH(MODE_, true, EM_); } while (0)
     if (mode == MODE_ACT) {
         if (emit == 2) DEMON_LAUNCH_SI(MODE_ACT, 2); else DEMON_LAUNCH_SI(MODE_ACT, 1);
     } else if (mode == MODE_RES) {

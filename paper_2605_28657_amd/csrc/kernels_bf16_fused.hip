@@ -12,6 +12,8 @@
 // 32 (kk/2) + 8 (2 (kk%2) + e/4) + 4 h + e%4.  The 1x1 weights are packed in that order at create.
 // The result is written to a second buffer (neighbouring tiles still read this tile's input rows).
 // With EMIT the kernel also writes bf16(snake_next(h_out)), the operand of the next (unfused) layer.
+#include <stdlib.h>
+
 #include <algorithm>
 
 #include "device_common.h"
@@ -19,6 +21,7 @@
 namespace demon {
 
 constexpr int FUSED_MAXSPAN = 64;
+static const bool g_c64_tn1 = getenv("DEMON_VAE_C64_TN1") != nullptr;   // experiment: 128-column tiles for C = 64
 
 struct FusedParams {
     const float* x; float* y;
@@ -65,8 +68,14 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     static_assert(A_CH % 256 == 0 && W1_CH % 256 == 0, "staging loops assume whole passes");
     static_assert(CH * LD1 <= 2 * CH * LDK, "the 1x1 weights reuse the dilated-conv weight buffers");
 
-    __shared__ __attribute__((aligned(16))) uint16_t As[2 * CH * LDK];
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[XR_MAX * LDK];
+    // epilogue staging: every wave transposes its output through a private 32-column block
+    constexpr int LDT = CH + 4;
+    constexpr int STG_BYTES = 4 * 32 * LDT * 4;
+    constexpr int AS_BYTES = 2 * CH * LDK * 2, XS_BYTES = XR_MAX * LDK * 2;
+    constexpr int SMEM_BYTES = (AS_BYTES + XS_BYTES > STG_BYTES) ? AS_BYTES + XS_BYTES : STG_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
+    uint16_t* As = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* Xs = reinterpret_cast<uint16_t*>(smem + AS_BYTES);
 
     const Slot s = p.slots[blockIdx.y];
     const int nrows = s.len * p.r;
@@ -248,36 +257,48 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
                 acc[mo][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mo], mid[kk][ni], acc[mo][ni], 0, 0, 0);
     }
 
-    // ---- bias + residual, fp32 store to the other buffer (rows past out_hi are outside the descriptors)
+    // ---- bias + residual, fp32 store to the other buffer.  Each wave transposes 32 columns at a time
+    // through a private LDS block so that a lane owns 4 consecutive channels and CH/4 consecutive lanes a
+    // whole row: residual loads and stores are contiguous runs.  Rows past out_hi are outside the
+    // descriptors and dropped.
+    __syncthreads();                                   // all waves are done with the 1x1 weights in LDS
+    float* stage = reinterpret_cast<float*>(smem) + wn * (32 * LDT);
+    constexpr int LPR = CH / 4;                        // lanes per row
+    constexpr int RPI = 64 / LPR;                      // rows per instruction
+    const int cl = lane % LPR, rl = lane / LPR;
+    const float4 b4 = *reinterpret_cast<const float4*>(p.b1 + 4 * cl);
+    float4 a4 = make_float4(0, 0, 0, 0), i4 = a4;
+    if (EMIT) {
+        a4 = *reinterpret_cast<const float4*>(p.a3 + 4 * cl);
+        i4 = *reinterpret_cast<const float4*>(p.ib3 + 4 * cl);
+    }
 #pragma unroll
-    for (int mo = 0; mo < TM; ++mo) {
+    for (int ni = 0; ni < TN; ++ni) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int c = mo * 32 + 8 * g + 4 * h;
-            const float4 b4 = *reinterpret_cast<const float4*>(p.b1 + c);
-            float4 a4 = make_float4(0, 0, 0, 0), i4 = a4;
+        for (int mo = 0; mo < TM; ++mo)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<float4*>(&stage[j * LDT + mo * 32 + 8 * g + 4 * h]) =
+                    make_float4(acc[mo][ni][4 * g + 0], acc[mo][ni][4 * g + 1], acc[mo][ni][4 * g + 2], acc[mo][ni][4 * g + 3]);
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int row = it * RPI + rl;
+            const float4 t4 = *reinterpret_cast<const float4*>(&stage[row * LDT + 4 * cl]);
+            const int col = n0 + wn * WTN + ni * 32 + row;
+            const unsigned e = (unsigned)(col * CH + 4 * cl);
+            const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rs_x, e * 4u, 0, 0);
+            float v0 = t4.x + b4.x + __uint_as_float(r[0]);
+            float v1 = t4.y + b4.y + __uint_as_float(r[1]);
+            float v2 = t4.z + b4.z + __uint_as_float(r[2]);
+            float v3 = t4.w + b4.w + __uint_as_float(r[3]);
+            const u32x4 st = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2), __float_as_uint(v3)};
+            __builtin_amdgcn_raw_buffer_store_b128(st, rs_y, e * 4u, 0, 0);
             if (EMIT) {
-                a4 = *reinterpret_cast<const float4*>(p.a3 + c);
-                i4 = *reinterpret_cast<const float4*>(p.ib3 + c);
-            }
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni) {
-                const int col = n0 + wn * WTN + ni * 32 + j;
-                const unsigned e = (unsigned)(col * CH + c);
-                const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rs_x, e * 4u, 0, 0);
-                float v0 = acc[mo][ni][4 * g + 0] + b4.x + __uint_as_float(r[0]);
-                float v1 = acc[mo][ni][4 * g + 1] + b4.y + __uint_as_float(r[1]);
-                float v2 = acc[mo][ni][4 * g + 2] + b4.z + __uint_as_float(r[2]);
-                float v3 = acc[mo][ni][4 * g + 3] + b4.w + __uint_as_float(r[3]);
-                const u32x4 st = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2), __float_as_uint(v3)};
-                __builtin_amdgcn_raw_buffer_store_b128(st, rs_y, e * 4u, 0, 0);
-                if (EMIT) {
-                    v0 = snake_fast(v0, a4.x, i4.x); v1 = snake_fast(v1, a4.y, i4.y);
-                    v2 = snake_fast(v2, a4.z, i4.z); v3 = snake_fast(v3, a4.w, i4.w);
-                    const u32x2 sh = {(uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16),
-                                      (uint32_t)f32_to_bf16_bits(v2) | ((uint32_t)f32_to_bf16_bits(v3) << 16)};
-                    __builtin_amdgcn_raw_buffer_store_b64(sh, rs_a, e * 2u, 0, 0);
-                }
+                v0 = snake_fast(v0, a4.x, i4.x); v1 = snake_fast(v1, a4.y, i4.y);
+                v2 = snake_fast(v2, a4.z, i4.z); v3 = snake_fast(v3, a4.w, i4.w);
+                const u32x2 sh = {(uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16),
+                                  (uint32_t)f32_to_bf16_bits(v2) | ((uint32_t)f32_to_bf16_bits(v3) << 16)};
+                __builtin_amdgcn_raw_buffer_store_b64(sh, rs_a, e * 2u, 0, 0);
             }
         }
     }
@@ -297,7 +318,12 @@ hipError_t launch_res_unit_fused(const FusedArgs& a, hipStream_t stream)
     if ((long long)a.max_len * a.r * a.c * 4 > 0xf0000000ll) return hipErrorInvalidValue;
     const long long out_rows = std::min((long long)a.max_int * a.r + 2ll * a.margin, (long long)a.max_len * a.r);
     const bool emit = a.ya != nullptr;
-    if (a.c == 64) {
+    if (a.c == 64 && g_c64_tn1) {
+        constexpr int NT = 4 * 32 * 1;
+        dim3 grid((unsigned)((out_rows + NT - 1) / NT), (unsigned)a.n_slots);
+        if (emit) hipLaunchKernelGGL((res_unit_fused_kernel<64, 1, true>), grid, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL((res_unit_fused_kernel<64, 1, false>), grid, dim3(256), 0, stream, p);
+    } else if (a.c == 64) {
         constexpr int NT = 4 * 32 * 2;
         dim3 grid((unsigned)((out_rows + NT - 1) / NT), (unsigned)a.n_slots);
         if (emit) hipLaunchKernelGGL((res_unit_fused_kernel<64, 2, true>), grid, dim3(256), 0, stream, p);
