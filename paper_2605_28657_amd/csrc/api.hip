@@ -65,7 +65,7 @@ struct demon_vae {
     int head_cin = 0;
 
     // fp32 path: residual stream ping/pong + Snake scratch, all fp32.
-    // bf16 path: buf[0], buf[1] fp32 residual stream ping/pong, buf[2] bf16 activated branch tensor,
+    // bf16 path: buf[0], buf[1] residual stream ping/pong (half), buf[2] bf16 activated branch tensor,
     // buf[3], buf[4] bf16 activated operand of the next layer (each bf16 buffer: hi plane + lo plane).
     void* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     float* head_out = nullptr;                     // planar window waveforms [out_channels, cap_frames*S]
@@ -236,7 +236,7 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
         const int id = layer_id++;
         if (id != v->tap_layer || !v->tap_dst) return hipSuccess;
         const size_t n = std::min<size_t>(v->tap_cap, (size_t)plan->total_frames * r * c);
-        return launch_to_f32(x, v->tap_dst, n, false, stream);
+        return launch_to_f32(x, v->tap_dst, n, bf ? 2 : 0, stream);
     };
     auto conv_args = [&](const ConvLayer& L, const void* x, void* y, const void* res) {
         ConvArgs a;
@@ -321,7 +321,7 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
                 const ConvLayer* C = consumer(bi, (int)ui);
                 if (U.fused) {
                     FusedArgs f;
-                    f.x = (const float*)cur; f.y = (float*)other;
+                    f.x = cur; f.y = other;
                     if (C) { f.ya = acur; f.a3 = C->in_alpha; f.ib3 = C->in_inv_beta; }
                     f.w7 = (const uint16_t*)U.dilated.w; f.w1 = U.w1_fused;
                     f.b7 = U.dilated.bias; f.b1 = U.pointwise.bias;
@@ -348,7 +348,7 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
         }
     }
     const long long total_rows = plan->total_frames * r;
-    HIP_TRY(launch_head((const float*)cur, v->head_out, v->head_w, v->head_bias, v->head_alpha, v->head_inv_beta, v->head_cin,
+    HIP_TRY(launch_head(cur, bf, v->head_out, v->head_w, v->head_bias, v->head_alpha, v->head_inv_beta, v->head_cin,
                         v->st.out_channels, v->st.head_kernel, r, total_rows, bf, slots, ns, plan->max_int, stream), "head");
     HIP_TRY(mark(1), "event");
     HIP_TRY(launch_stitch(v->head_out, d_out, v->st.out_channels, r, n_frames, total_rows, slots, ns, plan->max_int, stream), "stitch");
@@ -506,7 +506,8 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
         if (v->d_slot_arena) (void)hipFree(v->d_slot_arena);
     };
     hipError_t e = hipMalloc(&v->d_params, ar.bytes.size());
-    for (int i = 0; e == hipSuccess && i < (bf ? 5 : 3); ++i) e = hipMalloc(&v->buf[i], act_elems * 4);   // bf16 buffers: hi and lo planes
+    // fp32 path: 4 bytes per element; bf16 path: half residual stream (2 bytes), bf16 operand buffers with hi and lo planes (4)
+    for (int i = 0; e == hipSuccess && i < (bf ? 5 : 3); ++i) e = hipMalloc(&v->buf[i], act_elems * ((bf && i < 2) ? 2 : 4));
     if (e == hipSuccess) e = hipMalloc((void**)&v->head_out, head_bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&v->d_slot_arena, sizeof(Slot) * kMaxSlots * kPlanCache);
     if (e == hipSuccess) e = hipMemcpy(v->d_params, ar.bytes.data(), ar.bytes.size(), hipMemcpyHostToDevice);

@@ -29,10 +29,12 @@ __device__ __forceinline__ float snake_precise(float x, float alpha, float inv_b
     return fmaf(s * s, inv_beta, x);
 }
 
-// Fast variant for the bf16 path: alpha_rev = alpha / (2 pi), the hardware sine takes revolutions.
+// Fast variant for the bf16 path: alpha_rev = alpha / (2 pi), the hardware sine takes revolutions.  It is
+// defined for |alpha_rev x| <= 256 and returns 0 beyond, where snake(x) = x is exact to far below the bf16
+// rounding of the operand it feeds (sin^2/beta <= 1/beta against |x| > 1600/alpha), so no range reduction.
 __device__ __forceinline__ float snake_fast(float x, float alpha_rev, float inv_beta)
 {
-    const float s = __builtin_amdgcn_sinf(__builtin_amdgcn_fractf(alpha_rev * x));
+    const float s = __builtin_amdgcn_sinf(alpha_rev * x);
     return fmaf(s * s, inv_beta, x);
 }
 
@@ -42,5 +44,28 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, un
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
+
+// Residual stream h of the bf16 path in HBM: IEEE half.  bf16 storage of h (one rounding of 2^-9 per layer, at
+// full strength on the main path) would by itself exceed the error budget; half has 3 more mantissa bits, its
+// roundings are an order of magnitude below those of the bf16 MFMA operands, and it halves the traffic of the
+// HBM-bound layers compared to fp32.  All arithmetic on h is fp32.
+typedef _Float16 hres_t;
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// four consecutive elements starting at element index e of the buffer
+__device__ __forceinline__ float4 hres_load4(__amdgpu_buffer_rsrc_t rs, unsigned e)
+{
+    const u32x2 r = __builtin_amdgcn_raw_buffer_load_b64(rs, e * 2u, 0, 0);
+    const f16x4 hv = __builtin_bit_cast(f16x4, r);
+    return make_float4((float)hv[0], (float)hv[1], (float)hv[2], (float)hv[3]);
+}
+__device__ __forceinline__ void hres_store4(__amdgpu_buffer_rsrc_t rs, unsigned e, float v0, float v1, float v2, float v3)
+{
+    const f16x4 hv = {(_Float16)v0, (_Float16)v1, (_Float16)v2, (_Float16)v3};     // round to nearest even
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, hv), rs, e * 2u, 0, 0);
+}
+// the values a later kernel will read back for (v0..v3): what survives the rounding of the store
+__device__ __forceinline__ float hres_round(float v) { return (float)(_Float16)v; }
 
 }  // namespace demon

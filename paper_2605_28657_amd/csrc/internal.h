@@ -88,7 +88,7 @@ uint16_t f32_to_bf16_rne(float v);
 
 // Fused residual unit (bf16 path, C = 64 or 128): y = x + W1 snake2(W7 (*) snake1(x) + b7) + b1, x != y.
 struct FusedArgs {
-    const float* x; float* y;
+    const void* x; void* y;  // residual stream in its HBM storage type (half)
     uint16_t* ya = nullptr;  // optional: bf16(snake(y; a3, ib3)) for an unfused consumer
     const float* a3 = nullptr; const float* ib3 = nullptr;
     const uint16_t* w7;      // packed as pack_bf16 does for an MT = C, KC = 64 tile
@@ -112,14 +112,15 @@ hipError_t launch_gather(const void* latent, float* x0, int c0, int n_frames, bo
                          const float* inv_beta = nullptr);
 // head: Snake -> Conv1d(k, cin -> oc) -> tanh; output planar fp32 [oc, total_rows]
 // `fast` selects the hardware-sine Snake (alpha given in revolutions) used by the bf16 path.
-hipError_t launch_head(const float* x, float* y, const float* w /*[k][cin][oc]*/, const float* bias,
+// `x_half`: the input is the bf16 path's half-precision residual stream, else fp32.
+hipError_t launch_head(const void* x, bool x_half, float* y, const float* w /*[k][cin][oc]*/, const float* bias,
                        const float* alpha, const float* inv_beta, int cin, int oc, int k, int r,
                        long long total_rows, bool fast, const Slot* slots, int n_slots, int max_int,
                        hipStream_t stream);
 // crop + stitch: planar slot waveform -> d_out [n_clips, oc, n_frames*S]
 hipError_t launch_stitch(const float* y, float* out, int oc, int S, int n_frames, long long total_rows,
                          const Slot* slots, int n_slots, int max_int, hipStream_t stream);
-// debug tap: activation -> fp32 copy
-hipError_t launch_to_f32(const void* x, float* dst, size_t n, bool bf16, hipStream_t stream);
+// debug tap: activation -> fp32 copy; src_type 0 fp32, 1 bf16, 2 half
+hipError_t launch_to_f32(const void* x, float* dst, size_t n, int src_type, hipStream_t stream);
 
 }  // namespace demon

@@ -45,7 +45,7 @@ struct MfmaParams {
     const uint16_t* xa;      // activated input, bf16 [rows][cin]; lo plane at xa + in_lo_off
     const uint16_t* w;       // packed weight blocks
     const float* bias;
-    float* y;                // fp32 output; MODE_RES: also the residual source (in place); unused in MODE_ACT
+    hres_t* y;               // residual-stream output; MODE_RES: also the residual source (in place); unused in MODE_ACT
     uint16_t* ya;            // bf16 activated output; lo plane at ya + out_lo_off
     const float* out_alpha; const float* out_inv_beta;   // Snake applied before writing ya
     const Slot* slots;
@@ -208,13 +208,20 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
         }
     };
 
+    // accumulators start at the bias: lane (j, h) holds GEMM rows m0 + wm*WTM + mi*32 + 8g + 4h + {0..3}
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < TN; ++ni)
+        for (int g = 0; g < 4; ++g) {
+            const int mu_b = m0 + wm * WTM + mi * 32 + 8 * g + 4 * h;
+            const float4 bb = *reinterpret_cast<const float4*>(p.bias + ((MODE == MODE_UP) ? mu_b % p.cout : mu_b));
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+            for (int ni = 0; ni < TN; ++ni) {
+                acc[mi][ni][4 * g + 0] = bb.x; acc[mi][ni][4 * g + 1] = bb.y;
+                acc[mi][ni][4 * g + 2] = bb.z; acc[mi][ni][4 * g + 3] = bb.w;
+            }
+        }
 
     load_a(0);
     load_x(0);
@@ -277,12 +284,11 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     const int cl = lane % LPR, rl = lane / LPR;
     const unsigned out_rows = (unsigned)out_hi;
     const __amdgpu_buffer_rsrc_t rs_y = make_rsrc(MODE == MODE_ACT ? nullptr : p.y + rowbase_o * p.cout,
-                                                  MODE == MODE_ACT ? 0u : out_rows * p.cout * 4u);
+                                                  MODE == MODE_ACT ? 0u : out_rows * p.cout * (unsigned)sizeof(hres_t));
     const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.ya + rowbase_o * p.cout, EMIT > 0 ? out_rows * p.cout * 2u : 0u);
     const __amdgpu_buffer_rsrc_t rs_al = make_rsrc(p.ya + p.out_lo_off + rowbase_o * p.cout, EMIT > 1 ? out_rows * p.cout * 2u : 0u);
     const int mu = m0 + wm * WTM + 4 * cl;             // this lane's 4 GEMM rows
     const int o = (MODE == MODE_UP) ? mu % p.cout : mu;   // ... are 4 consecutive output channels
-    const float4 b4 = *reinterpret_cast<const float4*>(p.bias + o);
     float4 oa = make_float4(0, 0, 0, 0), ob = oa;
     if (EMIT > 0) {
         oa = *reinterpret_cast<const float4*>(p.out_alpha + o);
@@ -301,20 +307,20 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
         for (int it = 0; it < 32 / RPI; ++it) {
             const int row = it * RPI + rl;
             const float4 t4 = *reinterpret_cast<const float4*>(&stage[row * LDT + 4 * cl]);
-            float v0 = t4.x + b4.x, v1 = t4.y + b4.y, v2 = t4.z + b4.z, v3 = t4.w + b4.w;
+            float v0 = t4.x, v1 = t4.y, v2 = t4.z, v3 = t4.w;
             const int col = n0 + wn * WTN + ni * 32 + row;
             // element index inside the window: conv (col, mu); transposed conv: column m, row mu = phi*cout + o
             // lands on sample m s - p + phi, i.e. on the run starting at (m s - p) cout + mu.  A negative row
             // wraps to a huge offset = out of range.
             const unsigned e = (MODE == MODE_UP) ? (unsigned)((col * s_up - p_up) * p.cout + mu) : (unsigned)(col * p.cout + mu);
             if (MODE == MODE_RES) {
-                const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rs_y, e * 4u, 0, 0);
-                v0 += __uint_as_float(r[0]); v1 += __uint_as_float(r[1]);
-                v2 += __uint_as_float(r[2]); v3 += __uint_as_float(r[3]);
+                const float4 r = hres_load4(rs_y, e);
+                v0 += r.x; v1 += r.y; v2 += r.z; v3 += r.w;
             }
             if (MODE != MODE_ACT) {
-                const u32x4 st = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2), __float_as_uint(v3)};
-                __builtin_amdgcn_raw_buffer_store_b128(st, rs_y, e * 4u, 0, 0);
+                hres_store4(rs_y, e, v0, v1, v2, v3);
+                // the next layer's operand is Snake of the STORED value (what a kernel reading h would see)
+                v0 = hres_round(v0); v1 = hres_round(v1); v2 = hres_round(v2); v3 = hres_round(v3);
             }
             if (EMIT > 0) {
                 v0 = snake_fast(v0, oa.x, ob.x); v1 = snake_fast(v1, oa.y, ob.y);
@@ -362,7 +368,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     const int M = a.stride > 0 ? a.stride * a.cout : a.cout;
     MfmaParams p;
     p.xa = (const uint16_t*)a.x; p.w = (const uint16_t*)a.w; p.bias = a.bias;
-    p.y = (float*)a.y; p.ya = (uint16_t*)a.ya;
+    p.y = (hres_t*)a.y; p.ya = (uint16_t*)a.ya;
     p.out_alpha = a.out_alpha; p.out_inv_beta = a.out_inv_beta;
     p.slots = a.slots;
     p.r_in = a.r_in; p.cin = a.cin; p.cout = a.cout; p.ntaps = a.ntaps; p.stride = a.stride;
@@ -385,7 +391,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     // one window's activation plane must fit a 32-bit byte offset (buffer descriptors)
     const long long r_out = (long long)a.r_in * (a.stride > 0 ? a.stride : 1);
     const long long max_in_bytes = (long long)a.max_len * a.r_in * a.cin * 2;
-    const long long max_out_bytes = (long long)a.max_len * r_out * a.cout * 4;
+    const long long max_out_bytes = (long long)a.max_len * r_out * a.cout * (long long)sizeof(hres_t);
     if (max_in_bytes > 0xf0000000ll || max_out_bytes > 0xf0000000ll) return hipErrorInvalidValue;
     // most columns any window needs: interior plus margins, never more than the longest window
     long long out_rows = std::min((long long)a.max_int * r_out + 2ll * a.margin, (long long)a.max_len * r_out);

@@ -24,7 +24,7 @@ constexpr int FUSED_MAXSPAN = 64;
 static const bool g_c64_tn1 = getenv("DEMON_VAE_C64_TN1") != nullptr;   // experiment: 128-column tiles for C = 64
 
 struct FusedParams {
-    const float* x; float* y;
+    const hres_t* x; hres_t* y;
     uint16_t* ya;                // optional activated bf16 copy of y (EMIT)
     const uint16_t* w7;          // [chunk][tap] blocks of C x 64 bf16
     const uint16_t* w1;          // [C][C] bf16, K axis permuted (see above)
@@ -95,18 +95,18 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     const int seg = tid % SEGS, xr0 = tid / SEGS;
 
     // descriptors: one window of the input, the computed part of the window for the outputs
-    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.x + rowbase * CH, (unsigned)nrows * CH * 4u);
-    const __amdgpu_buffer_rsrc_t rs_y = make_rsrc(p.y + rowbase * CH, (unsigned)out_hi * CH * 4u);
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.x + rowbase * CH, (unsigned)nrows * CH * (unsigned)sizeof(hres_t));
+    const __amdgpu_buffer_rsrc_t rs_y = make_rsrc(p.y + rowbase * CH, (unsigned)out_hi * CH * (unsigned)sizeof(hres_t));
     const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.ya + rowbase * CH, EMIT ? (unsigned)out_hi * CH * 2u : 0u);
     const __amdgpu_buffer_rsrc_t rs_w = make_rsrc(p.w7, (unsigned)(p.nchunks * p.ntaps) * (A_CH * 16u));
 
     const int nstages = p.nchunks * p.ntaps;
     const unsigned a_voff = tid * 16u;
-    const unsigned x_voff = ((unsigned)((n0 + minoff + xr0) * CH) + seg * 8u) * 4u;      // may wrap "negative": out of range
-    constexpr unsigned x_row_step = RPP * CH * 4u;
+    const unsigned x_voff = ((unsigned)((n0 + minoff + xr0) * CH) + seg * 8u) * (unsigned)sizeof(hres_t);   // may wrap "negative": out of range
+    constexpr unsigned x_row_step = RPP * CH * (unsigned)sizeof(hres_t);
 
     u32x4 ra[A_ITERS];
-    u32x4 rx[X_ITERS][2];
+    u32x4 rx[X_ITERS];           // 8 channels of one row (half)
     float al[8], ib[8];
 
     auto load_a = [&](int stage) __attribute__((always_inline)) {
@@ -122,13 +122,11 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
         }
     };
     auto load_x = [&](int chunk) __attribute__((always_inline)) {
-        const unsigned coff = x_voff + (unsigned)(chunk * KC) * 4u;
+        const unsigned coff = x_voff + (unsigned)(chunk * KC) * (unsigned)sizeof(hres_t);
 #pragma unroll
         for (int it = 0; it < X_ITERS; ++it) {
             if (it * RPP >= XR) break;                        // uniform
-            const unsigned off = coff + it * x_row_step;
-            rx[it][0] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, off, 0, 0);
-            rx[it][1] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, off + 16u, 0, 0);
+            rx[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, coff + it * x_row_step, 0, 0);
         }
         const int cbase = chunk * KC + seg * 8;
 #pragma unroll
@@ -141,9 +139,10 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
             const int xr = xr0 + it * RPP;
             if (xr >= XR_MAX) continue;
             u32x4 v;
+            const f16x8 hv = __builtin_bit_cast(f16x8, rx[it]);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                float e0 = __uint_as_float(rx[it][q >> 1][(2 * q) & 3]), e1 = __uint_as_float(rx[it][q >> 1][(2 * q + 1) & 3]);
+                float e0 = (float)hv[2 * q], e1 = (float)hv[2 * q + 1];
                 e0 = snake_fast(e0, al[2 * q], ib[2 * q]);
                 e1 = snake_fast(e1, al[2 * q + 1], ib[2 * q + 1]);
                 v[q] = (uint32_t)f32_to_bf16_bits(e0) | ((uint32_t)f32_to_bf16_bits(e1) << 16);
@@ -152,13 +151,19 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
         }
     };
 
+    // accumulators start at the bias: lane (j, h) holds rows (channels) mi*32 + 8g + 4h + {0..3}
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < TN; ++ni)
+        for (int g = 0; g < 4; ++g) {
+            const float4 b4 = *reinterpret_cast<const float4*>(p.b7 + mi * 32 + 8 * g + 4 * h);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+            for (int ni = 0; ni < TN; ++ni) {
+                acc[mi][ni][4 * g + 0] = b4.x; acc[mi][ni][4 * g + 1] = b4.y;
+                acc[mi][ni][4 * g + 2] = b4.z; acc[mi][ni][4 * g + 3] = b4.w;
+            }
+        }
 
     load_a(0);
     load_x(0);
@@ -221,15 +226,14 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int c = mi * 32 + 8 * g + 4 * h;
-            const float4 b4 = *reinterpret_cast<const float4*>(p.b7 + c);
             const float4 a4 = *reinterpret_cast<const float4*>(p.a2 + c);
             const float4 i4 = *reinterpret_cast<const float4*>(p.ib2 + c);
 #pragma unroll
             for (int ni = 0; ni < TN; ++ni) {
-                const float v0 = snake_fast(acc[mi][ni][4 * g + 0] + b4.x, a4.x, i4.x);
-                const float v1 = snake_fast(acc[mi][ni][4 * g + 1] + b4.y, a4.y, i4.y);
-                const float v2 = snake_fast(acc[mi][ni][4 * g + 2] + b4.z, a4.z, i4.z);
-                const float v3 = snake_fast(acc[mi][ni][4 * g + 3] + b4.w, a4.w, i4.w);
+                const float v0 = snake_fast(acc[mi][ni][4 * g + 0], a4.x, i4.x);
+                const float v1 = snake_fast(acc[mi][ni][4 * g + 1], a4.y, i4.y);
+                const float v2 = snake_fast(acc[mi][ni][4 * g + 2], a4.z, i4.z);
+                const float v3 = snake_fast(acc[mi][ni][4 * g + 3], a4.w, i4.w);
                 bf16x8& f = mid[2 * mi + g / 2][ni];
                 f[4 * (g & 1) + 0] = (__bf16)v0; f[4 * (g & 1) + 1] = (__bf16)v1;
                 f[4 * (g & 1) + 2] = (__bf16)v2; f[4 * (g & 1) + 3] = (__bf16)v3;
@@ -238,13 +242,18 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     }
     __syncthreads();
 
-    // ---- 1x1 conv: K = C channels straight from registers
+    // ---- 1x1 conv: K = C channels straight from registers; accumulators start at its bias
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < TN; ++ni)
+        for (int g = 0; g < 4; ++g) {
+            const float4 b4 = *reinterpret_cast<const float4*>(p.b1 + mi * 32 + 8 * g + 4 * h);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+            for (int ni = 0; ni < TN; ++ni) {
+                acc[mi][ni][4 * g + 0] = b4.x; acc[mi][ni][4 * g + 1] = b4.y;
+                acc[mi][ni][4 * g + 2] = b4.z; acc[mi][ni][4 * g + 3] = b4.w;
+            }
+        }
 #pragma unroll
     for (int kk = 0; kk < CH / 16; ++kk) {
         bf16x8 af[TM];
@@ -266,7 +275,6 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     constexpr int LPR = CH / 4;                        // lanes per row
     constexpr int RPI = 64 / LPR;                      // rows per instruction
     const int cl = lane % LPR, rl = lane / LPR;
-    const float4 b4 = *reinterpret_cast<const float4*>(p.b1 + 4 * cl);
     float4 a4 = make_float4(0, 0, 0, 0), i4 = a4;
     if (EMIT) {
         a4 = *reinterpret_cast<const float4*>(p.a3 + 4 * cl);
@@ -286,14 +294,12 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
             const float4 t4 = *reinterpret_cast<const float4*>(&stage[row * LDT + 4 * cl]);
             const int col = n0 + wn * WTN + ni * 32 + row;
             const unsigned e = (unsigned)(col * CH + 4 * cl);
-            const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rs_x, e * 4u, 0, 0);
-            float v0 = t4.x + b4.x + __uint_as_float(r[0]);
-            float v1 = t4.y + b4.y + __uint_as_float(r[1]);
-            float v2 = t4.z + b4.z + __uint_as_float(r[2]);
-            float v3 = t4.w + b4.w + __uint_as_float(r[3]);
-            const u32x4 st = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2), __float_as_uint(v3)};
-            __builtin_amdgcn_raw_buffer_store_b128(st, rs_y, e * 4u, 0, 0);
+            const float4 r = hres_load4(rs_x, e);
+            float v0 = t4.x + r.x, v1 = t4.y + r.y, v2 = t4.z + r.z, v3 = t4.w + r.w;
+            hres_store4(rs_y, e, v0, v1, v2, v3);
             if (EMIT) {
+                // the next layer's operand is Snake of the STORED value
+                v0 = hres_round(v0); v1 = hres_round(v1); v2 = hres_round(v2); v3 = hres_round(v3);
                 v0 = snake_fast(v0, a4.x, i4.x); v1 = snake_fast(v1, a4.y, i4.y);
                 v2 = snake_fast(v2, a4.z, i4.z); v3 = snake_fast(v3, a4.w, i4.w);
                 const u32x2 sh = {(uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16),
@@ -307,7 +313,7 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
 hipError_t launch_res_unit_fused(const FusedArgs& a, hipStream_t stream)
 {
     FusedParams p;
-    p.x = a.x; p.y = a.y; p.ya = a.ya; p.w7 = a.w7; p.w1 = a.w1; p.b7 = a.b7; p.b1 = a.b1;
+    p.x = (const hres_t*)a.x; p.y = (hres_t*)a.y; p.ya = a.ya; p.w7 = a.w7; p.w1 = a.w1; p.b7 = a.b7; p.b1 = a.b1;
     p.a1 = a.a1; p.ib1 = a.ib1; p.a2 = a.a2; p.ib2 = a.ib2; p.a3 = a.a3; p.ib3 = a.ib3;
     p.slots = a.slots; p.r = a.r; p.ntaps = a.ntaps;
     p.tap0 = -((a.ntaps - 1) / 2) * a.dil; p.tap_step = a.dil;
@@ -315,7 +321,7 @@ hipError_t launch_res_unit_fused(const FusedArgs& a, hipStream_t stream)
     if ((a.c != 64 && a.c != 128) || (a.ntaps - 1) * a.dil > FUSED_MAXSPAN || a.margin < 0 || a.x == a.y) return hipErrorInvalidValue;
     if (a.ya && (!a.a3 || !a.ib3)) return hipErrorInvalidValue;
     // one window's activation plane must fit a 32-bit byte offset (buffer descriptors)
-    if ((long long)a.max_len * a.r * a.c * 4 > 0xf0000000ll) return hipErrorInvalidValue;
+    if ((long long)a.max_len * a.r * a.c * (long long)sizeof(hres_t) > 0xf0000000ll) return hipErrorInvalidValue;
     const long long out_rows = std::min((long long)a.max_int * a.r + 2ll * a.margin, (long long)a.max_len * a.r);
     const bool emit = a.ya != nullptr;
     if (a.c == 64 && g_c64_tn1) {

@@ -12,6 +12,7 @@ namespace demon {
 template <typename T> __device__ __forceinline__ float load_act(const T* p);
 template <> __device__ __forceinline__ float load_act<float>(const float* p) { return *p; }
 template <> __device__ __forceinline__ float load_act<uint16_t>(const uint16_t* p) { return bf16_bits_to_f32(*p); }
+template <> __device__ __forceinline__ float load_act<_Float16>(const _Float16* p) { return (float)*p; }
 
 // ---------------------------------------------------------------------------------- gather
 template <typename T>
@@ -76,8 +77,8 @@ constexpr int HEAD_MAXK = 15;
 constexpr int HEAD_MAXOC = 8;
 constexpr int HEAD_LDR = 1044;                 // >= HEAD_NT + HEAD_MAXK - 1, = 4 (mod 16)
 
-template <bool FAST, int OC, int K>
-__global__ __launch_bounds__(256) void head_fast_kernel(const float* __restrict__ x, float* __restrict__ y,
+template <typename TX, bool FAST, int OC, int K>
+__global__ __launch_bounds__(256) void head_fast_kernel(const TX* __restrict__ x, float* __restrict__ y,
                                                         const float* __restrict__ w, const float* __restrict__ bias,
                                                         const float* __restrict__ alpha, const float* __restrict__ inv_beta,
                                                         int cin, int r, long long total_rows,
@@ -110,7 +111,13 @@ __global__ __launch_bounds__(256) void head_fast_kernel(const float* __restrict_
             const long long n = n0 - HALF + row;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (n >= 0 && n < nrows) {
-                v = *reinterpret_cast<const float4*>(x + (size_t)(rowbase + n) * cin + c0 + 4 * q);
+                const TX* src = x + (size_t)(rowbase + n) * cin + c0 + 4 * q;
+                if (sizeof(TX) == 4) {
+                    v = *reinterpret_cast<const float4*>(src);
+                } else {
+                    const f16x4 hv = *reinterpret_cast<const f16x4*>(src);
+                    v = make_float4((float)hv[0], (float)hv[1], (float)hv[2], (float)hv[3]);
+                }
                 if (FAST) {
                     v.x = snake_fast(v.x, al.x, ib.x); v.y = snake_fast(v.y, al.y, ib.y);
                     v.z = snake_fast(v.z, al.z, ib.z); v.w = snake_fast(v.w, al.w, ib.w);
@@ -164,8 +171,8 @@ __global__ __launch_bounds__(256) void head_fast_kernel(const float* __restrict_
 constexpr int HEADG_NT = 256;
 constexpr int HEADG_KC = 32;
 
-template <bool FAST>
-__global__ __launch_bounds__(256) void head_generic_kernel(const float* __restrict__ x, float* __restrict__ y,
+template <typename TX, bool FAST>
+__global__ __launch_bounds__(256) void head_generic_kernel(const TX* __restrict__ x, float* __restrict__ y,
                                                            const float* __restrict__ w, const float* __restrict__ bias,
                                                            const float* __restrict__ alpha, const float* __restrict__ inv_beta,
                                                            int cin, int oc, int k, int r, long long total_rows,
@@ -193,7 +200,7 @@ __global__ __launch_bounds__(256) void head_generic_kernel(const float* __restri
             const long long n = n0 - half + row;
             float v = 0.f;
             if (c < kc && n >= 0 && n < nrows) {
-                v = x[(size_t)(rowbase + n) * cin + c0 + c];
+                v = load_act<TX>(x + (size_t)(rowbase + n) * cin + c0 + c);
                 v = FAST ? snake_fast(v, alpha[c0 + c], inv_beta[c0 + c]) : snake_precise(v, alpha[c0 + c], inv_beta[c0 + c]);
             }
             xs[row * (HEADG_KC + 1) + c] = v;
@@ -218,25 +225,29 @@ __global__ __launch_bounds__(256) void head_generic_kernel(const float* __restri
     }
 }
 
-hipError_t launch_head(const float* x, float* y, const float* w, const float* bias, const float* alpha,
+hipError_t launch_head(const void* x, bool x_half, float* y, const float* w, const float* bias, const float* alpha,
                        const float* inv_beta, int cin, int oc, int k, int r, long long total_rows,
                        bool fast, const Slot* slots, int n_slots, int max_int, hipStream_t stream)
 {
-    if (k > HEAD_MAXK || oc > HEAD_MAXOC) return hipErrorInvalidValue;
+    if (k > HEAD_MAXK || oc > HEAD_MAXOC || (x_half && !fast)) return hipErrorInvalidValue;
     const long long rows = (long long)max_int * r;
     if (oc == 2 && k == 7 && cin % HEAD_KC == 0) {
         dim3 grid((unsigned)((rows + HEAD_NT - 1) / HEAD_NT), (unsigned)n_slots);
-        if (fast)
-            hipLaunchKernelGGL((head_fast_kernel<true, 2, 7>), grid, dim3(256), 0, stream, x, y, w, bias, alpha, inv_beta, cin, r, total_rows, slots);
+        if (x_half)
+            hipLaunchKernelGGL((head_fast_kernel<_Float16, true, 2, 7>), grid, dim3(256), 0, stream, (const _Float16*)x, y, w, bias, alpha, inv_beta, cin, r, total_rows, slots);
+        else if (fast)
+            hipLaunchKernelGGL((head_fast_kernel<float, true, 2, 7>), grid, dim3(256), 0, stream, (const float*)x, y, w, bias, alpha, inv_beta, cin, r, total_rows, slots);
         else
-            hipLaunchKernelGGL((head_fast_kernel<false, 2, 7>), grid, dim3(256), 0, stream, x, y, w, bias, alpha, inv_beta, cin, r, total_rows, slots);
+            hipLaunchKernelGGL((head_fast_kernel<float, false, 2, 7>), grid, dim3(256), 0, stream, (const float*)x, y, w, bias, alpha, inv_beta, cin, r, total_rows, slots);
         return hipGetLastError();
     }
     dim3 grid((unsigned)((rows + HEADG_NT - 1) / HEADG_NT), (unsigned)n_slots);
-    if (fast)
-        hipLaunchKernelGGL(head_generic_kernel<true>, grid, dim3(256), 0, stream, x, y, w, bias, alpha, inv_beta, cin, oc, k, r, total_rows, slots);
+    if (x_half)
+        hipLaunchKernelGGL((head_generic_kernel<_Float16, true>), grid, dim3(256), 0, stream, (const _Float16*)x, y, w, bias, alpha, inv_beta, cin, oc, k, r, total_rows, slots);
+    else if (fast)
+        hipLaunchKernelGGL((head_generic_kernel<float, true>), grid, dim3(256), 0, stream, (const float*)x, y, w, bias, alpha, inv_beta, cin, oc, k, r, total_rows, slots);
     else
-        hipLaunchKernelGGL(head_generic_kernel<false>, grid, dim3(256), 0, stream, x, y, w, bias, alpha, inv_beta, cin, oc, k, r, total_rows, slots);
+        hipLaunchKernelGGL((head_generic_kernel<float, false>), grid, dim3(256), 0, stream, (const float*)x, y, w, bias, alpha, inv_beta, cin, oc, k, r, total_rows, slots);
     return hipGetLastError();
 }
 
@@ -282,11 +293,12 @@ __global__ __launch_bounds__(256) void to_f32_kernel(const T* __restrict__ x, fl
     if (i < n) dst[i] = load_act<T>(x + i);
 }
 
-hipError_t launch_to_f32(const void* x, float* dst, size_t n, bool bf16, hipStream_t stream)
+hipError_t launch_to_f32(const void* x, float* dst, size_t n, int src_type, hipStream_t stream)
 {
     if (n == 0) return hipSuccess;
     dim3 grid((unsigned)((n + 255) / 256));
-    if (bf16) hipLaunchKernelGGL(to_f32_kernel<uint16_t>, grid, dim3(256), 0, stream, (const uint16_t*)x, dst, n);
+    if (src_type == 1) hipLaunchKernelGGL(to_f32_kernel<uint16_t>, grid, dim3(256), 0, stream, (const uint16_t*)x, dst, n);
+    else if (src_type == 2) hipLaunchKernelGGL(to_f32_kernel<_Float16>, grid, dim3(256), 0, stream, (const _Float16*)x, dst, n);
     else hipLaunchKernelGGL(to_f32_kernel<float>, grid, dim3(256), 0, stream, (const float*)x, dst, n);
     return hipGetLastError();
 }
