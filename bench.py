@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--workload", default="full_60s_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="add per-launch timings (one extra instrumented step)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
@@ -71,6 +73,13 @@ def main():
 
     def step():
         vae.decode_windowed(z, window=wl.window, halo=-1, out=out)
+
+    if args.calibration_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # 1 GiB read + 1 GiB written by one elementwise copy kernel
+        torch.cuda.synchronize()
+        del src, dst
 
     # group-level HIP events (5 per step, on the decode stream) stay on during the timed region
     vae.set_timing(1)

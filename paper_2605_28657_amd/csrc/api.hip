@@ -22,7 +22,8 @@ constexpr int kTimingRing = 32;        // decode calls whose events are kept for
 // operand rounding passes into the output at full strength, while the extra MFMA work is small
 // (these GEMMs have short K).
 constexpr int kSplitWidth = 512;
-// DEMON_VAE_NO_FUSED=1 in the environment keeps every residual unit on the two-kernel path (A/B timing).
+// DEMON_VAE_NO_FUSED=1 in the environment keeps every residual unit on the two-kernel path (A/B timing and
+// parity tests of the unfused kernels at 64 and 128 channels).
 const bool g_allow_fused = getenv("DEMON_VAE_NO_FUSED") == nullptr;
 
 struct ConvLayer {

@@ -50,6 +50,8 @@ struct MfmaParams {
     const float* out_alpha; const float* out_inv_beta;   // Snake applied before writing ya
     const Slot* slots;
     int r_in, cin, cout, ntaps, tap0, tap_step, stride, nchunks, margin;
+    int mtiles_x;            // > 0: blockIdx.x = column tile * mtiles_x + row tile (the row tiles of one column tile run
+                             // together and share its activation rows in L2); 0: blockIdx.z = row tile
     unsigned w_bytes;
     long long in_lo_off, out_lo_off;     // element offsets of the lo planes
 };
@@ -142,9 +144,11 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     // GEMM columns: output rows (conv) or input positions m whose s outputs m s - p .. m s - p + s - 1 touch them
     const int col_lo = (MODE == MODE_UP) ? (out_lo + p.stride / 2) / p.stride : out_lo;
     const int ncols = (MODE == MODE_UP) ? (out_hi - 1 + p.stride / 2) / p.stride + 1 : out_hi;
-    const int n0 = col_lo + blockIdx.x * NT;
+    const int mtile = p.mtiles_x > 0 ? (int)(blockIdx.x % (unsigned)p.mtiles_x) : (int)blockIdx.z;
+    const int ntile = p.mtiles_x > 0 ? (int)(blockIdx.x / (unsigned)p.mtiles_x) : (int)blockIdx.x;
+    const int n0 = col_lo + ntile * NT;
     if (n0 >= ncols) return;
-    const int m0 = blockIdx.z * MT;
+    const int m0 = mtile * MT;
     const long long rowbase = (long long)s.row0 * p.r_in;
     const long long rowbase_o = (long long)s.row0 * r_out;
 
@@ -164,7 +168,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     const __amdgpu_buffer_rsrc_t rs_xl = make_rsrc(p.xa + p.in_lo_off + rowbase * p.cin, SPLIT_IN ? (unsigned)nrows * p.cin * 2u : 0u);
 
     const int nstages = p.nchunks * p.ntaps;
-    const unsigned w_tile0 = (unsigned)blockIdx.z * nstages * (A_CH * 16u);
+    const unsigned w_tile0 = (unsigned)mtile * nstages * (A_CH * 16u);
     const unsigned a_voff = tid * 16u;
     const unsigned x_voff = ((unsigned)((n0 + minoff + xr0) * p.cin) + seg * 8u) * 2u;    // may wrap "negative": out of range
     const unsigned x_row_step = (unsigned)(RPP * p.cin) * 2u;
@@ -396,7 +400,14 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     // most columns any window needs: interior plus margins, never more than the longest window
     long long out_rows = std::min((long long)a.max_int * r_out + 2ll * a.margin, (long long)a.max_len * r_out);
     const long long ncols = a.stride > 0 ? out_rows / a.stride + 2 : out_rows;
-    dim3 grid((unsigned)((ncols + v.NT - 1) / v.NT), (unsigned)a.n_slots, (unsigned)(M / v.MT));
+    // Grid order: row tiles fastest, so that the row tiles of one column tile are in flight together and share
+    // its activation rows in L2 (measured: same time as column tiles fastest, about a third less L2 miss traffic);
+    // the weights are then re-read once per group of column tiles in flight, from L2 / Infinity Cache.
+    const long long ntiles = (ncols + v.NT - 1) / v.NT;
+    const int mtiles = M / v.MT;
+    const bool m_fastest = mtiles > 1 && ntiles * mtiles < 0x7fffffffll;
+    p.mtiles_x = m_fastest ? mtiles : 0;
+    dim3 grid(m_fastest ? (unsigned)(ntiles * mtiles) : (unsigned)ntiles, (unsigned)a.n_slots, m_fastest ? 1u : (unsigned)mtiles);
     switch (variant) {
         case 0: return launch_variant<128, 128, 64, 2, 2>(p, mode, a.split_in, emit, grid, stream);
         case 1: return launch_variant<64, 256, 64, 1, 4>(p, mode, a.split_in, emit, grid, stream);

@@ -12,8 +12,6 @@
 // 32 (kk/2) + 8 (2 (kk%2) + e/4) + 4 h + e%4.  The 1x1 weights are packed in that order at create.
 // The result is written to a second buffer (neighbouring tiles still read this tile's input rows).
 // With EMIT the kernel also writes bf16(snake_next(h_out)), the operand of the next (unfused) layer.
-#include <stdlib.h>
-
 #include <algorithm>
 
 #include "device_common.h"
@@ -21,7 +19,6 @@
 namespace demon {
 
 constexpr int FUSED_MAXSPAN = 64;
-static const bool g_c64_tn1 = getenv("DEMON_VAE_C64_TN1") != nullptr;   // experiment: 128-column tiles for C = 64
 
 struct FusedParams {
     const hres_t* x; hres_t* y;
@@ -152,6 +149,13 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     };
 
     // accumulators start at the bias: lane (j, h) holds rows (channels) mi*32 + 8g + 4h + {0..3}
+    u32x4 rw1[W1_CH / 256];      // the 1x1 weights on their way to LDS
+    auto load_w1 = [&]() __attribute__((always_inline)) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(p.w1);
+#pragma unroll
+        for (int it = 0; it < W1_CH / 256; ++it) rw1[it] = src[tid + it * 256];
+    };
+
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
@@ -179,6 +183,7 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
         const bool more = stage + 1 < nstages;
         const bool new_chunk = more && nchunk != chunk;
         if (more) load_a(stage + 1);
+        else load_w1();                            // last stage: its shadow hides the fetch of the 1x1 weights
         if (new_chunk) load_x(nchunk);
 
         const int off = p.tap0 + tap * p.tap_step - minoff;
@@ -210,13 +215,10 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
 
     // ---- stage the 1x1 weights into the (now free) weight buffers
     __syncthreads();
-    {
-        const u32x4* src = reinterpret_cast<const u32x4*>(p.w1);
 #pragma unroll
-        for (int it = 0; it < W1_CH / 256; ++it) {
-            const int q = tid + it * 256;
-            *reinterpret_cast<u32x4*>(&As[(q / (CH / 8)) * LD1 + (q % (CH / 8)) * 8]) = src[q];
-        }
+    for (int it = 0; it < W1_CH / 256; ++it) {
+        const int q = tid + it * 256;
+        *reinterpret_cast<u32x4*>(&As[(q / (CH / 8)) * LD1 + (q % (CH / 8)) * 8]) = rw1[it];
     }
 
     // ---- bias + Snake on the accumulators; repack them as the B fragments of the 1x1 conv
@@ -324,12 +326,7 @@ hipError_t launch_res_unit_fused(const FusedArgs& a, hipStream_t stream)
     if ((long long)a.max_len * a.r * a.c * (long long)sizeof(hres_t) > 0xf0000000ll) return hipErrorInvalidValue;
     const long long out_rows = std::min((long long)a.max_int * a.r + 2ll * a.margin, (long long)a.max_len * a.r);
     const bool emit = a.ya != nullptr;
-    if (a.c == 64 && g_c64_tn1) {
-        constexpr int NT = 4 * 32 * 1;
-        dim3 grid((unsigned)((out_rows + NT - 1) / NT), (unsigned)a.n_slots);
-        if (emit) hipLaunchKernelGGL((res_unit_fused_kernel<64, 1, true>), grid, dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL((res_unit_fused_kernel<64, 1, false>), grid, dim3(256), 0, stream, p);
-    } else if (a.c == 64) {
+    if (a.c == 64) {
         constexpr int NT = 4 * 32 * 2;
         dim3 grid((unsigned)((out_rows + NT - 1) / NT), (unsigned)a.n_slots);
         if (emit) hipLaunchKernelGGL((res_unit_fused_kernel<64, 2, true>), grid, dim3(256), 0, stream, p);
