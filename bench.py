@@ -20,6 +20,8 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# measured with rocprofv3 --pmc (see profiles/full_60s_bf16_hbm_traffic.txt); not collectable inside this process
+TRAFFIC_BYTES_PER_STEP = {"full_60s_bf16": None}
 
 
 def conv_flops_per_frame(spec):
@@ -114,19 +116,24 @@ def main():
                    "window": wl.window, "halo": halo, "n_windows": n_windows,
                    "strides": list(spec.strides), "widths": list(spec.widths)},
         "roofline": {
-            "kernel": "conv_mfma_kernel (all %d convolution launches of a step)" % n_conv_launches,
+            "kernel": "MFMA convolution kernels (conv_mfma_kernel + res_unit_fused_kernel: all convolution launches of a step, "
+                      "%d layers)" % n_conv_launches,
             "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-            "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
-            "flop_per_launch": conv_f * frames / n_conv_launches,
-            "avg_launch_ms": conv_ms / n_conv_launches,
+            "frac": achieved / PEAK_BF16_TFLOPS,
+            # L2 miss traffic of these kernels per step from rocprofv3 FETCH_SIZE + WRITE_SIZE (bytes, scaled by a plain
+            # copy; profiles/full_60s_bf16_hbm_traffic.txt); only measured for the 60 s workload
+            "traffic": TRAFFIC_BYTES_PER_STEP.get(args.workload),
+            "algorithmic_flop": conv_f * frames,
+            "time_ms": conv_ms,
         },
         "stage_ms": {"gather": float(groups[0]), "convolutions": conv_ms, "head": float(groups[2]),
                      "stitch": float(groups[3])},
     }
-    # HBM-bound kernels: algorithmic bytes = what must be read plus what must be written
-    ext_rows = ext * S
-    head_bytes = ext_rows * spec.widths[-1] * 4 + ext_rows * spec.out_channels * 4
-    stitch_bytes = 2 * frames * S * spec.out_channels * 4
+    # HBM-bound kernels: algorithmic bytes = what must be read plus what must be written.  The head reads the
+    # interior rows of the last residual stream (half precision on the bf16 path) once and writes the window waveforms.
+    rows = frames * S
+    head_bytes = rows * spec.widths[-1] * (2 if wl.bf16 else 4) + rows * spec.out_channels * 4
+    stitch_bytes = 2 * rows * spec.out_channels * 4
     result["hbm_kernels"] = {
         "head": {"GB/s": head_bytes / (groups[2] * 1e-3) / 1e9, "frac": head_bytes / (groups[2] * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "stitch": {"GB/s": stitch_bytes / (groups[3] * 1e-3) / 1e9, "frac": stitch_bytes / (groups[3] * 1e-3) / 1e9 / PEAK_HBM_GBS},

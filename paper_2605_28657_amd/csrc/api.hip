@@ -62,6 +62,7 @@ struct demon_vae {
     void* d_params = nullptr;          // one allocation: all packed weights, biases, Snake parameters
     std::vector<Block> blocks;
     const float* head_w = nullptr;  const float* head_bias = nullptr;
+    const uint16_t* head_wfrag = nullptr;   // bf16 path: half-precision MFMA fragments of the head weights (or nullptr)
     const float* head_alpha = nullptr;  const float* head_inv_beta = nullptr;
     int head_cin = 0;
 
@@ -349,6 +350,10 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
         }
     }
     const long long total_rows = plan->total_frames * r;
+    if (v->head_wfrag) {
+        HIP_TRY(launch_head_mfma(cur, v->head_out, v->head_wfrag, v->head_bias, v->head_alpha, v->head_inv_beta, v->head_cin,
+                                 v->st.out_channels, v->st.head_kernel, r, total_rows, slots, ns, ml, plan->max_int, stream), "head");
+    } else
     HIP_TRY(launch_head(cur, bf, v->head_out, v->head_w, v->head_bias, v->head_alpha, v->head_inv_beta, v->head_cin,
                         v->st.out_channels, v->st.head_kernel, r, total_rows, bf, slots, ns, plan->max_int, stream), "head");
     HIP_TRY(mark(1), "event");
@@ -492,6 +497,15 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
                 }
     }
     w += (size_t)oc * cin * hk;
+    size_t hwf = 0;
+    const bool head_mfma = bf && (cin == 64 || cin == 32) && head_mfma_frag_count(cin, hk) <= 40;
+    if (head_mfma) {
+        // from the bf16-rounded weights, like every other weight of this path
+        std::vector<float> wr((size_t)oc * cin * hk);
+        for (size_t i = 0; i < wr.size(); ++i) { const uint32_t u = (uint32_t)f32_to_bf16_rne((w - (size_t)oc * cin * hk)[i]) << 16; memcpy(&wr[i], &u, 4); }
+        hwf = ar.reserve(head_mfma_frag_count(cin, hk) * 64 * 16);
+        pack_head_mfma(wr.data(), cin, oc, hk, reinterpret_cast<uint16_t*>(ar.bytes.data() + hwf));
+    }
     const size_t hb = pack_floats(ar, w, oc);
     w += oc;
     v->head_cin = cin;
@@ -525,6 +539,7 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
     for (const FusedFix& f : fused_fix) f.U->w1_fused = reinterpret_cast<const uint16_t*>(base + f.off);
     v->head_alpha = fptr(hs.alpha); v->head_inv_beta = fptr(hs.inv_beta);
     v->head_w = fptr(hw); v->head_bias = fptr(hb);
+    if (head_mfma) v->head_wfrag = reinterpret_cast<const uint16_t*>(base + hwf);
 
     *out = v.release();
     return DEMON_OK;

@@ -117,6 +117,12 @@ hipError_t launch_head(const void* x, bool x_half, float* y, const float* w /*[k
                        const float* alpha, const float* inv_beta, int cin, int oc, int k, int r,
                        long long total_rows, bool fast, const Slot* slots, int n_slots, int max_int,
                        hipStream_t stream);
+// MFMA head of the bf16 path (cin 32 or 64, oc <= 32); weights packed by pack_head_mfma
+size_t head_mfma_frag_count(int cin, int k);          // 16-byte x 64-lane fragments
+void pack_head_mfma(const float* w /*[oc][cin][k]*/, int cin, int oc, int k, uint16_t* dst);
+hipError_t launch_head_mfma(const void* x, float* y, const uint16_t* wfrag, const float* bias, const float* alpha,
+                            const float* inv_beta, int cin, int oc, int k, int r, long long total_rows,
+                            const Slot* slots, int n_slots, int max_len, int max_int, hipStream_t stream);
 // crop + stitch: planar slot waveform -> d_out [n_clips, oc, n_frames*S]
 hipError_t launch_stitch(const float* y, float* out, int oc, int S, int n_frames, long long total_rows,
                          const Slot* slots, int n_slots, int max_int, hipStream_t stream);

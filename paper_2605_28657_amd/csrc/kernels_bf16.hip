@@ -113,7 +113,9 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
 {
     constexpr int NTH = 64 * WM * WN;           // threads per workgroup
     constexpr int LDK = KC + 8;                 // padded LDS row (bf16 elements): 16-byte multiple, bank-spread
-    constexpr int XR_MAX = NT + MAXSPAN;
+    // rows of the activation tile: the dilated conv reaches MAXSPAN rows past its NT columns, the 1x1 conv
+    // none and the transposed conv one; a smaller tile lets two workgroups share a CU also with split operands
+    constexpr int XR_MAX = NT + (MODE == MODE_ACT ? MAXSPAN : 8);
     constexpr int WTM = MT / WM, WTN = NT / WN; // tile of one wave
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int SEGS = KC / 8;                // 16-byte segments per row
@@ -387,7 +389,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     const int emit = a.ya ? (a.split_out ? 2 : 1) : 0;
     const int span = (a.ntaps - 1) * (a.stride > 0 ? 1 : a.dil);
     // shape checks: everything the kernel's indexing assumes
-    if (span > MAXSPAN || M % v.MT != 0 || a.cin % v.KC != 0 || a.cout % 4 != 0 || a.margin < 0) return hipErrorInvalidValue;
+    if (span > (mode == MODE_ACT ? MAXSPAN : 8) || M % v.MT != 0 || a.cin % v.KC != 0 || a.cout % 4 != 0 || a.margin < 0) return hipErrorInvalidValue;
     if (mode == MODE_ACT && emit == 0) return hipErrorInvalidValue;
     if (emit > 0 && (!a.out_alpha || !a.out_inv_beta)) return hipErrorInvalidValue;
     if (mode != MODE_ACT && !a.y) return hipErrorInvalidValue;

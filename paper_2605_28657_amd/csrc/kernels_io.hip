@@ -225,6 +225,144 @@ __global__ __launch_bounds__(256) void head_generic_kernel(const TX* __restrict_
     }
 }
 
+// MFMA head for the bf16 path (half-precision residual stream in, out_channels <= 32).
+// GEMM with rows = time, columns = output channel (padded to 32), K = (tap, channel):
+//     D[n, o] = sum_t sum_c snake(h[n + t - (K-1)/2, c]) W[o, c, t]
+// on v_mfma_f32_32x32x16_f16: operands in IEEE half (their rounding is an order of magnitude below that of
+// the bf16 operands elsewhere), fp32 accumulation.  The A operand is the activation tile: whole 128-byte
+// rows are read once from HBM, Snake is applied in fp32, the tile sits row-major in LDS and a tap is a row
+// offset.  The B operand (the weights, zero beyond out_channels) is packed at create in fragment order and
+// staged into LDS once per workgroup.  A lane with column index < out_channels holds the results.
+constexpr int HM_NT = 256;                     // rows per sub-tile: 4 waves x 64 rows
+constexpr int HM_SUB = 4;                      // sub-tiles per workgroup (the weights are staged once)
+constexpr int HM_MAXFRAG = 40;                 // taps * channels / 16
+
+size_t head_mfma_frag_count(int cin, int k) { return (size_t)k * (cin / 16); }
+
+// [tap][k-step][lane][8]: lane (j, h) of k-step ks holds W[o = j][c = 16 ks + 8 h + e][tap], e = 0..7
+void pack_head_mfma(const float* w /*[oc][cin][k]*/, int cin, int oc, int k, uint16_t* dst)
+{
+    size_t pos = 0;
+    for (int t = 0; t < k; ++t)
+        for (int ks = 0; ks < cin / 16; ++ks)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int e = 0; e < 8; ++e) {
+                    const int j = lane & 31, h = lane >> 5, c = 16 * ks + 8 * h + e;
+                    const _Float16 v = (j < oc) ? (_Float16)w[((size_t)j * cin + c) * k + t] : (_Float16)0.f;
+                    uint16_t bits;
+                    __builtin_memcpy(&bits, &v, 2);
+                    dst[pos++] = bits;
+                }
+}
+
+typedef _Float16 f16x8v __attribute__((ext_vector_type(8)));
+
+template <int CIN>
+__global__ __launch_bounds__(256) void head_mfma_kernel(const _Float16* __restrict__ x, float* __restrict__ y,
+                                                        const uint16_t* __restrict__ wfrag, const float* __restrict__ bias,
+                                                        const float* __restrict__ alpha, const float* __restrict__ inv_beta,
+                                                        int oc, int k, int r, long long total_rows,
+                                                        const Slot* __restrict__ slots)
+{
+    constexpr int LDX = CIN + 8;                           // padded LDS row (halfs)
+    constexpr int XR_MAX = HM_NT + HEAD_MAXK - 1;
+    constexpr int SEGS = CIN / 8, RPP = 256 / SEGS;
+    constexpr int X_ITERS = (XR_MAX + RPP - 1) / RPP;
+    constexpr int KS = CIN / 16;
+    __shared__ __attribute__((aligned(16))) _Float16 Xs[XR_MAX * LDX];
+    __shared__ __attribute__((aligned(16))) uint16_t Ws[HM_MAXFRAG * 64 * 8];
+
+    const Slot s = slots[blockIdx.y];
+    const int nrows = s.len * r;
+    const int lo = s.crop * r, hi = (s.crop + s.n_int) * r;
+    const int half = (k - 1) / 2;
+    const int XR = HM_NT + k - 1;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, j = lane & 31, h = lane >> 5;
+    const int seg = tid % SEGS, xr0 = tid / SEGS;
+    const long long rowbase = (long long)s.row0 * r;
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(x + rowbase * CIN, (unsigned)nrows * CIN * 2u);
+    if (lo + (int)blockIdx.x * (HM_NT * HM_SUB) >= hi) return;
+
+    // weights -> LDS once
+    {
+        const u32x4* src = reinterpret_cast<const u32x4*>(wfrag);
+        for (int q = tid; q < k * KS * 64; q += 256) reinterpret_cast<u32x4*>(Ws)[q] = src[q];
+    }
+    float al[8], ib[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { al[e] = alpha[seg * 8 + e]; ib[e] = inv_beta[seg * 8 + e]; }
+    const float b = (j < oc) ? bias[j] : 0.f;
+
+    for (int sub = 0; sub < HM_SUB; ++sub) {
+        const int n0 = lo + ((int)blockIdx.x * HM_SUB + sub) * HM_NT;
+        if (n0 >= hi) break;                                   // uniform
+        __syncthreads();                                       // the previous sub-tile's reads are done
+#pragma unroll
+        for (int it = 0; it < X_ITERS; ++it) {
+            const int xr = xr0 + it * RPP;
+            if (it * RPP >= XR) break;                         // uniform
+            if (xr >= XR_MAX) continue;
+            // rows outside the window are out of range of the descriptor: zero = the conv's zero padding
+            const unsigned off = (unsigned)((n0 - half + xr) * CIN + seg * 8) * 2u;
+            const u32x4 raw = __builtin_amdgcn_raw_buffer_load_b128(rs_x, off, 0, 0);
+            const f16x8v hv = __builtin_bit_cast(f16x8v, raw);
+            f16x8v ov;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ov[e] = (_Float16)snake_fast((float)hv[e], al[e], ib[e]);
+            *reinterpret_cast<f16x8v*>(&Xs[xr * LDX + seg * 8]) = ov;
+        }
+        __syncthreads();
+
+        f32x16 acc[2];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[mi][q] = b;
+        for (int t = 0; t < k; ++t) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const f16x8v bw = *reinterpret_cast<const f16x8v*>(&Ws[((t * KS + ks) * 64 + lane) * 8]);
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) {
+                    const f16x8v av = *reinterpret_cast<const f16x8v*>(&Xs[(wave * 64 + mi * 32 + j + t) * LDX + ks * 16 + h * 8]);
+                    acc[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bw, acc[mi], 0, 0, 0);
+                }
+            }
+        }
+        // lane (j, h) holds output channel j, rows 8g + 4h + {0..3}
+        if (j < oc) {
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n0 + wave * 64 + mi * 32 + 8 * g + 4 * h;
+                    float* dst = y + (size_t)j * total_rows + rowbase + n;
+                    if (n + 4 <= hi && (r % 4) == 0) {
+                        *reinterpret_cast<float4*>(dst) = make_float4(tanhf(acc[mi][4 * g + 0]), tanhf(acc[mi][4 * g + 1]),
+                                                                      tanhf(acc[mi][4 * g + 2]), tanhf(acc[mi][4 * g + 3]));
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            if (n + q < hi) dst[q] = tanhf(acc[mi][4 * g + q]);
+                    }
+                }
+        }
+    }
+}
+
+hipError_t launch_head_mfma(const void* x, float* y, const uint16_t* wfrag, const float* bias, const float* alpha,
+                            const float* inv_beta, int cin, int oc, int k, int r, long long total_rows,
+                            const Slot* slots, int n_slots, int max_len, int max_int, hipStream_t stream)
+{
+    if (oc > 32 || k > HEAD_MAXK || (cin != 64 && cin != 32) || head_mfma_frag_count(cin, k) > HM_MAXFRAG) return hipErrorInvalidValue;
+    if ((long long)max_len * r * cin * 2 > 0xf0000000ll) return hipErrorInvalidValue;
+    const long long rows = (long long)max_int * r;
+    dim3 grid((unsigned)((rows + HM_NT * HM_SUB - 1) / (HM_NT * HM_SUB)), (unsigned)n_slots);
+    if (cin == 64) hipLaunchKernelGGL(head_mfma_kernel<64>, grid, dim3(256), 0, stream, (const _Float16*)x, y, wfrag, bias, alpha, inv_beta, oc, k, r, total_rows, slots);
+    else hipLaunchKernelGGL(head_mfma_kernel<32>, grid, dim3(256), 0, stream, (const _Float16*)x, y, wfrag, bias, alpha, inv_beta, oc, k, r, total_rows, slots);
+    return hipGetLastError();
+}
+
 hipError_t launch_head(const void* x, bool x_half, float* y, const float* w, const float* bias, const float* alpha,
                        const float* inv_beta, int cin, int oc, int k, int r, long long total_rows,
                        bool fast, const Slot* slots, int n_slots, int max_int, hipStream_t stream)

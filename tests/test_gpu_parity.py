@@ -214,3 +214,31 @@ def test_workspace_and_argument_errors():
     vae.decode(zt, out=out)
     torch.cuda.synchronize()
     vae.close()
+
+
+def test_unfused_kernels_for_64_and_128_channels_in_a_subprocess():
+    """DEMON_VAE_NO_FUSED=1 (read when the library loads) keeps the 64- and 128-channel residual units on the
+    two-kernel path; same parity bar, and bit-identical windowed == full there too."""
+    import os
+    import subprocess
+    import sys
+    code = r'''
+import sys, os
+sys.path.insert(0, os.path.join(os.getcwd(), "tests")); sys.path.insert(0, os.getcwd())
+import numpy as np
+import demon_inputs as di, oracle
+from gpu_util import make, to_device, assert_close
+for spec, T in ((di.DecoderSpec(64, (2,), (128,), (1, 3, 9)), 150), (di.DecoderSpec(64, (4,), (64,), (1, 3, 9)), 150)):
+    vae, w, z = make(spec, "bf16", T, snake="uniform", max_extended_frames=8 * T)
+    zt = to_device(z, "bf16")
+    full = vae.decode(zt).cpu().numpy()
+    win = vae.decode_windowed(zt, window=37, halo=-1).cpu().numpy()
+    assert_close(full, oracle.decode(spec, w, z), "bf16", "unfused")
+    assert np.array_equal(win, full)
+    vae.close()
+print("ok")
+'''
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, DEMON_VAE_NO_FUSED="1")
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=240)
+    assert r.returncode == 0 and "ok" in r.stdout, r.stdout + r.stderr
