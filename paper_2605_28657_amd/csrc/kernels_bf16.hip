@@ -50,8 +50,8 @@ struct MfmaParams {
     const float* out_alpha; const float* out_inv_beta;   // Snake applied before writing ya
     const Slot* slots;
     int r_in, cin, cout, ntaps, tap0, tap_step, stride, nchunks, margin;
-    int mtiles_x;            // > 0: blockIdx.x = column tile * mtiles_x + row tile (the row tiles of one column tile run
-                             // together and share its activation rows in L2); 0: blockIdx.z = row tile
+    int mtiles_x;            // > 0: blockIdx.x enumerates (column tile, row tile), see the kernel; 0: blockIdx.z = row tile
+    int xcd_group;           // with mtiles_x: 1 = all row tiles of a column tile on one XCD, 0 = row tiles dealt over the XCDs
     unsigned w_bytes;
     long long in_lo_off, out_lo_off;     // element offsets of the lo planes
 };
@@ -146,8 +146,20 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     // GEMM columns: output rows (conv) or input positions m whose s outputs m s - p .. m s - p + s - 1 touch them
     const int col_lo = (MODE == MODE_UP) ? (out_lo + p.stride / 2) / p.stride : out_lo;
     const int ncols = (MODE == MODE_UP) ? (out_hi - 1 + p.stride / 2) / p.stride + 1 : out_hi;
-    const int mtile = p.mtiles_x > 0 ? (int)(blockIdx.x % (unsigned)p.mtiles_x) : (int)blockIdx.z;
-    const int ntile = p.mtiles_x > 0 ? (int)(blockIdx.x / (unsigned)p.mtiles_x) : (int)blockIdx.x;
+    // Workgroups are dealt to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  All row tiles
+    // of a column tile read the same activation rows, so they get ids that are equal mod 8 and adjacent in
+    // dispatch order: id = 8 * ((column tile / 8) * mtiles + row tile) + column tile % 8.
+    // (With xcd_group = 0 the id is column tile * mtiles + row tile: XCD x then only ever touches the row tiles
+    // = x mod 8, one eighth of a weight matrix too large for one L2, and reads every activation row once.)
+    int mtile = (int)blockIdx.z, ntile = (int)blockIdx.x;
+    if (p.mtiles_x > 0 && p.xcd_group) {
+        const unsigned q = blockIdx.x >> 3;
+        mtile = (int)(q % (unsigned)p.mtiles_x);
+        ntile = (int)(q / (unsigned)p.mtiles_x) * 8 + (int)(blockIdx.x & 7u);
+    } else if (p.mtiles_x > 0) {
+        mtile = (int)(blockIdx.x % (unsigned)p.mtiles_x);
+        ntile = (int)(blockIdx.x / (unsigned)p.mtiles_x);
+    }
     const int n0 = col_lo + ntile * NT;
     if (n0 >= ncols) return;
     const int m0 = mtile * MT;
@@ -402,14 +414,20 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     // most columns any window needs: interior plus margins, never more than the longest window
     long long out_rows = std::min((long long)a.max_int * r_out + 2ll * a.margin, (long long)a.max_len * r_out);
     const long long ncols = a.stride > 0 ? out_rows / a.stride + 2 : out_rows;
-    // Grid order: row tiles fastest, so that the row tiles of one column tile are in flight together and share
-    // its activation rows in L2 (measured: same time as column tiles fastest, about a third less L2 miss traffic);
-    // the weights are then re-read once per group of column tiles in flight, from L2 / Infinity Cache.
+    // Grid order (L2 miss traffic; X = activation bytes, W = weight bytes, 8 XCDs with 4 MB of L2 each).
+    //  * W fits one L2: the row tiles of a column tile go to the same XCD, adjacent in dispatch order; they share
+    //    its activation rows in that L2 and the weights stay resident: about X + 8 W.
+    //  * W larger, more than 8 row tiles: ids run over row tiles first, so XCD x owns the row tiles = x mod 8 (an
+    //    eighth of W, resident) and reads all activations: about 8 X + W.
+    //  * else column tiles fastest (blockIdx.x): workgroups in flight share one row tile of the weights: mtiles X + W.
     const long long ntiles = (ncols + v.NT - 1) / v.NT;
     const int mtiles = M / v.MT;
-    const bool m_fastest = mtiles > 1 && ntiles * mtiles < 0x7fffffffll;
+    const long long ntiles8 = (ntiles + 7) / 8 * 8;           // whole groups of 8 column tiles; the surplus exits at once
+    const bool w_fits_l2 = wb <= (4u << 20);
+    const bool m_fastest = mtiles > 1 && ntiles8 * mtiles < 0x7fffffffll && (w_fits_l2 || mtiles > 8);
     p.mtiles_x = m_fastest ? mtiles : 0;
-    dim3 grid(m_fastest ? (unsigned)(ntiles * mtiles) : (unsigned)ntiles, (unsigned)a.n_slots, m_fastest ? 1u : (unsigned)mtiles);
+    p.xcd_group = w_fits_l2 ? 1 : 0;
+    dim3 grid(m_fastest ? (unsigned)(ntiles8 * mtiles) : (unsigned)ntiles, (unsigned)a.n_slots, m_fastest ? 1u : (unsigned)mtiles);
     switch (variant) {
         case 0: return launch_variant<128, 128, 64, 2, 2>(p, mode, a.split_in, emit, grid, stream);
         case 1: return launch_variant<64, 256, 64, 1, 4>(p, mode, a.split_in, emit, grid, stream);
