@@ -155,7 +155,8 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     if (p.mtiles_x > 0 && p.xcd_group) {
         const unsigned q = blockIdx.x >> 3;
         mtile = (int)(q % (unsigned)p.mtiles_x);
-        ntile = (int)(q / (unsigned)p.mtiles_x) * 8 + (int)(blockIdx.x & 7u);
+        // ... rotated by the window index, so that windows with fewer than 8 column tiles still use all XCDs
+        ntile = (int)(q / (unsigned)p.mtiles_x) * 8 + (int)((blockIdx.x - blockIdx.y) & 7u);
     } else if (p.mtiles_x > 0) {
         mtile = (int)(blockIdx.x % (unsigned)p.mtiles_x);
         ntile = (int)(blockIdx.x / (unsigned)p.mtiles_x);
