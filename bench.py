@@ -153,6 +153,39 @@ def main():
         result["launch_ms"] = dict(zip(names, [round(x, 4) for x in t]))
     vae.set_timing(0)
 
+    # Latency of re-decoding one playback window (3 s = 75 latent frames in the middle of the clip, analytic halo)
+    # into the resident waveform buffer: the call the paper's 8x windowed-decode figure is about (section 3.6).
+    pw = min(75, wl.n_frames)
+    pb = max(0, (wl.n_frames - pw) // 2)
+    for _ in range(3):
+        vae.decode_windowed(z, window=pw, halo=-1, frame_begin=pb, frame_end=pb + pw, out=out)
+    torch.cuda.synchronize()
+    reps = 50
+    p0 = time.perf_counter()
+    for _ in range(reps):
+        vae.decode_windowed(z, window=pw, halo=-1, frame_begin=pb, frame_end=pb + pw, out=out)
+    torch.cuda.synchronize()
+    pw_ms = (time.perf_counter() - p0) * 1e3 / reps
+    result["playback_window"] = {"frames": pw, "audio_s": pw / 25.0, "ms": pw_ms,
+                                 "speedup_vs_whole_clip_decode": ms_per_step / wl.n_clips / pw_ms}
+
+    # the two small kernels around the playback-window decode: similarity gate on the whole latent, 50 ms crossfade
+    import paper_2605_28657_amd as pa
+    z_prev = z.clone()
+    tail = out[0, :, :2400]
+    headv = out[0, :, 2400:4800]
+    xf = torch.empty((spec.out_channels, 2400), dtype=torch.float32, device="cuda:0")
+    small = {}
+    for name, fn in (("similarity_filter", lambda: pa.latent_similarity(z, z_prev, 1e-3)),
+                     ("crossfade_50ms", lambda: pa.crossfade(tail, headv, out=xf))):
+        fn(); torch.cuda.synchronize()
+        q0 = time.perf_counter()
+        for _ in range(200):
+            fn()
+        torch.cuda.synchronize()
+        small[name + "_ms"] = (time.perf_counter() - q0) * 1e3 / 200
+    result["playback_window"].update(small)
+
     if not args.no_cpu_baseline:
         # The oracle (fp32 build, as it stands) on a bounded sample: the first windows with their halo.
         import oracle

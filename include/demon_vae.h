@@ -24,6 +24,7 @@
 #define DEMON_VAE_H
 
 #include <stddef.h>
+#include <stdint.h>
 
 #ifdef __cplusplus
 extern "C" {
@@ -154,6 +155,45 @@ demon_status demon_vae_decode(demon_vae* vae, const void* d_latent, int n_clips,
 demon_status demon_vae_decode_windowed(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
                                        int frame_begin, int frame_end, int window, int halo,
                                        float* d_out, void* stream);
+
+/*
+ * The same windowed decode with the 16-bit render fused into the stitch (section 3.6 states its
+ * exactness criterion on the 16-bit PCM render).  Each sample is quantised in fp32 as
+ * q = rint(32767 * clamp(y, -1, 1)), ties to even, and written channel-interleaved:
+ *   d_pcm : device, int16, [n_clips, n_frames * S, out_channels]; only samples
+ *           [frame_begin*S, frame_end*S) of every clip are written.
+ * All other arguments, limits and errors as for demon_vae_decode_windowed.
+ */
+demon_status demon_vae_decode_windowed_pcm16(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
+                                             int frame_begin, int frame_end, int window, int halo,
+                                             int16_t* d_pcm, void* stream);
+
+/*
+ * Latent similarity filter (section 3.5): per clip, mse = mean over all elements of
+ * (curr - prev)^2, accumulated in double precision in a fixed order and rounded to fp32;
+ * unchanged = (mse < threshold).  The paper's threshold is 1e-3.  A caller that finds
+ * unchanged != 0 skips the decode of that clip and keeps the previous waveform.
+ *   d_curr, d_prev : device, [n_clips, elems_per_clip] (any channel/frame order, the same in both);
+ *                    fp32 for DEMON_F32, bf16 for DEMON_BF16.  Read only.
+ *   d_mse          : device, fp32 [n_clips], or NULL.
+ *   d_unchanged    : device, int [n_clips] (1 = below threshold), or NULL.  Not both NULL.
+ * No handle and no workspace are needed.  INVALID_ARG: null pointers, n_clips outside [1, 65535],
+ * elems_per_clip < 1, unknown dtype, threshold negative or NaN.
+ */
+demon_status demon_vae_latent_similarity(const void* d_curr, const void* d_prev, int n_clips, long long elems_per_clip,
+                                         demon_dtype dtype, float threshold, float* d_mse, int* d_unchanged, void* stream);
+
+/*
+ * Equal-power crossfade of a chunk boundary of the playback stream (the paper crossfades each
+ * decoded chunk into the output stream and names a 50 ms equal-power fade, 2400 samples at 48 kHz):
+ *   d_out[c][i] = cos(t_i) * d_prev_tail[c][i] + sin(t_i) * d_next_head[c][i],  t_i = (pi/2)(i + 1/2)/n_samples
+ * for planes c < n_planes, samples i < n_samples; plane c of a buffer starts c * stride floats after
+ * its pointer, so the segments may lie inside larger planar waveforms.  All device, fp32.  d_out may
+ * alias either input exactly (same pointer and stride).  INVALID_ARG: null pointers, n_planes outside
+ * [1, 65535], n_samples < 1, a negative stride, or output planes that overlap.
+ */
+demon_status demon_vae_crossfade(const float* d_prev_tail, long long prev_stride, const float* d_next_head, long long next_stride,
+                                 float* d_out, long long out_stride, int n_planes, int n_samples, void* stream);
 
 /*
  * Test aid: after the next decode calls, copy the activation produced by layer `layer` (0-based

@@ -4,4 +4,5 @@ Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
 package; it shares no code with the HIP library and never calls it.
 """
 from .oracle import (conv1d, convT1d, snake, decode, decode_windowed, window_grid,  # noqa: F401
-                     receptive_field, backward_interval, forward_interval, omp_threads)
+                     receptive_field, backward_interval, forward_interval, omp_threads, pcm16,
+                     latent_mse, latent_unchanged, crossfade)

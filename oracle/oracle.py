@@ -185,3 +185,43 @@ def receptive_field(spec) -> Tuple[int, int]:
     f = 1000                                   # any frame; the stack is shift-invariant
     lo, hi = backward_interval(spec, f * S, (f + 1) * S - 1)
     return f - lo, hi - f
+
+
+def pcm16(y, dtype=np.float32):
+    """16-bit render of a planar waveform y [channels, samples] -> int16 [samples, channels] (interleaved).
+
+    Section 3.6 judges the windowed decode on its 16-bit PCM render.  The paper does not print the quantiser;
+    the reading taken here is the symmetric one, q = round_half_even(32767 * clamp(y, -1, 1)), evaluated in
+    single precision by default because the product's rounding decides the integer.
+    """
+    y = np.asarray(y).astype(dtype)
+    v = np.clip(y, dtype(-1), dtype(1)) * dtype(32767)
+    return np.rint(v).astype(np.int16).T.copy()
+
+
+def latent_mse(curr, prev):
+    """Mean squared difference of two latents of equal shape, in double precision: the quantity the latent
+    similarity filter (section 3.5) compares with its threshold."""
+    a = np.asarray(curr, dtype=np.float64)
+    b = np.asarray(prev, dtype=np.float64)
+    assert a.shape == b.shape and a.size > 0
+    d = a - b
+    return float(np.sum(d * d) / d.size)
+
+
+def latent_unchanged(curr, prev, threshold=1e-3):
+    """Gate of the similarity filter: True means the decode is skipped and the previous audio is reused."""
+    return latent_mse(curr, prev) < threshold
+
+
+def crossfade(prev_tail, next_head):
+    """Equal-power crossfade of two [channels, N] segments that overlap in time (the chunk boundary of the
+    playback stream; the paper names a 50 ms equal-power crossfade without printing the gain curve).  Reading
+    taken here: quarter-sine gains sampled at the sample midpoints, theta_n = (pi/2)(n + 1/2)/N,
+    out = cos(theta) * prev_tail + sin(theta) * next_head, so that the squared gains sum to one everywhere."""
+    a = np.asarray(prev_tail, dtype=np.float64)
+    b = np.asarray(next_head, dtype=np.float64)
+    assert a.shape == b.shape and a.ndim == 2
+    n = a.shape[1]
+    theta = (np.pi / 2) * (np.arange(n) + 0.5) / n
+    return np.cos(theta)[None, :] * a + np.sin(theta)[None, :] * b

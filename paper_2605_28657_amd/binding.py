@@ -65,6 +65,11 @@ def load_library() -> ctypes.CDLL:
     lib.demon_vae_receptive_field.argtypes = [ctypes.c_void_p, P(ctypes.c_int), P(ctypes.c_int)]
     lib.demon_vae_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     lib.demon_vae_decode_windowed.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 6 + [ctypes.c_void_p, ctypes.c_void_p]
+    lib.demon_vae_decode_windowed_pcm16.argtypes = lib.demon_vae_decode_windowed.argtypes
+    lib.demon_vae_latent_similarity.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_int,
+                                                ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.demon_vae_crossfade.argtypes = [ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p, ctypes.c_longlong,
+                                        ctypes.c_void_p, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     lib.demon_vae_debug_tap.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t]
     lib.demon_vae_set_timing.argtypes = [ctypes.c_void_p, ctypes.c_int]
     lib.demon_vae_get_timing.argtypes = [ctypes.c_void_p, P(ctypes.c_float), ctypes.c_int, P(ctypes.c_int)]
@@ -166,6 +171,59 @@ def demon_vae_decode_windowed(handle: int, d_latent: int, n_clips: int, n_frames
                                                     window, halo, d_out, stream))
 
 
+def demon_vae_decode_windowed_pcm16(handle: int, d_latent: int, n_clips: int, n_frames: int, frame_begin: int,
+                                    frame_end: int, window: int, halo: int, d_pcm: int, stream: int = 0):
+    _check(load_library().demon_vae_decode_windowed_pcm16(handle, d_latent, n_clips, n_frames, frame_begin,
+                                                          frame_end, window, halo, d_pcm, stream))
+
+
+def demon_vae_latent_similarity(d_curr: int, d_prev: int, n_clips: int, elems_per_clip: int, dtype: int,
+                                threshold: float, d_mse: int, d_unchanged: int, stream: int = 0):
+    _check(load_library().demon_vae_latent_similarity(d_curr, d_prev, n_clips, elems_per_clip, dtype, threshold,
+                                                      d_mse, d_unchanged, stream))
+
+
+def demon_vae_crossfade(d_prev_tail: int, prev_stride: int, d_next_head: int, next_stride: int, d_out: int,
+                        out_stride: int, n_planes: int, n_samples: int, stream: int = 0):
+    _check(load_library().demon_vae_crossfade(d_prev_tail, prev_stride, d_next_head, next_stride, d_out, out_stride,
+                                              n_planes, n_samples, stream))
+
+
+def latent_similarity(curr, prev, threshold: float = 1e-3):
+    """(mse, unchanged) device tensors of shape [n_clips] for two latents [n_clips, C, T] (or [C, T])."""
+    import torch
+    if curr.dim() == 2:
+        curr, prev = curr[None], prev[None]
+    assert curr.is_cuda and prev.is_cuda and curr.shape == prev.shape and curr.dtype == prev.dtype
+    assert curr.is_contiguous() and prev.is_contiguous()
+    dtype = {torch.bfloat16: DEMON_BF16, torch.float32: DEMON_F32}[curr.dtype]
+    n = curr.shape[0]
+    mse = torch.empty(n, dtype=torch.float32, device=curr.device)
+    flag = torch.empty(n, dtype=torch.int32, device=curr.device)
+    demon_vae_latent_similarity(curr.data_ptr(), prev.data_ptr(), n, curr[0].numel(), dtype, threshold,
+                                mse.data_ptr(), flag.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    return mse, flag
+
+
+def crossfade(prev_tail, next_head, out=None):
+    """Equal-power crossfade of two fp32 device tensors [..., n]; the last dimension must be contiguous and the
+    leading dimensions must collapse to one plane stride (views into planar waveforms are fine)."""
+    import torch
+
+    def planes(t):
+        t2 = t.reshape(-1, t.shape[-1]) if t.is_contiguous() else t
+        assert t2.dim() == 2 and t2.stride(1) == 1 and t2.dtype == torch.float32 and t2.is_cuda
+        return t2
+
+    if out is None:
+        out = torch.empty(prev_tail.shape, dtype=torch.float32, device=prev_tail.device)
+    a, b, o = planes(prev_tail), planes(next_head), planes(out)
+    assert a.shape == b.shape == o.shape
+    demon_vae_crossfade(a.data_ptr(), a.stride(0), b.data_ptr(), b.stride(0), o.data_ptr(), o.stride(0),
+                        a.shape[0], a.shape[1], torch.cuda.current_stream().cuda_stream)
+    return out
+
+
 def demon_vae_debug_tap(handle: int, layer: int, d_dst: int, capacity: int):
     _check(load_library().demon_vae_debug_tap(handle, layer, d_dst, capacity))
 
@@ -240,6 +298,25 @@ class DemonVAE:
             frame_end = t
         demon_vae_decode_windowed(self.handle, latent.data_ptr(), n_clips, t, frame_begin, frame_end, window, halo,
                                   out.data_ptr(), stream)
+        return out
+
+    def decode_windowed_pcm16(self, latent, window: int, halo: int = -1, frame_begin: int = 0,
+                              frame_end: Optional[int] = None, out=None):
+        """out: int16 [n_clips, n_frames * S, out_channels], channel-interleaved."""
+        import torch
+        if latent.dim() == 2:
+            latent = latent[None]
+        assert latent.is_cuda and latent.dtype == self.torch_dtype and latent.is_contiguous()
+        n_clips, c, t = latent.shape
+        assert c == self.spec.latent_channels
+        if out is None:
+            out = torch.zeros((n_clips, t * self.S, self.spec.out_channels), dtype=torch.int16, device=latent.device)
+        assert out.is_cuda and out.dtype == torch.int16 and out.is_contiguous()
+        assert tuple(out.shape) == (n_clips, t * self.S, self.spec.out_channels)
+        if frame_end is None:
+            frame_end = t
+        demon_vae_decode_windowed_pcm16(self.handle, latent.data_ptr(), n_clips, t, frame_begin, frame_end, window,
+                                        halo, out.data_ptr(), torch.cuda.current_stream().cuda_stream)
         return out
 
     def set_timing(self, level: int):

@@ -210,7 +210,7 @@ demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, i
 #define HIP_TRY(expr, what) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_fail(e_, what); } while (0)
 
 demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_frames, int fb, int fe,
-                        int window, int halo, float* d_out, hipStream_t stream)
+                        int window, int halo, float* d_out, int16_t* d_pcm, hipStream_t stream)
 {
     Plan* plan = nullptr;
     demon_status rc = get_plan(v, n_clips, n_frames, fb, fe, window, halo, &plan);
@@ -357,7 +357,10 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
     HIP_TRY(launch_head(cur, bf, v->head_out, v->head_w, v->head_bias, v->head_alpha, v->head_inv_beta, v->head_cin,
                         v->st.out_channels, v->st.head_kernel, r, total_rows, bf, slots, ns, plan->max_int, stream), "head");
     HIP_TRY(mark(1), "event");
-    HIP_TRY(launch_stitch(v->head_out, d_out, v->st.out_channels, r, n_frames, total_rows, slots, ns, plan->max_int, stream), "stitch");
+    if (d_pcm)
+        HIP_TRY(launch_stitch_pcm16(v->head_out, d_pcm, v->st.out_channels, r, n_frames, total_rows, slots, ns, plan->max_int, stream), "stitch");
+    else
+        HIP_TRY(launch_stitch(v->head_out, d_out, v->st.out_channels, r, n_frames, total_rows, slots, ns, plan->max_int, stream), "stitch");
     HIP_TRY(mark(1), "event");
     if (v->timing > 0) ++v->timed_calls;
     return DEMON_OK;
@@ -563,12 +566,12 @@ demon_status demon_vae_receptive_field(const demon_vae* v, int* halo_left, int* 
     return DEMON_OK;
 }
 
-demon_status demon_vae_decode_windowed(demon_vae* v, const void* d_latent, int n_clips, int n_frames,
-                                       int frame_begin, int frame_end, int window, int halo,
-                                       float* d_out, void* stream)
+static demon_status decode_checked(demon_vae* v, const void* d_latent, int n_clips, int n_frames,
+                                   int frame_begin, int frame_end, int window, int halo,
+                                   float* d_out, int16_t* d_pcm, void* stream)
 {
     clear_error();
-    if (!v || !d_latent || !d_out) return fail(DEMON_ERR_INVALID_ARG, "NULL argument");
+    if (!v || !d_latent || (!d_out && !d_pcm)) return fail(DEMON_ERR_INVALID_ARG, "NULL argument");
     if (n_clips < 1) return fail(DEMON_ERR_INVALID_ARG, "n_clips must be >= 1");
     if (n_frames < 1) return fail(DEMON_ERR_INVALID_ARG, "n_frames must be >= 1");
     if (frame_begin < 0) return fail(DEMON_ERR_INVALID_ARG, "frame_begin must be >= 0");
@@ -579,13 +582,57 @@ demon_status demon_vae_decode_windowed(demon_vae* v, const void* d_latent, int n
     if (n_frames > v->max_frames) return fail(DEMON_ERR_WORKSPACE, "n_frames %d exceeds max_frames %d", n_frames, v->max_frames);
     if (n_clips > v->max_clips) return fail(DEMON_ERR_WORKSPACE, "n_clips %d exceeds max_clips %d", n_clips, v->max_clips);
     if (halo == -1) halo = std::max(v->rf_left, v->rf_right);
-    return run_decode(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, d_out, (hipStream_t)stream);
+    return run_decode(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, d_out, d_pcm, (hipStream_t)stream);
+}
+
+demon_status demon_vae_decode_windowed(demon_vae* v, const void* d_latent, int n_clips, int n_frames,
+                                       int frame_begin, int frame_end, int window, int halo,
+                                       float* d_out, void* stream)
+{
+    if (!d_out) { clear_error(); return fail(DEMON_ERR_INVALID_ARG, "NULL argument"); }
+    return decode_checked(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, d_out, nullptr, stream);
+}
+
+demon_status demon_vae_decode_windowed_pcm16(demon_vae* v, const void* d_latent, int n_clips, int n_frames,
+                                             int frame_begin, int frame_end, int window, int halo,
+                                             int16_t* d_pcm, void* stream)
+{
+    if (!d_pcm) { clear_error(); return fail(DEMON_ERR_INVALID_ARG, "NULL argument"); }
+    return decode_checked(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, nullptr, d_pcm, stream);
 }
 
 demon_status demon_vae_decode(demon_vae* v, const void* d_latent, int n_clips, int n_frames, float* d_out, void* stream)
 {
     // one window per clip covering [0, n_frames), no halo: the same kernels as the windowed decode
     return demon_vae_decode_windowed(v, d_latent, n_clips, n_frames, 0, n_frames, n_frames > 0 ? n_frames : 1, 0, d_out, stream);
+}
+
+demon_status demon_vae_latent_similarity(const void* d_curr, const void* d_prev, int n_clips, long long elems_per_clip,
+                                         demon_dtype dtype, float threshold, float* d_mse, int* d_unchanged, void* stream)
+{
+    clear_error();
+    if (!d_curr || !d_prev || (!d_mse && !d_unchanged)) return fail(DEMON_ERR_INVALID_ARG, "NULL argument");
+    if (n_clips < 1 || n_clips > 65535) return fail(DEMON_ERR_INVALID_ARG, "n_clips must be in [1, 65535]");
+    if (elems_per_clip < 1) return fail(DEMON_ERR_INVALID_ARG, "elems_per_clip must be >= 1");
+    if (dtype != DEMON_F32 && dtype != DEMON_BF16) return fail(DEMON_ERR_INVALID_ARG, "unknown dtype");
+    if (!(threshold >= 0.0f)) return fail(DEMON_ERR_INVALID_ARG, "threshold must be >= 0");
+    HIP_TRY(launch_latent_mse(d_curr, d_prev, n_clips, elems_per_clip, dtype == DEMON_BF16, threshold, d_mse, d_unchanged,
+                              (hipStream_t)stream), "latent similarity");
+    return DEMON_OK;
+}
+
+demon_status demon_vae_crossfade(const float* d_prev_tail, long long prev_stride, const float* d_next_head, long long next_stride,
+                                 float* d_out, long long out_stride, int n_planes, int n_samples, void* stream)
+{
+    clear_error();
+    if (!d_prev_tail || !d_next_head || !d_out) return fail(DEMON_ERR_INVALID_ARG, "NULL argument");
+    if (n_planes < 1 || n_planes > 65535) return fail(DEMON_ERR_INVALID_ARG, "n_planes must be in [1, 65535]");
+    if (n_samples < 1) return fail(DEMON_ERR_INVALID_ARG, "n_samples must be >= 1");
+    if (prev_stride < 0 || next_stride < 0 || out_stride < 0) return fail(DEMON_ERR_INVALID_ARG, "negative plane stride");
+    if (n_planes > 1 && out_stride < n_samples) return fail(DEMON_ERR_INVALID_ARG, "output planes overlap");
+    HIP_TRY(launch_crossfade(d_prev_tail, prev_stride, d_next_head, next_stride, d_out, out_stride, n_planes, n_samples,
+                             (hipStream_t)stream), "crossfade");
+    return DEMON_OK;
 }
 
 demon_status demon_vae_set_timing(demon_vae* v, int level)

@@ -126,6 +126,15 @@ hipError_t launch_head_mfma(const void* x, float* y, const uint16_t* wfrag, cons
 // crop + stitch: planar slot waveform -> d_out [n_clips, oc, n_frames*S]
 hipError_t launch_stitch(const float* y, float* out, int oc, int S, int n_frames, long long total_rows,
                          const Slot* slots, int n_slots, int max_int, hipStream_t stream);
+// crop + stitch + 16-bit render: planar slot waveform -> d_pcm [n_clips, n_frames*S, oc] interleaved int16
+hipError_t launch_stitch_pcm16(const float* y, int16_t* pcm, int oc, int S, int n_frames, long long total_rows,
+                               const Slot* slots, int n_slots, int max_int, hipStream_t stream);
+// latent similarity filter: per clip mse = mean((a-b)^2) over n elements and the gate mse < threshold
+hipError_t launch_latent_mse(const void* a, const void* b, int n_clips, long long n, bool bf16, float threshold,
+                             float* mse, int* unchanged, hipStream_t stream);
+// equal-power crossfade of n_planes planar segments of n samples
+hipError_t launch_crossfade(const float* tail, long long tail_stride, const float* head, long long head_stride,
+                            float* out, long long out_stride, int n_planes, int n, hipStream_t stream);
 // debug tap: activation -> fp32 copy; src_type 0 fp32, 1 bf16, 2 half
 hipError_t launch_to_f32(const void* x, float* dst, size_t n, int src_type, hipStream_t stream);
 

@@ -423,6 +423,119 @@ hipError_t launch_stitch(const float* y, float* out, int oc, int S, int n_frames
     return hipGetLastError();
 }
 
+// 16-bit render fused into the stitch: q = rint(32767 * clamp(y, -1, 1)) in fp32 (round half to even), channels
+// interleaved per sample: pcm[clip][sample][channel].  One thread quantises VEC consecutive samples of all channels.
+template <int VEC, int OC>
+__global__ __launch_bounds__(256) void stitch_pcm16_kernel(const float* __restrict__ y, int16_t* __restrict__ pcm,
+                                                           int oc, int S, int n_frames, long long total_rows,
+                                                           const Slot* __restrict__ slots)
+{
+    const Slot s = slots[blockIdx.y];
+    const long long n = (long long)s.n_int * S;
+    const long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * VEC;
+    if (i >= n) return;
+    const float* src = y + ((long long)s.row0 + s.crop) * S + i;
+    int16_t* dst = pcm + ((size_t)s.clip * ((size_t)n_frames * S) + (size_t)s.begin * S + i) * oc;
+    auto quant = [](float v) -> int16_t {
+        v = fminf(fmaxf(v, -1.0f), 1.0f);
+        return (int16_t)__float2int_rn(v * 32767.0f);
+    };
+    if (OC == 2 && VEC == 4) {
+        const float4 l = *reinterpret_cast<const float4*>(src);
+        const float4 r = *reinterpret_cast<const float4*>(src + total_rows);
+        const float lv[4] = {l.x, l.y, l.z, l.w}, rv[4] = {r.x, r.y, r.z, r.w};
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            o[e] = (uint32_t)(uint16_t)quant(lv[e]) | ((uint32_t)(uint16_t)quant(rv[e]) << 16);
+        *reinterpret_cast<u32x4*>(dst) = o;
+    } else {
+        for (int e = 0; e < VEC && i + e < n; ++e)
+            for (int c = 0; c < oc; ++c) dst[(size_t)e * oc + c] = quant(src[(size_t)c * total_rows + e]);
+    }
+}
+
+hipError_t launch_stitch_pcm16(const float* y, int16_t* pcm, int oc, int S, int n_frames, long long total_rows,
+                               const Slot* slots, int n_slots, int max_int, hipStream_t stream)
+{
+    // 16-byte stores need 4 stereo samples per thread at a 16-byte aligned address: S % 4 == 0 keeps every window start aligned
+    const bool vec = oc == 2 && (S % 4 == 0) && (total_rows % 4 == 0) &&
+                     (reinterpret_cast<uintptr_t>(y) % 16 == 0) && (reinterpret_cast<uintptr_t>(pcm) % 16 == 0);
+    const long long per = (long long)max_int * S;
+    if (vec) {
+        dim3 grid((unsigned)((per / 4 + 255) / 256), (unsigned)n_slots);
+        hipLaunchKernelGGL((stitch_pcm16_kernel<4, 2>), grid, dim3(256), 0, stream, y, pcm, oc, S, n_frames, total_rows, slots);
+    } else {
+        dim3 grid((unsigned)((per + 255) / 256), (unsigned)n_slots);
+        hipLaunchKernelGGL((stitch_pcm16_kernel<1, 0>), grid, dim3(256), 0, stream, y, pcm, oc, S, n_frames, total_rows, slots);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------- latent similarity filter
+// One workgroup per clip: squared differences accumulate in double in a fixed order (thread-strided partial sums, then a
+// tree over the workgroup), so the result does not depend on scheduling.  mse and the gate go out as fp32 / int.
+template <typename T>
+__global__ __launch_bounds__(1024) void latent_mse_kernel(const T* __restrict__ a, const T* __restrict__ b, long long n,
+                                                          float threshold, float* __restrict__ mse, int* __restrict__ unchanged)
+{
+    __shared__ double part[16];
+    const T* pa = a + (size_t)blockIdx.x * n;
+    const T* pb = b + (size_t)blockIdx.x * n;
+    double acc = 0.0;
+    for (long long i = threadIdx.x; i < n; i += 1024) {
+        const double d = (double)load_act<T>(pa + i) - (double)load_act<T>(pb + i);
+        acc += d * d;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int w = 0; w < 16; ++w) t += part[w];
+        const float m = (float)(t / (double)n);
+        if (mse) mse[blockIdx.x] = m;
+        if (unchanged) unchanged[blockIdx.x] = m < threshold ? 1 : 0;
+    }
+}
+
+hipError_t launch_latent_mse(const void* a, const void* b, int n_clips, long long n, bool bf16, float threshold,
+                             float* mse, int* unchanged, hipStream_t stream)
+{
+    if (bf16)
+        hipLaunchKernelGGL(latent_mse_kernel<uint16_t>, dim3(n_clips), dim3(1024), 0, stream,
+                           (const uint16_t*)a, (const uint16_t*)b, n, threshold, mse, unchanged);
+    else
+        hipLaunchKernelGGL(latent_mse_kernel<float>, dim3(n_clips), dim3(1024), 0, stream,
+                           (const float*)a, (const float*)b, n, threshold, mse, unchanged);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------- equal-power crossfade
+// out[c][i] = cos(theta_i) * tail[c][i] + sin(theta_i) * head[c][i], theta_i = (pi/2)(i + 1/2)/n.  Element-wise, so out may
+// alias head or tail.
+__global__ __launch_bounds__(256) void crossfade_kernel(const float* __restrict__ tail, long long tail_stride,
+                                                        const float* __restrict__ head, long long head_stride,
+                                                        float* out, long long out_stride, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int c = blockIdx.y;
+    const float theta = 1.57079632679489662f * (((float)i + 0.5f) / (float)n);
+    float sn, cs;
+    sincosf(theta, &sn, &cs);
+    out[c * out_stride + i] = cs * tail[c * tail_stride + i] + sn * head[c * head_stride + i];
+}
+
+hipError_t launch_crossfade(const float* tail, long long tail_stride, const float* head, long long head_stride,
+                            float* out, long long out_stride, int n_planes, int n, hipStream_t stream)
+{
+    dim3 grid((unsigned)((n + 255) / 256), (unsigned)n_planes);
+    hipLaunchKernelGGL(crossfade_kernel, grid, dim3(256), 0, stream, tail, tail_stride, head, head_stride, out, out_stride, n);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------- debug tap
 template <typename T>
 __global__ __launch_bounds__(256) void to_f32_kernel(const T* __restrict__ x, float* __restrict__ dst, size_t n)

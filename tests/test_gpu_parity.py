@@ -170,6 +170,35 @@ def test_partial_redecode_splices_into_existing_waveform(dtype, spec):
     vae.close()
 
 
+@pytest.mark.parametrize("dtype,spec,T,window", [("f32", di.TINY, 50, 16), ("bf16", STACK_V1, 37, 8),
+                                                 ("f32", STACK_ODD, 23, 5), ("bf16", di.FULL, 9, 4)])
+def test_pcm16_render_fused_into_the_stitch(dtype, spec, T, window):
+    """The integer decision is taken in fp32 on both sides: the int16 output must equal the oracle's quantiser
+    applied to the fp32 output of the same decode, bit for bit; against the oracle's own decode it may differ by the
+    floating-point tolerance expressed in 16-bit steps."""
+    S = spec.total_stride
+    vae, w, z = make(spec, dtype, T, n_clips=2, max_extended_frames=8 * T)
+    zt = to_device(z, dtype)
+    y = vae.decode_windowed(zt, window=window, halo=-1).cpu().numpy()
+    q = vae.decode_windowed_pcm16(zt, window=window, halo=-1).cpu().numpy()
+    assert q.dtype == np.int16 and q.shape == (2, T * S, spec.out_channels)
+    for c in range(2):
+        assert np.array_equal(q[c], oracle.pcm16(y[c]))
+        ref = oracle.pcm16(oracle.decode(spec, w, z[c]), dtype=np.float64)
+        tol = 32767 * (2e-2 if dtype == "bf16" else 1e-4) + 1
+        assert np.abs(q[c].astype(np.int32) - ref.astype(np.int32)).max() <= tol
+    # a partial range writes only its own samples, and the full-clip render equals the windowed one
+    out = torch.full((2, T * S, spec.out_channels), 1234, dtype=torch.int16, device="cuda:0")
+    fb, fe = 3, min(T, 3 + window + 2)
+    vae.decode_windowed_pcm16(zt, window=window, halo=-1, frame_begin=fb, frame_end=fe, out=out)
+    got = out.cpu().numpy()
+    assert np.all(got[:, :fb * S] == 1234) and np.all(got[:, fe * S:] == 1234)
+    assert np.array_equal(got[:, fb * S:fe * S], q[:, fb * S:fe * S])
+    whole = vae.decode_windowed_pcm16(zt, window=T, halo=0).cpu().numpy()
+    assert np.array_equal(whole, q)
+    vae.close()
+
+
 def test_runs_are_deterministic_and_plans_are_reused():
     vae, w, z = make(STACK_V1, "bf16", 64, max_extended_frames=1200)
     zt = to_device(z, "bf16")
@@ -242,3 +271,69 @@ print("ok")
     env = dict(os.environ, DEMON_VAE_NO_FUSED="1")
     r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=240)
     assert r.returncode == 0 and "ok" in r.stdout, r.stdout + r.stderr
+
+
+# ------------------------------------------------------------------ latent similarity filter and crossfade
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("C,T", [(64, 1500), (16, 50), (64, 1), (3, 1025)])
+def test_latent_similarity_filter(dtype, C, T):
+    bf = dtype == "bf16"
+    prev = np.stack([di.make_latent(C, T, 40 + i, bf16=bf) for i in range(5)])
+    curr = prev.copy()
+    rng = np.random.default_rng(41)
+    curr[1] = di.make_latent(C, T, 50, bf16=bf)                                        # unrelated latent: mse ~ 2
+    curr[2] = di.round_to_bf16(prev[2] + 0.02 * rng.standard_normal((C, T)).astype(np.float32)) if bf else \
+        prev[2] + np.float32(0.02) * rng.standard_normal((C, T)).astype(np.float32)    # small drift: mse ~ 4e-4
+    curr[3] = di.round_to_bf16(prev[3] + 0.06 * rng.standard_normal((C, T)).astype(np.float32)) if bf else \
+        prev[3] + np.float32(0.06) * rng.standard_normal((C, T)).astype(np.float32)    # larger drift: mse ~ 3.6e-3
+    curr[4, C // 2, T // 2] += 1.0                                                      # one element
+    if bf:
+        curr[4] = di.round_to_bf16(curr[4])
+    mse, flag = pa.latent_similarity(to_device(curr, dtype), to_device(prev, dtype), 1e-3)
+    mse = mse.cpu().numpy(); flag = flag.cpu().numpy()
+    for c in range(5):
+        ref = oracle.latent_mse(curr[c], prev[c])
+        assert mse[c] == pytest.approx(ref, rel=1e-6, abs=1e-30), (c, mse[c], ref)
+        if abs(ref - 1e-3) > 1e-8:                       # away from the threshold the gate is unique
+            assert bool(flag[c]) == oracle.latent_unchanged(curr[c], prev[c], 1e-3)
+        assert bool(flag[c]) == bool(np.float32(mse[c]) < np.float32(1e-3))     # the decision as taken in fp32
+    assert mse[0] == 0.0 and flag[0] == 1 and flag[1] == 0
+    # a 2-D latent is one clip; another threshold
+    m1, f1 = pa.latent_similarity(to_device(curr[1], dtype), to_device(prev[1], dtype), 10.0)
+    assert m1.shape == (1,) and float(m1[0]) == mse[1] and int(f1[0]) == 1
+
+
+@pytest.mark.parametrize("n", [1, 7, 2400, 5003])
+def test_equal_power_crossfade(n):
+    rng = np.random.default_rng(60 + n)
+    a = rng.uniform(-1, 1, (2, n)).astype(np.float32); b = rng.uniform(-1, 1, (2, n)).astype(np.float32)
+    ref = oracle.crossfade(a, b)
+    got = pa.crossfade(to_device(a, "f32"), to_device(b, "f32")).cpu().numpy()
+    assert np.abs(got - ref).max() <= 1e-6
+    # segments inside larger planar waveforms, written in place over the head of the next chunk
+    S = 3 * n + 11
+    prev_wave = torch.from_numpy(rng.uniform(-1, 1, (2, S)).astype(np.float32)).to("cuda:0")
+    next_wave = torch.from_numpy(rng.uniform(-1, 1, (2, S)).astype(np.float32)).to("cuda:0")
+    before = next_wave.clone()
+    tail, head = prev_wave[:, S - n:], next_wave[:, :n]
+    ref2 = oracle.crossfade(tail.cpu().numpy(), head.cpu().numpy())
+    pa.crossfade(tail, head, out=head)
+    assert np.abs(next_wave[:, :n].cpu().numpy() - ref2).max() <= 1e-6
+    assert torch.equal(next_wave[:, n:], before[:, n:])
+
+
+def test_filter_and_crossfade_argument_errors():
+    lib = pa.load_library()
+    x = torch.zeros(8, device="cuda:0")
+    p = x.data_ptr()
+    assert lib.demon_vae_latent_similarity(p, p, 0, 8, pa.DEMON_F32, 1e-3, p, None, None) == pa.DEMON_ERR_INVALID_ARG
+    assert lib.demon_vae_latent_similarity(p, p, 1, 0, pa.DEMON_F32, 1e-3, p, None, None) == pa.DEMON_ERR_INVALID_ARG
+    assert lib.demon_vae_latent_similarity(p, p, 1, 8, 7, 1e-3, p, None, None) == pa.DEMON_ERR_INVALID_ARG
+    assert lib.demon_vae_latent_similarity(p, p, 1, 8, pa.DEMON_F32, -1.0, p, None, None) == pa.DEMON_ERR_INVALID_ARG
+    assert lib.demon_vae_latent_similarity(p, p, 1, 8, pa.DEMON_F32, 1e-3, None, None, None) == pa.DEMON_ERR_INVALID_ARG
+    assert lib.demon_vae_latent_similarity(None, p, 1, 8, pa.DEMON_F32, 1e-3, p, None, None) == pa.DEMON_ERR_INVALID_ARG
+    assert lib.demon_vae_crossfade(p, 4, p, 4, p, 4, 1, 0, None) == pa.DEMON_ERR_INVALID_ARG
+    assert lib.demon_vae_crossfade(p, 4, p, 4, p, 2, 2, 4, None) == pa.DEMON_ERR_INVALID_ARG
+    assert lib.demon_vae_crossfade(None, 4, p, 4, p, 4, 1, 4, None) == pa.DEMON_ERR_INVALID_ARG
+    assert lib.demon_vae_crossfade(p, -4, p, 4, p, 4, 1, 4, None) == pa.DEMON_ERR_INVALID_ARG
+    torch.cuda.synchronize()

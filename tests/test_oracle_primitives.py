@@ -139,3 +139,97 @@ def test_f32_build_matches_f64():
     y32 = oracle.conv1d(x, W, b, 3, dtype=np.float32)
     assert y32.dtype == np.float32
     np.testing.assert_allclose(y32, y64, atol=2e-5)
+
+
+# ------------------------------------------------------------------ 16-bit render (section 3.6)
+def test_pcm16_fixed_points_ties_and_clamp():
+    y = np.array([[0.0, 1.0, -1.0, 0.5 / 32767, 1.5 / 32767, 2.5 / 32767, -0.5 / 32767, -1.5 / 32767, 1.7, -3.0,
+                   100 / 32767, -100 / 32767]])
+    q = oracle.pcm16(y, dtype=np.float64)
+    assert q.dtype == np.int16 and q.shape == (12, 1)
+    assert q[:, 0].tolist() == [0, 32767, -32767, 0, 2, 2, 0, -2, 32767, -32767, 100, -100]
+
+
+def test_pcm16_interleaves_channels():
+    y = np.array([[0.1, 0.2, 0.3], [-0.1, -0.2, -0.3]])
+    q = oracle.pcm16(y)
+    assert q.shape == (3, 2) and q.flags["C_CONTIGUOUS"]
+    assert np.all(q[:, 0] > 0) and np.all(q[:, 1] < 0) and np.array_equal(q[:, 0], -q[:, 1])
+
+
+def test_pcm16_single_precision_matches_exact_rational_arithmetic():
+    """Brute force: the fp32 product is rounded once from the exact rational product (39 significant bits fit a
+    double), then rounded half-to-even to an integer with Python's rational round()."""
+    from fractions import Fraction
+    rng = np.random.default_rng(5)
+    y = np.concatenate([rng.uniform(-1.2, 1.2, 400), (np.arange(-40, 40) + 0.5) / 32767.0]).astype(np.float32)
+    q = oracle.pcm16(y[None], dtype=np.float32)[:, 0]
+    for yi, qi in zip(y, q):
+        c = min(max(Fraction(float(yi)), Fraction(-1)), Fraction(1))
+        prod32 = np.float32(float(c * 32767))                    # exact in double, one rounding to single
+        assert int(qi) == round(Fraction(float(prod32)))
+    # and the quantisation error bound of a mid-tread quantiser
+    inside = np.abs(y) <= 1
+    assert np.all(np.abs(q[inside] / 32767.0 - y[inside]) <= 0.5 / 32767 + 1e-7)
+
+
+# ------------------------------------------------------------------ latent similarity filter (section 3.5)
+def test_latent_mse_closed_forms():
+    rng = np.random.default_rng(11)
+    a = rng.standard_normal((64, 50))
+    assert oracle.latent_mse(a, a) == 0.0
+    assert oracle.latent_mse(a + 0.25, a) == pytest.approx(0.0625, rel=1e-12)
+    b = a.copy(); b[3, 7] += 2.0                       # one differing element: 4 / size
+    assert oracle.latent_mse(a, b) == pytest.approx(4.0 / a.size, rel=1e-12)
+    assert oracle.latent_mse(a, b) == oracle.latent_mse(b, a)
+    assert oracle.latent_mse(3 * a, 3 * b) == pytest.approx(9 * oracle.latent_mse(a, b), rel=1e-12)
+    # independent unit normals differ by variance 2
+    c = rng.standard_normal((64, 4000)); d = rng.standard_normal((64, 4000))
+    assert oracle.latent_mse(c, d) == pytest.approx(2.0, rel=2e-2)
+
+
+def test_latent_mse_brute_force_and_library():
+    from sklearn.metrics import mean_squared_error
+    rng = np.random.default_rng(12)
+    a = rng.standard_normal((5, 9)); b = rng.standard_normal((5, 9))
+    acc = 0.0
+    for i in range(5):
+        for j in range(9):
+            acc += (a[i, j] - b[i, j]) ** 2
+    assert oracle.latent_mse(a, b) == pytest.approx(acc / 45, rel=1e-13)
+    assert oracle.latent_mse(a, b) == pytest.approx(mean_squared_error(a.ravel(), b.ravel()), rel=1e-13)
+
+
+def test_latent_gate_uses_the_papers_threshold():
+    a = np.zeros((64, 10))
+    assert oracle.latent_unchanged(a + 0.03, a)              # 9e-4 < 1e-3
+    assert not oracle.latent_unchanged(a + 0.032, a)         # 1.024e-3
+    assert not oracle.latent_unchanged(a + np.sqrt(1e-3) * 1.0001, a)
+    assert oracle.latent_unchanged(a + 0.5, a, threshold=0.3)
+
+
+# ------------------------------------------------------------------ equal-power crossfade of the chunk boundary
+@pytest.mark.parametrize("n", [1, 2, 7, 2400])
+def test_crossfade_gains_are_equal_power_and_mirror_images(n):
+    one = np.ones((1, n)); zero = np.zeros((1, n))
+    g_out = oracle.crossfade(one, zero)[0]
+    g_in = oracle.crossfade(zero, one)[0]
+    np.testing.assert_allclose(g_out ** 2 + g_in ** 2, 1.0, atol=1e-14)
+    np.testing.assert_allclose(g_out, g_in[::-1], atol=1e-15)
+    assert np.all(np.diff(g_in) > 0) and np.all(np.diff(g_out) < 0)
+    assert 0 < g_in[0] <= np.sqrt(0.5) + 1e-15 and g_in[0] == pytest.approx(np.sin(np.pi / (4 * n)), rel=1e-12)
+    if n % 2 == 1:
+        assert g_in[n // 2] == pytest.approx(np.sqrt(0.5), rel=1e-14)
+
+
+def test_crossfade_is_linear_and_keeps_the_power_of_uncorrelated_signals():
+    rng = np.random.default_rng(13)
+    a = rng.standard_normal((2, 2400)); b = rng.standard_normal((2, 2400))
+    y = oracle.crossfade(a, b)
+    np.testing.assert_allclose(oracle.crossfade(2 * a, -3 * b), 2 * oracle.crossfade(a, 0 * b) - 3 * oracle.crossfade(0 * a, b), atol=1e-13)
+    assert np.mean(y ** 2) == pytest.approx(1.0, rel=0.1)
+    # a signal crossfaded with itself is boosted by cos+sin (at most sqrt 2 in the middle), never attenuated
+    s = oracle.crossfade(a, a) / a
+    assert np.all(s >= 1.0 - 1e-12) and s.max() == pytest.approx(np.sqrt(2), rel=1e-6)
+    # channels are independent
+    np.testing.assert_array_equal(oracle.crossfade(a[:1], b[:1])[0], y[0])
