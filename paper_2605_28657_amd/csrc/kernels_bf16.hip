@@ -242,6 +242,26 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
             }
         }
 
+    // Epilogue geometry (see the epilogue): a lane owns 4 consecutive channels of RPI-strided rows.
+    constexpr int LPR = WTM / 4;                       // lanes per row
+    constexpr int RPI = 64 / LPR;                      // rows per instruction
+    const int cl = lane % LPR, rl = lane / LPR;
+    const unsigned out_rows = (unsigned)out_hi;
+    const __amdgpu_buffer_rsrc_t rs_y = make_rsrc(MODE == MODE_ACT ? nullptr : p.y + rowbase_o * p.cout,
+                                                  MODE == MODE_ACT ? 0u : out_rows * p.cout * (unsigned)sizeof(hres_t));
+    // The residual values this lane will add are fetched now: issued in the epilogue, each of the loads would be
+    // waited for in turn (they cannot move above the in-place stores), a chain of memory latencies per tile.
+    u32x2 resv[MODE == MODE_RES ? TN : 1][32 / RPI];
+    if (MODE == MODE_RES) {
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int it = 0; it < 32 / RPI; ++it) {
+                const int col = n0 + wn * WTN + ni * 32 + it * RPI + rl;
+                resv[ni][it] = __builtin_amdgcn_raw_buffer_load_b64(rs_y, (unsigned)(col * p.cout + m0 + wm * WTM + 4 * cl) * 2u, 0, 0);
+            }
+    }
+
     load_a(0);
     load_x(0);
     store_a(0);
@@ -298,12 +318,6 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     // out of range of the descriptors and dropped.
     __syncthreads();                                   // all waves are done with the operand tiles
     float* stage = reinterpret_cast<float*>(smem) + wave * (32 * LDT);
-    constexpr int LPR = WTM / 4;                       // lanes per row
-    constexpr int RPI = 64 / LPR;                      // rows per instruction
-    const int cl = lane % LPR, rl = lane / LPR;
-    const unsigned out_rows = (unsigned)out_hi;
-    const __amdgpu_buffer_rsrc_t rs_y = make_rsrc(MODE == MODE_ACT ? nullptr : p.y + rowbase_o * p.cout,
-                                                  MODE == MODE_ACT ? 0u : out_rows * p.cout * (unsigned)sizeof(hres_t));
     const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.ya + rowbase_o * p.cout, EMIT > 0 ? out_rows * p.cout * 2u : 0u);
     const __amdgpu_buffer_rsrc_t rs_al = make_rsrc(p.ya + p.out_lo_off + rowbase_o * p.cout, EMIT > 1 ? out_rows * p.cout * 2u : 0u);
     const int mu = m0 + wm * WTM + 4 * cl;             // this lane's 4 GEMM rows
@@ -333,8 +347,8 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
             // wraps to a huge offset = out of range.
             const unsigned e = (MODE == MODE_UP) ? (unsigned)((col * s_up - p_up) * p.cout + mu) : (unsigned)(col * p.cout + mu);
             if (MODE == MODE_RES) {
-                const float4 r = hres_load4(rs_y, e);
-                v0 += r.x; v1 += r.y; v2 += r.z; v3 += r.w;
+                const f16x4 r = __builtin_bit_cast(f16x4, resv[ni][it]);
+                v0 += (float)r[0]; v1 += (float)r[1]; v2 += (float)r[2]; v3 += (float)r[3];
             }
             if (MODE != MODE_ACT) {
                 hres_store4(rs_y, e, v0, v1, v2, v3);

@@ -175,6 +175,25 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     store_x();
     __syncthreads();
 
+    // The residual values this lane adds in the epilogue (4 consecutive channels of RPI-strided rows) are fetched
+    // ahead of time: loaded where they are used, each would be waited for in turn, a chain of memory latencies per
+    // tile.  With 64 channels there are registers to hold them through the K loop; with 128 they are fetched after
+    // it, in the shadow of the Snake and the 1x1 convolution.
+    constexpr int LPR = CH / 4;                        // lanes per row
+    constexpr int RPI = 64 / LPR;                      // rows per instruction
+    constexpr bool EARLY_RES = CH == 64;
+    const int cl = lane % LPR, rl = lane / LPR;
+    u32x2 resv[TN][32 / RPI];
+    auto load_res = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int it = 0; it < 32 / RPI; ++it)
+                resv[ni][it] = __builtin_amdgcn_raw_buffer_load_b64(
+                    rs_x, (unsigned)((n0 + wn * WTN + ni * 32 + it * RPI + rl) * CH + 4 * cl) * 2u, 0, 0);
+    };
+    if (EARLY_RES) load_res();
+
     // ---- dilated conv: K loop over (chunk, tap) stages, fixed order
     int chunk = 0, tap = 0;
     for (int stage = 0; stage < nstages; ++stage) {
@@ -212,6 +231,8 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
         }
         tap = ntap; chunk = nchunk;
     }
+
+    if (!EARLY_RES) load_res();
 
     // ---- stage the 1x1 weights into the (now free) weight buffers
     __syncthreads();
@@ -274,9 +295,6 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     // descriptors and dropped.
     __syncthreads();                                   // all waves are done with the 1x1 weights in LDS
     float* stage = reinterpret_cast<float*>(smem) + wn * (32 * LDT);
-    constexpr int LPR = CH / 4;                        // lanes per row
-    constexpr int RPI = 64 / LPR;                      // rows per instruction
-    const int cl = lane % LPR, rl = lane / LPR;
     float4 a4 = make_float4(0, 0, 0, 0), i4 = a4;
     if (EMIT) {
         a4 = *reinterpret_cast<const float4*>(p.a3 + 4 * cl);
@@ -296,8 +314,8 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
             const float4 t4 = *reinterpret_cast<const float4*>(&stage[row * LDT + 4 * cl]);
             const int col = n0 + wn * WTN + ni * 32 + row;
             const unsigned e = (unsigned)(col * CH + 4 * cl);
-            const float4 r = hres_load4(rs_x, e);
-            float v0 = t4.x + r.x, v1 = t4.y + r.y, v2 = t4.z + r.z, v3 = t4.w + r.w;
+            const f16x4 r = __builtin_bit_cast(f16x4, resv[ni][it]);
+            float v0 = t4.x + (float)r[0], v1 = t4.y + (float)r[1], v2 = t4.z + (float)r[2], v3 = t4.w + (float)r[3];
             hres_store4(rs_y, e, v0, v1, v2, v3);
             if (EMIT) {
                 // the next layer's operand is Snake of the STORED value
