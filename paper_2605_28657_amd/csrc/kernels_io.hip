@@ -293,6 +293,18 @@ __global__ __launch_bounds__(256) void head_mfma_kernel(const _Float16* __restri
     for (int e = 0; e < 8; ++e) { al[e] = alpha[seg * 8 + e]; ib[e] = inv_beta[seg * 8 + e]; }
     const float b = (j < oc) ? bias[j] : 0.f;
 
+    // The raw rows of a sub-tile are fetched one sub-tile ahead, so that their latency hides behind the MFMAs and the
+    // tanh epilogue of the previous one.  Rows outside the window are out of range of the descriptor and read as
+    // zero = the convolution's zero padding.
+    u32x4 raw[X_ITERS];
+    auto load_rows = [&](int n0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int it = 0; it < X_ITERS; ++it) {
+            if (it * RPP >= XR) break;                         // uniform
+            raw[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, (unsigned)((n0 - half + xr0 + it * RPP) * CIN + seg * 8) * 2u, 0, 0);
+        }
+    };
+    load_rows(lo + (int)blockIdx.x * (HM_NT * HM_SUB));
     for (int sub = 0; sub < HM_SUB; ++sub) {
         const int n0 = lo + ((int)blockIdx.x * HM_SUB + sub) * HM_NT;
         if (n0 >= hi) break;                                   // uniform
@@ -302,16 +314,14 @@ __global__ __launch_bounds__(256) void head_mfma_kernel(const _Float16* __restri
             const int xr = xr0 + it * RPP;
             if (it * RPP >= XR) break;                         // uniform
             if (xr >= XR_MAX) continue;
-            // rows outside the window are out of range of the descriptor: zero = the conv's zero padding
-            const unsigned off = (unsigned)((n0 - half + xr) * CIN + seg * 8) * 2u;
-            const u32x4 raw = __builtin_amdgcn_raw_buffer_load_b128(rs_x, off, 0, 0);
-            const f16x8v hv = __builtin_bit_cast(f16x8v, raw);
+            const f16x8v hv = __builtin_bit_cast(f16x8v, raw[it]);
             f16x8v ov;
 #pragma unroll
             for (int e = 0; e < 8; ++e) ov[e] = (_Float16)snake_fast((float)hv[e], al[e], ib[e]);
             *reinterpret_cast<f16x8v*>(&Xs[xr * LDX + seg * 8]) = ov;
         }
         __syncthreads();
+        if (sub + 1 < HM_SUB && n0 + HM_NT < hi) load_rows(n0 + HM_NT);
 
         f32x16 acc[2];
 #pragma unroll
