@@ -53,6 +53,15 @@ typedef _Float16 hres_t;
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
+// Pins a value to its fp32 rounding.  Without it the compiler may fuse the arithmetic that produced v with a following
+// conversion to half into one mixed-precision instruction that rounds once; it does so in some unrolled iterations and
+// not in others, and the result of an element would then depend on its position in the tile.
+__device__ __forceinline__ float keep_f32(float v)
+{
+    asm("" : "+v"(v));
+    return v;
+}
+
 // four consecutive elements starting at element index e of the buffer
 __device__ __forceinline__ float4 hres_load4(__amdgpu_buffer_rsrc_t rs, unsigned e)
 {

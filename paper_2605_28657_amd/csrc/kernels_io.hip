@@ -317,7 +317,7 @@ __global__ __launch_bounds__(256) void head_mfma_kernel(const _Float16* __restri
             const f16x8v hv = __builtin_bit_cast(f16x8v, raw[it]);
             f16x8v ov;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) ov[e] = (_Float16)snake_fast((float)hv[e], al[e], ib[e]);
+            for (int e = 0; e < 8; ++e) ov[e] = (_Float16)keep_f32(snake_fast((float)hv[e], al[e], ib[e]));
             *reinterpret_cast<f16x8v*>(&Xs[xr * LDX + seg * 8]) = ov;
         }
         __syncthreads();

@@ -103,3 +103,32 @@ def test_null_handle_calls_return_invalid_arg():
     l = ctypes.c_int()
     assert lib.demon_vae_receptive_field(None, ctypes.byref(l), ctypes.byref(l)) == pa.DEMON_ERR_INVALID_ARG
     lib.demon_vae_destroy(None)      # ignored
+
+
+def test_half_conversions_keep_the_fp32_rounding():
+    """The device code converts fp32 results to half in unrolled loops.  If the compiler fuses the producing
+    arithmetic with the conversion (one mixed-precision instruction that rounds once) it does so in some iterations
+    only, and a value then depends on its position in a tile: the windowed decode would stop being bit-identical to
+    the full decode.  The generated code of the kernels must hold no such instruction."""
+    import shutil
+    import subprocess
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+    from paper_2605_28657_amd import build as b
+    if shutil.which("hipcc") is None:
+        pytest.skip("hipcc not available")
+    flags = [f for f in b.FLAGS if f != "-fPIC"]
+
+    def asm_of(src):
+        with tempfile.TemporaryDirectory() as d:
+            out = os.path.join(d, "k.s")
+            r = subprocess.run(["hipcc"] + flags + ["-S", "--cuda-device-only", "-o", out, os.path.join(b.CSRC, src)],
+                               capture_output=True, text=True)
+            assert r.returncode == 0, r.stderr[-2000:]
+            return open(out).read()
+
+    srcs = [s_ for s_ in b.SOURCES if s_.endswith(".hip") and s_ != "api.hip"]
+    with ThreadPoolExecutor(max_workers=len(srcs)) as ex:
+        for src, text in zip(srcs, ex.map(asm_of, srcs)):
+            bad = re.findall(r"v_(?:fma|mad)_mix(?:lo|hi)_f16", text)
+            assert not bad, f"{src}: {len(bad)} fused arithmetic-to-half instructions"
