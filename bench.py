@@ -21,7 +21,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # measured with rocprofv3 --pmc (see profiles/full_60s_bf16_hbm_traffic.txt); not collectable inside this process
-TRAFFIC_BYTES_PER_STEP = {"full_60s_bf16": 18865643847}
+TRAFFIC_BYTES_PER_STEP = {"full_60s_bf16": 17985715450}
 
 
 def conv_flops_per_frame(spec):
@@ -36,6 +36,62 @@ def conv_flops_per_frame(spec):
     return 2 * conv, 2 * head
 
 
+def sustained_power(step, torch, seconds=3.0):
+    """Back-to-back steps for `seconds` while a thread reads the socket power from hwmon and, once, the shader clocks
+    from amd-smi.  The board holds this workload at its power cap by lowering the clock, so both belong beside the rate."""
+    import glob
+    import subprocess
+    import threading
+    pfiles = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") + \
+        glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average")
+    cfiles = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap")
+    watts, clocks, stop = [], [], threading.Event()
+
+    def read_int(path):
+        try:
+            return int(open(path).read().strip())
+        except (OSError, ValueError):
+            return None
+
+    def sampler():
+        t_start = time.perf_counter()
+        asked = False
+        while not stop.is_set():
+            if time.perf_counter() - t_start > 0.8 and pfiles:
+                v = read_int(pfiles[0])
+                if v:
+                    watts.append(v / 1e6)
+            if time.perf_counter() - t_start > 1.2 and not asked:
+                asked = True
+                try:
+                    o = subprocess.run(["amd-smi", "metric", "-c"], capture_output=True, text=True, timeout=10).stdout
+                    for line in o.splitlines():
+                        f = line.split()
+                        if len(f) >= 3 and f[0] == "CLK:" and f[1].isdigit() and len(clocks) < 8:
+                            clocks.append(int(f[1]))             # the first 8 entries are the GFX (XCD) clocks
+                except (OSError, subprocess.SubprocessError):
+                    pass
+            time.sleep(0.1)
+
+    th = threading.Thread(target=sampler)
+    th.start()
+    t0 = time.perf_counter()
+    n = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
+        n += 10
+    dt = time.perf_counter() - t0
+    stop.set()
+    th.join()
+    cap = read_int(cfiles[0]) if cfiles else None
+    return {"ms_per_step_sustained": dt * 1e3 / n, "steps": n,
+            "socket_w_mean": sum(watts) / len(watts) if watts else None, "socket_w_max": max(watts) if watts else None,
+            "cap_w": cap / 1e6 if cap else None,
+            "gfx_clk_mhz_mean": sum(clocks) / len(clocks) if clocks else None, "gfx_clk_mhz_max_state": 2400}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -44,6 +100,10 @@ def main():
     ap.add_argument("--workload", default="full_60s_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="add per-launch timings (one extra instrumented step)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the playback-window / similarity-filter / crossfade timings (profiling runs: only the decode steps)")
+    ap.add_argument("--power", action="store_true",
+                    help="add 3 s of back-to-back steps with the socket power (hwmon) and shader clock (amd-smi) read beside them")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -153,38 +213,42 @@ def main():
         result["launch_ms"] = dict(zip(names, [round(x, 4) for x in t]))
     vae.set_timing(0)
 
-    # Latency of re-decoding one playback window (3 s = 75 latent frames in the middle of the clip, analytic halo)
-    # into the resident waveform buffer: the call the paper's 8x windowed-decode figure is about (section 3.6).
-    pw = min(75, wl.n_frames)
-    pb = max(0, (wl.n_frames - pw) // 2)
-    for _ in range(3):
-        vae.decode_windowed(z, window=pw, halo=-1, frame_begin=pb, frame_end=pb + pw, out=out)
-    torch.cuda.synchronize()
-    reps = 50
-    p0 = time.perf_counter()
-    for _ in range(reps):
-        vae.decode_windowed(z, window=pw, halo=-1, frame_begin=pb, frame_end=pb + pw, out=out)
-    torch.cuda.synchronize()
-    pw_ms = (time.perf_counter() - p0) * 1e3 / reps
-    result["playback_window"] = {"frames": pw, "audio_s": pw / 25.0, "ms": pw_ms,
-                                 "speedup_vs_whole_clip_decode": ms_per_step / wl.n_clips / pw_ms}
-
-    # the two small kernels around the playback-window decode: similarity gate on the whole latent, 50 ms crossfade
-    import paper_2605_28657_amd as pa
-    z_prev = z.clone()
-    tail = out[0, :, :2400]
-    headv = out[0, :, 2400:4800]
-    xf = torch.empty((spec.out_channels, 2400), dtype=torch.float32, device="cuda:0")
-    small = {}
-    for name, fn in (("similarity_filter", lambda: pa.latent_similarity(z, z_prev, 1e-3)),
-                     ("crossfade_50ms", lambda: pa.crossfade(tail, headv, out=xf))):
-        fn(); torch.cuda.synchronize()
-        q0 = time.perf_counter()
-        for _ in range(200):
-            fn()
+    if not args.no_extras:
+        # Latency of re-decoding one playback window (3 s = 75 latent frames in the middle of the clip, analytic halo)
+        # into the resident waveform buffer: the call the paper's 8x windowed-decode figure is about (section 3.6).
+        pw = min(75, wl.n_frames)
+        pb = max(0, (wl.n_frames - pw) // 2)
+        for _ in range(3):
+            vae.decode_windowed(z, window=pw, halo=-1, frame_begin=pb, frame_end=pb + pw, out=out)
         torch.cuda.synchronize()
-        small[name + "_ms"] = (time.perf_counter() - q0) * 1e3 / 200
-    result["playback_window"].update(small)
+        reps = 50
+        p0 = time.perf_counter()
+        for _ in range(reps):
+            vae.decode_windowed(z, window=pw, halo=-1, frame_begin=pb, frame_end=pb + pw, out=out)
+        torch.cuda.synchronize()
+        pw_ms = (time.perf_counter() - p0) * 1e3 / reps
+        result["playback_window"] = {"frames": pw, "audio_s": pw / 25.0, "ms": pw_ms,
+                                     "speedup_vs_whole_clip_decode": ms_per_step / wl.n_clips / pw_ms}
+
+        # the two small kernels around the playback-window decode: similarity gate on the whole latent, 50 ms crossfade
+        import paper_2605_28657_amd as pa
+        z_prev = z.clone()
+        tail = out[0, :, :2400]
+        headv = out[0, :, 2400:4800]
+        xf = torch.empty((spec.out_channels, 2400), dtype=torch.float32, device="cuda:0")
+        small = {}
+        for name, fn in (("similarity_filter", lambda: pa.latent_similarity(z, z_prev, 1e-3)),
+                         ("crossfade_50ms", lambda: pa.crossfade(tail, headv, out=xf))):
+            fn(); torch.cuda.synchronize()
+            q0 = time.perf_counter()
+            for _ in range(200):
+                fn()
+            torch.cuda.synchronize()
+            small[name + "_ms"] = (time.perf_counter() - q0) * 1e3 / 200
+        result["playback_window"].update(small)
+
+    if args.power:
+        result["power"] = sustained_power(step, torch)
 
     if not args.no_cpu_baseline:
         # The oracle (fp32 build, as it stands) on a bounded sample: the first windows with their halo.

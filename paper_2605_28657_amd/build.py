@@ -7,6 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdemon_vae.so")
+PROBE = os.path.join(HERE, "mfma_probe")        # stand-alone measurement aid (sustained MFMA rate), see csrc/mfma_probe.hip
 SOURCES = ["host_plan.cpp", "api.hip", "kernels_io.hip", "kernels_f32.hip", "kernels_bf16.hip", "kernels_bf16_fused.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -34,7 +35,16 @@ def build() -> str:
         raise RuntimeError("link failed:\n" + r.stderr)
     for o in objs:
         os.remove(o)
+    build_probe()
     return LIB
+
+
+def build_probe() -> str:
+    cmd = ["hipcc"] + [f for f in FLAGS if f != "-fPIC"] + [os.path.join(CSRC, "mfma_probe.hip"), "-o", PROBE]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed on mfma_probe.hip:\n" + r.stderr)
+    return PROBE
 
 
 if __name__ == "__main__":
