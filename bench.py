@@ -229,6 +229,18 @@ def main():
         pw_ms = (time.perf_counter() - p0) * 1e3 / reps
         result["playback_window"] = {"frames": pw, "audio_s": pw / 25.0, "ms": pw_ms,
                                      "speedup_vs_whole_clip_decode": ms_per_step / wl.n_clips / pw_ms}
+        # the same call captured once into a HIP graph and replayed (31 launches per replay, no host work in between)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            vae.decode_windowed(z, window=pw, halo=-1, frame_begin=pb, frame_end=pb + pw, out=out)
+        graph.replay()
+        torch.cuda.synchronize()
+        p0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        result["playback_window"]["ms_graph_replay"] = (time.perf_counter() - p0) * 1e3 / reps
+        del graph
 
         # the two small kernels around the playback-window decode: similarity gate on the whole latent, 50 ms crossfade
         import paper_2605_28657_amd as pa

@@ -94,3 +94,26 @@ def test_240s_partial_redecode_equals_full_redecode():
     check_blocks(g, oracle_blocks(weights, lat2[0], (1994, 2046, 2102)), "dirty span")
     check_blocks(g, oracle_blocks(weights, lat2[0], (5996,)), "clip end")
     vae.close()
+
+
+def test_60s_playback_window_and_pcm16_render():
+    """The single 3 s playback window of the latency figure (frames 712..787 of the 60 s clip) and the 16-bit render
+    of the whole clip, in the launch configurations bench.py uses."""
+    wl = di.WORKLOADS["full_60s_bf16"]
+    vae, weights, lat = make_vae(wl)
+    zt = to_device(lat, "bf16")
+    whole = vae.decode_windowed(zt, window=wl.window, halo=-1)
+    pb, pw = (wl.n_frames - 75) // 2, 75
+    buf = torch.full_like(whole, 3.0)
+    vae.decode_windowed(zt, window=pw, halo=-1, frame_begin=pb, frame_end=pb + pw, out=buf)
+    assert torch.equal(buf[:, :, pb * S:(pb + pw) * S], whole[:, :, pb * S:(pb + pw) * S])      # bit for bit
+    assert float((buf[:, :, :pb * S] - 3.0).abs().max()) == 0.0 and float((buf[:, :, (pb + pw) * S:] - 3.0).abs().max()) == 0.0
+    check_blocks(buf[0].cpu().numpy(), oracle_blocks(weights, lat[0], (pb, pb + 36, pb + pw - BLOCK)), "playback window")
+    pcm = vae.decode_windowed_pcm16(zt, window=wl.window, halo=-1)
+    assert pcm.shape == (1, wl.n_frames * S, 2) and pcm.dtype == torch.int16
+    y = whole[0].cpu().numpy()
+    assert np.array_equal(pcm[0].cpu().numpy(), oracle.pcm16(y))                                 # the fp32 decision, bit for bit
+    for b, ref in oracle_blocks(weights, lat[0], (0, 749, 1496)).items():                        # and close to the oracle's render
+        d = pcm[0, b * S:(b + BLOCK) * S].cpu().numpy().astype(np.int32) - oracle.pcm16(ref, dtype=np.float64).astype(np.int32)
+        assert np.abs(d).max() <= 32767 * 2e-2 + 1
+    vae.close()

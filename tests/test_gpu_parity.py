@@ -341,3 +341,36 @@ def test_filter_and_crossfade_argument_errors():
     assert lib.demon_vae_crossfade(None, 4, p, 4, p, 4, 1, 4, None) == pa.DEMON_ERR_INVALID_ARG
     assert lib.demon_vae_crossfade(p, -4, p, 4, p, 4, 1, 4, None) == pa.DEMON_ERR_INVALID_ARG
     torch.cuda.synchronize()
+
+
+def test_playback_window_decode_replays_from_a_hip_graph():
+    """The decode allocates nothing and records no memset once its window plan is cached, so a caller may capture it
+    (the playback-window call of a streaming loop) and replay it; every replay is checked against the eager result,
+    with eager work and synchronisations in between, also after the latent changed in place."""
+    spec = di.DecoderSpec(64, (4, 2), (128, 64), (1, 3, 9))
+    T, S = 90, spec.total_stride
+    vae, w, z = make(spec, "bf16", T, max_extended_frames=3 * T)
+    zt = to_device(z, "bf16")
+    out_eager = torch.zeros((1, spec.out_channels, T * S), device="cuda:0")
+    out_graph = torch.zeros_like(out_eager)
+    args = dict(window=25, halo=-1, frame_begin=30, frame_end=55)
+    vae.decode_windowed(zt, out=out_eager, **args)              # also caches the plan (its slot table is uploaded here)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        vae.decode_windowed(zt, out=out_graph, **args)
+    for rep in range(4):
+        if rep == 2:                                            # new latent content, same buffers
+            z2 = np.stack([di.make_latent(spec.latent_channels, T, 77, bf16=True)])
+            zt.copy_(to_device(z2, "bf16"))
+            vae.decode_windowed(zt, out=out_eager, **args)
+        out_graph.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_graph, out_eager), rep
+        assert float(out_graph[:, :, :30 * S].abs().max()) == 0.0 and float(out_graph[:, :, 55 * S:].abs().max()) == 0.0
+        _ = vae.decode(zt)                                      # unrelated eager work between replays
+        torch.cuda.synchronize()
+    ref = oracle.decode(spec, w, z2)
+    assert_close(out_graph.cpu().numpy()[:, :, 30 * S:55 * S], ref[:, :, 30 * S:55 * S], "bf16", "graph replay")
+    vae.close()
