@@ -71,6 +71,9 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     constexpr int AS_BYTES = 2 * CH * LDK * 2, XS_BYTES = XR_MAX * LDK * 2;
     constexpr int SMEM_BYTES = (AS_BYTES + XS_BYTES > STG_BYTES) ? AS_BYTES + XS_BYTES : STG_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
+    // per-channel vectors used after the K loop (bias of both convolutions, Snake between them): read from global
+    // memory where they are used, each load would be waited for in turn
+    __shared__ __attribute__((aligned(16))) float prm[4 * CH];     // b7 | a2 | ib2 | b1
     uint16_t* As = reinterpret_cast<uint16_t*>(smem);
     uint16_t* Xs = reinterpret_cast<uint16_t*>(smem + AS_BYTES);
 
@@ -148,7 +151,6 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
         }
     };
 
-    // accumulators start at the bias: lane (j, h) holds rows (channels) mi*32 + 8g + 4h + {0..3}
     u32x4 rw1[W1_CH / 256];      // the 1x1 weights on their way to LDS
     auto load_w1 = [&]() __attribute__((always_inline)) {
         const u32x4* src = reinterpret_cast<const u32x4*>(p.w1);
@@ -156,25 +158,17 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
         for (int it = 0; it < W1_CH / 256; ++it) rw1[it] = src[tid + it * 256];
     };
 
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const float4 b4 = *reinterpret_cast<const float4*>(p.b7 + mi * 32 + 8 * g + 4 * h);
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni) {
-                acc[mi][ni][4 * g + 0] = b4.x; acc[mi][ni][4 * g + 1] = b4.y;
-                acc[mi][ni][4 * g + 2] = b4.z; acc[mi][ni][4 * g + 3] = b4.w;
-            }
-        }
-
+    // every request of the prologue is issued before the first result is waited for, in the order of use
     load_a(0);
     load_x(0);
-    store_a(0);
-    store_x();
-    __syncthreads();
-
+    constexpr int PRM_ITERS = 4 * CH / 256;
+    float pv[PRM_ITERS];
+#pragma unroll
+    for (int it = 0; it < PRM_ITERS; ++it) {
+        const int i = tid + it * 256, which = i / CH, c = i % CH;
+        const float* src = which == 0 ? p.b7 : which == 1 ? p.a2 : which == 2 ? p.ib2 : p.b1;
+        pv[it] = src[c];
+    }
     // The residual values this lane adds in the epilogue (4 consecutive channels of RPI-strided rows) are fetched
     // ahead of time: loaded where they are used, each would be waited for in turn, a chain of memory latencies per
     // tile.  With 64 channels there are registers to hold them through the K loop; with 128 they are fetched after
@@ -193,6 +187,25 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
                     rs_x, (unsigned)((n0 + wn * WTN + ni * 32 + it * RPI + rl) * CH + 4 * cl) * 2u, 0, 0);
     };
     if (EARLY_RES) load_res();
+    store_a(0);
+    store_x();
+#pragma unroll
+    for (int it = 0; it < PRM_ITERS; ++it) prm[tid + it * 256] = pv[it];
+    __syncthreads();
+
+    // accumulators start at the bias: lane (j, h) holds rows (channels) mi*32 + 8g + 4h + {0..3}
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float4 b4 = *reinterpret_cast<const float4*>(&prm[mi * 32 + 8 * g + 4 * h]);
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) {
+                acc[mi][ni][4 * g + 0] = b4.x; acc[mi][ni][4 * g + 1] = b4.y;
+                acc[mi][ni][4 * g + 2] = b4.z; acc[mi][ni][4 * g + 3] = b4.w;
+            }
+        }
 
     // ---- dilated conv: K loop over (chunk, tap) stages, fixed order
     int chunk = 0, tap = 0;
@@ -249,8 +262,8 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int c = mi * 32 + 8 * g + 4 * h;
-            const float4 a4 = *reinterpret_cast<const float4*>(p.a2 + c);
-            const float4 i4 = *reinterpret_cast<const float4*>(p.ib2 + c);
+            const float4 a4 = *reinterpret_cast<const float4*>(&prm[CH + c]);
+            const float4 i4 = *reinterpret_cast<const float4*>(&prm[2 * CH + c]);
 #pragma unroll
             for (int ni = 0; ni < TN; ++ni) {
                 const float v0 = snake_fast(acc[mi][ni][4 * g + 0], a4.x, i4.x);
@@ -270,7 +283,7 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const float4 b4 = *reinterpret_cast<const float4*>(p.b1 + mi * 32 + 8 * g + 4 * h);
+            const float4 b4 = *reinterpret_cast<const float4*>(&prm[3 * CH + mi * 32 + 8 * g + 4 * h]);
 #pragma unroll
             for (int ni = 0; ni < TN; ++ni) {
                 acc[mi][ni][4 * g + 0] = b4.x; acc[mi][ni][4 * g + 1] = b4.y;
