@@ -207,17 +207,10 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
             }
         }
 
-    // ---- dilated conv: K loop over (chunk, tap) stages, fixed order
+    // ---- dilated conv: K loop over (chunk, tap) stages, fixed order.  The last stage is peeled: its shadow hides the
+    // fetch of the 1x1 weights, and registers that are only written there must not be carried through the loop.
     int chunk = 0, tap = 0;
-    for (int stage = 0; stage < nstages; ++stage) {
-        int ntap = tap + 1, nchunk = chunk;
-        if (ntap == p.ntaps) { ntap = 0; ++nchunk; }
-        const bool more = stage + 1 < nstages;
-        const bool new_chunk = more && nchunk != chunk;
-        if (more) load_a(stage + 1);
-        else load_w1();                            // last stage: its shadow hides the fetch of the 1x1 weights
-        if (new_chunk) load_x(nchunk);
-
+    auto mma_stage = [&](int stage) __attribute__((always_inline)) {
         const int off = p.tap0 + tap * p.tap_step - minoff;
         const uint16_t* abase = &As[(stage & 1) * CH * LDK + j * LDK + h * 8];
         const uint16_t* xbase = &Xs[(wn * WTN + j + off) * LDK + h * 8];
@@ -234,16 +227,24 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
                 for (int ni = 0; ni < TN; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
         }
-        if (more) {
-            if (new_chunk) {
-                __syncthreads();
-                store_x();
-            }
-            store_a((stage + 1) & 1);
+    };
+    for (int stage = 0; stage + 1 < nstages; ++stage) {
+        int ntap = tap + 1, nchunk = chunk;
+        if (ntap == p.ntaps) { ntap = 0; ++nchunk; }
+        const bool new_chunk = nchunk != chunk;
+        load_a(stage + 1);
+        if (new_chunk) load_x(nchunk);
+        mma_stage(stage);
+        if (new_chunk) {
             __syncthreads();
+            store_x();
         }
+        store_a((stage + 1) & 1);
+        __syncthreads();
         tap = ntap; chunk = nchunk;
     }
+    load_w1();
+    mma_stage(nstages - 1);
 
     if (!EARLY_RES) load_res();
 
