@@ -22,6 +22,15 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
     return __builtin_bit_cast(uint16_t, b);
 }
 
+// two fp32 values -> one dword of two bf16 (lo in bits 0..15), one packed conversion (round to nearest even)
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
 // snake(x) = x + sin(alpha x)^2 / (beta + 1e-9); inv_beta = 1 / (beta + 1e-9) is prepared on the host.
 __device__ __forceinline__ float snake_precise(float x, float alpha, float inv_beta)
 {

@@ -358,15 +358,12 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
             if (EMIT > 0) {
                 v0 = snake_fast(v0, oa.x, ob.x); v1 = snake_fast(v1, oa.y, ob.y);
                 v2 = snake_fast(v2, oa.z, ob.z); v3 = snake_fast(v3, oa.w, ob.w);
-                const uint32_t h0 = f32_to_bf16_bits(v0), h1 = f32_to_bf16_bits(v1);
-                const uint32_t h2 = f32_to_bf16_bits(v2), h3 = f32_to_bf16_bits(v3);
-                const u32x2 sh = {h0 | (h1 << 16), h2 | (h3 << 16)};
+                const u32x2 sh = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
                 __builtin_amdgcn_raw_buffer_store_b64(sh, rs_a, e * 2u, 0, 0);
                 if (EMIT > 1) {
-                    const u32x2 sl = {(uint32_t)f32_to_bf16_bits(v0 - __uint_as_float(h0 << 16)) |
-                                          ((uint32_t)f32_to_bf16_bits(v1 - __uint_as_float(h1 << 16)) << 16),
-                                      (uint32_t)f32_to_bf16_bits(v2 - __uint_as_float(h2 << 16)) |
-                                          ((uint32_t)f32_to_bf16_bits(v3 - __uint_as_float(h3 << 16)) << 16)};
+                    // lo plane: what the hi plane's rounding left over
+                    const u32x2 sl = {pack_bf16x2(v0 - __uint_as_float(sh[0] << 16), v1 - __uint_as_float(sh[0] & 0xffff0000u)),
+                                      pack_bf16x2(v2 - __uint_as_float(sh[1] << 16), v3 - __uint_as_float(sh[1] & 0xffff0000u))};
                     __builtin_amdgcn_raw_buffer_store_b64(sl, rs_al, e * 2u, 0, 0);
                 }
             }

@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
                 float e0 = (float)hv[2 * q], e1 = (float)hv[2 * q + 1];
                 e0 = snake_fast(e0, al[2 * q], ib[2 * q]);
                 e1 = snake_fast(e1, al[2 * q + 1], ib[2 * q + 1]);
-                v[q] = (uint32_t)f32_to_bf16_bits(e0) | ((uint32_t)f32_to_bf16_bits(e1) << 16);
+                v[q] = pack_bf16x2(e0, e1);
             }
             *reinterpret_cast<u32x4*>(&Xs[xr * LDK + seg * 8]) = v;
         }
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     }
 
     // ---- bias + Snake on the accumulators; repack them as the B fragments of the 1x1 conv
-    bf16x8 mid[CH / 16][TN];
+    u32x4 mid[CH / 16][TN];      // bf16x8 fragments, built from packed pairs
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi) {
 #pragma unroll
@@ -271,9 +271,9 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
                 const float v1 = snake_fast(acc[mi][ni][4 * g + 1], a4.y, i4.y);
                 const float v2 = snake_fast(acc[mi][ni][4 * g + 2], a4.z, i4.z);
                 const float v3 = snake_fast(acc[mi][ni][4 * g + 3], a4.w, i4.w);
-                bf16x8& f = mid[2 * mi + g / 2][ni];
-                f[4 * (g & 1) + 0] = (__bf16)v0; f[4 * (g & 1) + 1] = (__bf16)v1;
-                f[4 * (g & 1) + 2] = (__bf16)v2; f[4 * (g & 1) + 3] = (__bf16)v3;
+                u32x4& f = mid[2 * mi + g / 2][ni];
+                f[2 * (g & 1) + 0] = pack_bf16x2(v0, v1);
+                f[2 * (g & 1) + 1] = pack_bf16x2(v2, v3);
             }
         }
     }
@@ -300,7 +300,7 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
         for (int mo = 0; mo < TM; ++mo)
 #pragma unroll
             for (int ni = 0; ni < TN; ++ni)
-                acc[mo][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mo], mid[kk][ni], acc[mo][ni], 0, 0, 0);
+                acc[mo][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mo], __builtin_bit_cast(bf16x8, mid[kk][ni]), acc[mo][ni], 0, 0, 0);
     }
 
     // ---- bias + residual, fp32 store to the other buffer.  Each wave transposes 32 columns at a time
@@ -336,8 +336,7 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
                 v0 = hres_round(v0); v1 = hres_round(v1); v2 = hres_round(v2); v3 = hres_round(v3);
                 v0 = snake_fast(v0, a4.x, i4.x); v1 = snake_fast(v1, a4.y, i4.y);
                 v2 = snake_fast(v2, a4.z, i4.z); v3 = snake_fast(v3, a4.w, i4.w);
-                const u32x2 sh = {(uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16),
-                                  (uint32_t)f32_to_bf16_bits(v2) | ((uint32_t)f32_to_bf16_bits(v3) << 16)};
+                const u32x2 sh = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
                 __builtin_amdgcn_raw_buffer_store_b64(sh, rs_a, e * 2u, 0, 0);
             }
         }
