@@ -229,7 +229,16 @@ def main():
         pw_ms = (time.perf_counter() - p0) * 1e3 / reps
         result["playback_window"] = {"frames": pw, "audio_s": pw / 25.0, "ms": pw_ms,
                                      "speedup_vs_whole_clip_decode": ms_per_step / wl.n_clips / pw_ms}
+        # a window that moves by one frame per call: a new window grid (table upload on the stream) every call
+        p0 = time.perf_counter()
+        for i in range(reps):
+            b = (pb + i) % max(1, wl.n_frames - pw)
+            vae.decode_windowed(z, window=pw, halo=-1, frame_begin=b, frame_end=b + pw, out=out)
+        torch.cuda.synchronize()
+        result["playback_window"]["ms_moving_window"] = (time.perf_counter() - p0) * 1e3 / reps
         # the same call captured once into a HIP graph and replayed (31 launches per replay, no host work in between)
+        vae.decode_windowed(z, window=pw, halo=-1, frame_begin=pb, frame_end=pb + pw, out=out)     # its grid must be cached
+        torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             vae.decode_windowed(z, window=pw, halo=-1, frame_begin=pb, frame_end=pb + pw, out=out)

@@ -17,8 +17,13 @@
  *   snake(x) = x + sin(alpha_c x)^2 / (beta_c + 1e-9), per channel c.
  *
  * All entry points return a status and never throw or abort.  A handle may be
- * used by one host thread at a time.  Decode calls are asynchronous on the
- * given HIP stream and do not synchronise; they allocate nothing.
+ * used by one host thread at a time, and its decode calls must go to one
+ * stream (or be ordered by the caller): they share the handle's workspace.
+ * Decode calls are asynchronous on the given HIP stream and allocate nothing.
+ * A window grid (clips, frames, range, window, halo) seen for the first time
+ * has its table uploaded by a small copy on the same stream; the 8 most
+ * recent grids are kept.  Under stream capture only cached grids are
+ * accepted (issue the call once before capturing).
  */
 #ifndef DEMON_VAE_H
 #define DEMON_VAE_H

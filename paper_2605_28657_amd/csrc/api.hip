@@ -72,6 +72,8 @@ struct demon_vae {
     void* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     float* head_out = nullptr;                     // planar window waveforms [out_channels, cap_frames*S]
     Slot* d_slot_arena = nullptr;
+    Slot* h_slot_stage = nullptr;                  // pinned staging of the window tables, one region per cached plan
+    hipEvent_t plan_copied[kPlanCache] = {};       // recorded after a table's upload: its staging region is free again
     Plan plans[kPlanCache];
     unsigned long long use_counter = 0;
 
@@ -167,7 +169,10 @@ void build_slots(int n_clips, int n_frames, int fb, int fe, int window, int halo
     *total = row; *max_len = ml; *max_int = mi;
 }
 
-demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, int window, int halo, Plan** out)
+// Looks the window grid up in the plan cache; on a miss builds the table, writes it to the pinned staging region of the
+// least recently used entry and uploads it with a copy on the decode stream, so the call stays asynchronous: kernels of
+// earlier calls that still read the replaced table precede the copy on that stream.
+demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, int window, int halo, hipStream_t stream, Plan** out)
 {
     ++v->use_counter;
     Plan* victim = &v->plans[0];
@@ -189,15 +194,22 @@ demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, i
     build_slots(n_clips, n_frames, fb, fe, window, halo, &slots, &total, &max_len, &max_int);
     if (total > v->cap_frames)
         return fail(DEMON_ERR_WORKSPACE, "extended windows need %lld frames, the workspace holds %lld", total, v->cap_frames);
-    if (victim->valid) {
-        // the table being replaced may still be read by kernels of an earlier call
-        hipError_t e = hipDeviceSynchronize();
-        if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
-    }
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    hipError_t e = hipStreamIsCapturing(stream, &cap);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamIsCapturing");
+    if (cap != hipStreamCaptureStatusNone)
+        return fail(DEMON_ERR_INVALID_ARG, "this window grid is not cached: issue the call once outside the stream capture first");
     const int idx = (int)(victim - v->plans);
+    // the staging region may still be the source of this entry's previous upload
+    e = hipEventSynchronize(v->plan_copied[idx]);
+    if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize(window table)");
+    victim->valid = false;
+    Slot* h = v->h_slot_stage + (size_t)idx * kMaxSlots;
     Slot* d = v->d_slot_arena + (size_t)idx * kMaxSlots;
-    hipError_t e = hipMemcpy(d, slots.data(), sizeof(Slot) * slots.size(), hipMemcpyHostToDevice);
-    if (e != hipSuccess) return hip_fail(e, "hipMemcpy(window table)");
+    memcpy(h, slots.data(), sizeof(Slot) * slots.size());
+    e = hipMemcpyAsync(d, h, sizeof(Slot) * slots.size(), hipMemcpyHostToDevice, stream);
+    if (e == hipSuccess) e = hipEventRecord(v->plan_copied[idx], stream);
+    if (e != hipSuccess) return hip_fail(e, "uploading the window table");
     victim->valid = true;
     victim->n_clips = n_clips; victim->n_frames = n_frames; victim->frame_begin = fb; victim->frame_end = fe;
     victim->window = window; victim->halo = halo;
@@ -213,7 +225,7 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
                         int window, int halo, float* d_out, int16_t* d_pcm, hipStream_t stream)
 {
     Plan* plan = nullptr;
-    demon_status rc = get_plan(v, n_clips, n_frames, fb, fe, window, halo, &plan);
+    demon_status rc = get_plan(v, n_clips, n_frames, fb, fe, window, halo, stream, &plan);
     if (rc != DEMON_OK) return rc;
     const bool bf = v->dtype == DEMON_BF16;
     const Slot* slots = plan->d_slots;
@@ -522,12 +534,16 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
         for (void* b : v->buf) if (b) (void)hipFree(b);
         if (v->head_out) (void)hipFree(v->head_out);
         if (v->d_slot_arena) (void)hipFree(v->d_slot_arena);
+        if (v->h_slot_stage) (void)hipHostFree(v->h_slot_stage);
+        for (hipEvent_t ev : v->plan_copied) if (ev) (void)hipEventDestroy(ev);
     };
     hipError_t e = hipMalloc(&v->d_params, ar.bytes.size());
     // fp32 path: 4 bytes per element; bf16 path: half residual stream (2 bytes), bf16 operand buffers with hi and lo planes (4)
     for (int i = 0; e == hipSuccess && i < (bf ? 5 : 3); ++i) e = hipMalloc(&v->buf[i], act_elems * ((bf && i < 2) ? 2 : 4));
     if (e == hipSuccess) e = hipMalloc((void**)&v->head_out, head_bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&v->d_slot_arena, sizeof(Slot) * kMaxSlots * kPlanCache);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&v->h_slot_stage, sizeof(Slot) * kMaxSlots * kPlanCache, hipHostMallocDefault);
+    for (int i = 0; e == hipSuccess && i < kPlanCache; ++i) e = hipEventCreateWithFlags(&v->plan_copied[i], hipEventDisableTiming);
     if (e == hipSuccess) e = hipMemcpy(v->d_params, ar.bytes.data(), ar.bytes.size(), hipMemcpyHostToDevice);
     if (e != hipSuccess) { cleanup(); return hip_fail(e, "allocating decoder memory"); }
 
@@ -555,6 +571,8 @@ void demon_vae_destroy(demon_vae* v)
     for (void* b : v->buf) if (b) (void)hipFree(b);
     (void)hipFree(v->head_out);
     (void)hipFree(v->d_slot_arena);
+    (void)hipHostFree(v->h_slot_stage);
+    for (hipEvent_t e : v->plan_copied) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : v->events) (void)hipEventDestroy(e);
     delete v;
 }

@@ -374,3 +374,37 @@ def test_playback_window_decode_replays_from_a_hip_graph():
     ref = oracle.decode(spec, w, z2)
     assert_close(out_graph.cpu().numpy()[:, :, 30 * S:55 * S], ref[:, :, 30 * S:55 * S], "bf16", "graph replay")
     vae.close()
+
+
+def test_sliding_playback_window_cycles_the_plan_cache():
+    """A playback window that moves every call is a new window grid every call: more grids than the cache holds,
+    back to back without synchronising in between, each written into the same waveform buffer."""
+    spec = STACK_V1
+    T, S = 64, spec.total_stride
+    vae, w, z = make(spec, "bf16", T, max_extended_frames=2 * T)
+    zt = to_device(z, "bf16")
+    full = vae.decode(zt)
+    buf = torch.zeros_like(full)
+    for begin in range(0, T, 3):                             # 22 different grids, 8 cache entries
+        vae.decode_windowed(zt, window=3, halo=-1, frame_begin=begin, frame_end=min(T, begin + 3), out=buf)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, full)
+    for begin in (30, 0, 61, 30):                            # revisits and a short last window
+        buf[:, :, begin * S:].zero_()
+        vae.decode_windowed(zt, window=7, halo=-1, frame_begin=begin, frame_end=min(T, begin + 7), out=buf)
+        e = min(T, begin + 7)
+        assert torch.equal(buf[:, :, begin * S:e * S], full[:, :, begin * S:e * S])
+        buf.copy_(full)
+    # a grid that is not cached cannot be captured into a graph; the error names the remedy
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        g.capture_begin()
+        try:
+            with pytest.raises(pa.DemonError) as ei:
+                vae.decode_windowed(zt, window=5, halo=-1, frame_begin=11, frame_end=16, out=buf)
+        finally:
+            g.capture_end()
+    assert ei.value.status == pa.DEMON_ERR_INVALID_ARG and "capture" in ei.value.message
+    torch.cuda.synchronize()
+    vae.close()
