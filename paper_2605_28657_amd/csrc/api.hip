@@ -36,7 +36,9 @@ struct ConvLayer {
     const float* out_alpha = nullptr;  const float* out_inv_beta = nullptr;
 };
 
-struct ResUnit { ConvLayer dilated, pointwise; bool fused = false; const uint16_t* w1_fused = nullptr; };
+// fused: one kernel per unit that reads the half residual stream itself (64, 128 channels);
+// wide: one kernel per unit that reads the pre-activated operand (256 channels); else two kernels
+struct ResUnit { ConvLayer dilated, pointwise; bool fused = false, wide = false; const uint16_t* w1_fused = nullptr; };
 struct Block { ConvLayer up; std::vector<ResUnit> res; };
 
 struct Plan {
@@ -297,14 +299,14 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
             }
         }
     } else {
-        // ---- bf16 path.  h (fp32) ping-pongs between buf[0] and buf[1]; the activated bf16 operand `a` of the
-        // next unfused layer ping-pongs between buf[3] and buf[4]; buf[2] holds the activated branch tensor
-        // between the dilated and the 1x1 conv.  Each producer writes `a` with its consumer's Snake.
+        // ---- bf16 path.  h (half) ping-pongs between buf[0] and buf[1]; the activated bf16 operand `a` of the
+        // next layer that wants one ping-pongs between buf[3] and buf[4]; buf[2] holds the activated branch tensor
+        // between the dilated and the 1x1 conv of a two-kernel unit.  Each producer writes `a` with its consumer's Snake.
         uint16_t* acur = (uint16_t*)v->buf[3];
         uint16_t* aoth = (uint16_t*)v->buf[4];
         uint16_t* mid = (uint16_t*)v->buf[2];
         // the layer that consumes the output of block bi's unit ui (ui = -1: of its transposed conv);
-        // nullptr when that layer reads the fp32 stream itself (fused unit, head)
+        // nullptr when that layer reads the residual stream itself (narrow fused unit, head)
         auto consumer = [&](size_t bi, int ui) -> const ConvLayer* {
             const Block& B = v->blocks[bi];
             if (ui + 1 < (int)B.res.size()) return B.res[ui + 1].fused ? nullptr : &B.res[ui + 1].dilated;
@@ -346,6 +348,19 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
                     if (C && C->split_in) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a split-operand layer");
                     HIP_TRY(launch_res_unit_fused(f, stream), "fused residual unit");
                     std::swap(cur, other);
+                    HIP_TRY(mark(2), "event");
+                } else if (U.wide) {
+                    WideArgs f;
+                    f.xa = acur; f.y = cur;
+                    if (C) { f.ya = aoth; f.a3 = C->in_alpha; f.ib3 = C->in_inv_beta; }
+                    f.w7 = (const uint16_t*)U.dilated.w; f.w1 = U.w1_fused;
+                    f.b7 = U.dilated.bias; f.b1 = U.pointwise.bias;
+                    f.a2 = U.dilated.out_alpha; f.ib2 = U.dilated.out_inv_beta;
+                    f.slots = slots; f.n_slots = ns; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
+                    f.r = r; f.c = U.dilated.cin; f.ntaps = U.dilated.ntaps; f.dil = U.dilated.dil;
+                    if (C && C->split_in) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a split-operand layer");
+                    HIP_TRY(launch_res_unit_wide(f, stream), "fused residual unit (256 channels)");
+                    if (C) std::swap(acur, aoth);
                     HIP_TRY(mark(2), "event");
                 } else {
                     ConvArgs d = conv_args(U.dilated, acur, nullptr, nullptr);
@@ -461,15 +476,18 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
             }
             U.fused = bf && (c == 64 || c == 128) && (st.res_kernel - 1) * st.dilations[j] <= 64 && !D.split_out && g_allow_fused;
             if (U.fused) D.variant = (c == 64) ? 1 : 0;      // weight blocks of C x 64
+            U.wide = bf && c == 256 && (st.res_kernel - 1) * st.dilations[j] <= 64 && !D.split_out && g_allow_fused;
+            if (U.wide) D.variant = 3;                       // weight blocks of 256 x 32
             Pending pd{&D, 0, 0, {}, {}, true, true};
             pd.in = pack_snake(ar, w, w + c, c, bf);     w += 2 * c;
             pd.w = pack_conv(ar, w, D, bf);              w += (size_t)c * c * st.res_kernel;
             pd.bias = pack_floats(ar, w, c);             w += c;
             pd.outp = pack_snake(ar, w, w + c, c, bf);   w += 2 * c;      // Snake between the two convolutions
             Pending pp{&P, 0, 0, {}, {}, false, false};
-            if (U.fused) {
+            if (U.fused || U.wide) {
                 const size_t off = ar.reserve((size_t)c * c * 2);
-                pack_w1_fused(w, c, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
+                if (U.wide) pack_w1_wide(w, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
+                else pack_w1_fused(w, c, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
                 fused_fix.push_back({&U, off});
             }
             pp.w = pack_conv(ar, w, P, bf);              w += (size_t)c * c;

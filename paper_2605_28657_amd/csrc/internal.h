@@ -101,6 +101,21 @@ struct FusedArgs {
 hipError_t launch_res_unit_fused(const FusedArgs& a, hipStream_t stream);
 void pack_w1_fused(const float* w, int C, uint16_t* dst);
 
+// fused residual unit for 256 channels (kernels_bf16_wide.hip): reads the pre-activated bf16 operand, updates the
+// half residual stream in place
+struct WideArgs {
+    const uint16_t* xa; void* y;
+    uint16_t* ya = nullptr;  // optional: bf16(snake(y; a3, ib3)) for the consumer; must not be the buffer of xa
+    const float* a3 = nullptr; const float* ib3 = nullptr;
+    const uint16_t* w7;      // packed as pack_bf16 does for variant 3 (MT = 256, KC = 32)
+    const uint16_t* w1;      // packed by pack_w1_wide
+    const float* b7; const float* b1; const float* a2; const float* ib2;
+    const Slot* slots; int n_slots, max_len, max_int, margin;
+    int r, c, ntaps, dil;
+};
+hipError_t launch_res_unit_wide(const WideArgs& a, hipStream_t stream);
+void pack_w1_wide(const float* w /*[256][256]*/, uint16_t* dst);
+
 struct IoArgs {
     const Slot* slots; int n_slots; int max_len;
 };

@@ -57,7 +57,8 @@ struct MfmaParams {
 };
 
 struct Variant { int MT, NT, KC; };
-static const Variant kVariants[3] = {{128, 128, 64}, {64, 256, 64}, {32, 128, 16}};
+// variant 3 only names a weight layout: blocks of 256 x 32 for the fused 256-channel unit (kernels_bf16_wide.hip)
+static const Variant kVariants[4] = {{128, 128, 64}, {64, 256, 64}, {32, 128, 16}, {256, 128, 32}};
 
 int choose_variant_bf16(int cin, int m, bool split_in)
 {

@@ -1,0 +1,300 @@
+// Fused residual unit for 256 channels:
+//     h += W1 * snake2(W7 (*) a + b7) + b1,      a = bf16(snake1(h)) written by the producer of h
+// in one kernel: the activated branch tensor between the two convolutions never goes to HBM, and the 1x1
+// convolution (a short reduction with a long epilogue, bound by HBM when it runs on its own) costs one more
+// K loop instead of a launch.
+//
+// Workgroup = 4 waves, tile = all 256 channels x 128 time columns, every wave all 256 rows of its 32 columns
+// (8 accumulator tiles of 32 x 32).  The dilated convolution runs as in kernels_bf16.hip on the pre-activated
+// bf16 operand, with K stages of 32 channels so that two workgroups fit the LDS of a CU.  As in the narrow fused
+// unit, a lane of an accumulator tile holds column j and rows 8g + 4h + {0..3}, which after bias + Snake are the
+// B fragments of the 1x1 convolution once its K axis is permuted to that order (fused_k_to_channel); its weights,
+// 128 KB, do not fit the LDS and are streamed through the weight buffers in 8 blocks of 32 k-slots.
+// The residual stream is updated in place (only this tile reads or writes its elements); the emitted operand of
+// the next layer goes to a second buffer because neighbouring tiles still read this tile's input rows.
+#include <algorithm>
+
+#include "device_common.h"
+
+namespace demon {
+
+namespace {
+
+constexpr int W_CH = 256, W_KC = 32, W_LDK = W_KC + 8, W_NT = 128, W_TM = W_CH / 32, W_MAXSPAN = 64;
+constexpr int W_XR_MAX = W_NT + W_MAXSPAN;
+constexpr int W_SEGS = W_KC / 8, W_RPP = 256 / W_SEGS;
+constexpr int W_A_CH = W_CH * W_SEGS, W_A_ITERS = W_A_CH / 256;
+constexpr int W_X_ITERS = (W_XR_MAX + W_RPP - 1) / W_RPP;
+constexpr int W_NCHUNKS = W_CH / W_KC;
+constexpr int W_GRP = 64;                        // channels transposed at a time in the epilogue
+constexpr int W_LDT = W_GRP + 4;
+
+struct WideParams {
+    const uint16_t* xa;          // activated input, bf16 [rows][256]
+    hres_t* y;                   // residual stream, in place
+    uint16_t* ya;                // optional bf16(snake_next(y)) (EMIT); not the buffer of xa
+    const uint16_t* w7;          // [chunk][tap] blocks of 256 x 32 bf16
+    const uint16_t* w1;          // [chunk] blocks of 256 x 32 bf16, K axis permuted
+    const float* b7; const float* b1;
+    const float* a2; const float* ib2;    // Snake between the two convolutions (alpha in revolutions, 1/(beta+eps))
+    const float* a3; const float* ib3;    // Snake of the consumer (EMIT)
+    const Slot* slots;
+    int r, ntaps, tap0, tap_step, margin;
+};
+
+template <bool EMIT>
+__global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
+{
+    constexpr int CH = W_CH, KC = W_KC, LDK = W_LDK, NT = W_NT, TM = W_TM;
+    constexpr int A_ITERS = W_A_ITERS, X_ITERS = W_X_ITERS, SEGS = W_SEGS, RPP = W_RPP;
+    constexpr int AS_BYTES = 2 * CH * LDK * 2, XS_BYTES = W_XR_MAX * LDK * 2;
+    constexpr int STG_BYTES = 4 * 32 * W_LDT * 4;
+    constexpr int SMEM_BYTES = (AS_BYTES + XS_BYTES > STG_BYTES) ? AS_BYTES + XS_BYTES : STG_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
+    __shared__ __attribute__((aligned(16))) float prm[4 * CH];     // b7 | a2 | ib2 | b1
+    uint16_t* As = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* Xs = reinterpret_cast<uint16_t*>(smem + AS_BYTES);
+
+    const Slot s = p.slots[blockIdx.y];
+    const int nrows = s.len * p.r;
+    const int out_lo = max(0, s.crop * p.r - p.margin);
+    const int out_hi = min(nrows, (s.crop + s.n_int) * p.r + p.margin);
+    const int n0 = out_lo + blockIdx.x * NT;
+    if (n0 >= out_hi) return;
+    const long long rowbase = (long long)s.row0 * p.r;
+
+    const int last_off = p.tap0 + (p.ntaps - 1) * p.tap_step;
+    const int minoff = min(p.tap0, last_off);
+    const int XR = NT + max(p.tap0, last_off) - minoff;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wn = tid >> 6;
+    const int j = lane & 31, h = lane >> 5;
+    const int seg = tid % SEGS, xr0 = tid / SEGS;
+
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.xa + rowbase * CH, (unsigned)nrows * CH * 2u);
+    const __amdgpu_buffer_rsrc_t rs_y = make_rsrc(p.y + rowbase * CH, (unsigned)out_hi * CH * (unsigned)sizeof(hres_t));
+    const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.ya + rowbase * CH, EMIT ? (unsigned)out_hi * CH * 2u : 0u);
+    const int nstages = W_NCHUNKS * p.ntaps;
+    const __amdgpu_buffer_rsrc_t rs_w7 = make_rsrc(p.w7, (unsigned)nstages * (W_A_CH * 16u));
+    const __amdgpu_buffer_rsrc_t rs_w1 = make_rsrc(p.w1, (unsigned)W_NCHUNKS * (W_A_CH * 16u));
+
+    const unsigned a_voff = tid * 16u;
+    const unsigned x_voff = ((unsigned)((n0 + minoff + xr0) * CH) + seg * 8u) * 2u;      // may wrap "negative": out of range
+    constexpr unsigned x_row_step = RPP * CH * 2u;
+
+    u32x4 ra[A_ITERS];
+    u32x4 rx[X_ITERS];
+    auto load_a = [&](__amdgpu_buffer_rsrc_t rs, int block) __attribute__((always_inline)) {
+        const unsigned base = (unsigned)block * (W_A_CH * 16u);
+#pragma unroll
+        for (int it = 0; it < A_ITERS; ++it) ra[it] = __builtin_amdgcn_raw_buffer_load_b128(rs, a_voff, base + it * 4096u, 0);
+    };
+    auto store_a = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int it = 0; it < A_ITERS; ++it) {
+            const int q = tid + it * 256;
+            *reinterpret_cast<u32x4*>(&As[buf * CH * LDK + (q / SEGS) * LDK + (q % SEGS) * 8]) = ra[it];
+        }
+    };
+    auto load_x = [&](int chunk) __attribute__((always_inline)) {
+        const unsigned coff = x_voff + (unsigned)(chunk * KC) * 2u;
+#pragma unroll
+        for (int it = 0; it < X_ITERS; ++it) {
+            if (it * RPP >= XR) break;                        // uniform
+            rx[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, coff + it * x_row_step, 0, 0);
+        }
+    };
+    auto store_x = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int it = 0; it < X_ITERS; ++it) {
+            if (it * RPP >= XR) break;                        // uniform
+            const int xr = xr0 + it * RPP;
+            if (xr >= W_XR_MAX) continue;
+            *reinterpret_cast<u32x4*>(&Xs[xr * LDK + seg * 8]) = rx[it];
+        }
+    };
+
+    // every request of the prologue is issued before the first result is waited for, in the order of use
+    load_a(rs_w7, 0);
+    load_x(0);
+    constexpr int PRM_ITERS = 4 * CH / 256;
+    float pv[PRM_ITERS];
+#pragma unroll
+    for (int it = 0; it < PRM_ITERS; ++it) {
+        const float* src = it == 0 ? p.b7 : it == 1 ? p.a2 : it == 2 ? p.ib2 : p.b1;      // 256 threads, 256 channels
+        pv[it] = src[tid];
+    }
+    store_a(0);
+    store_x();
+#pragma unroll
+    for (int it = 0; it < PRM_ITERS; ++it) prm[it * CH + tid] = pv[it];
+    __syncthreads();
+
+    // accumulators start at the bias: lane (j, h) holds rows (channels) mi*32 + 8g + 4h + {0..3} of column j
+    f32x16 acc[TM];
+    auto init_acc = [&](int which) __attribute__((always_inline)) {
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 b4 = *reinterpret_cast<const float4*>(&prm[which * CH + mi * 32 + 8 * g + 4 * h]);
+                acc[mi][4 * g + 0] = b4.x; acc[mi][4 * g + 1] = b4.y; acc[mi][4 * g + 2] = b4.z; acc[mi][4 * g + 3] = b4.w;
+            }
+    };
+    init_acc(0);
+
+    // ---- dilated conv: K loop over (chunk, tap) stages, fixed order; the last stage is peeled, its shadow hides the
+    // fetch of the first block of the 1x1 weights
+    int chunk = 0, tap = 0;
+    auto mma_stage = [&](int stage) __attribute__((always_inline)) {
+        const int off = p.tap0 + tap * p.tap_step - minoff;
+        const uint16_t* abase = &As[(stage & 1) * CH * LDK + j * LDK + h * 8];
+        const uint16_t* xbase = &Xs[(wn * 32 + j + off) * LDK + h * 8];
+#pragma unroll
+        for (int ks = 0; ks < KC / 16; ++ks) {
+            const bf16x8 bfr = *reinterpret_cast<const bf16x8*>(xbase + ks * 16);
+#pragma unroll
+            for (int mi = 0; mi < TM; ++mi) {
+                const bf16x8 af = *reinterpret_cast<const bf16x8*>(abase + mi * 32 * LDK + ks * 16);
+                acc[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[mi], 0, 0, 0);
+            }
+        }
+    };
+    for (int stage = 0; stage + 1 < nstages; ++stage) {
+        int ntap = tap + 1, nchunk = chunk;
+        if (ntap == p.ntaps) { ntap = 0; ++nchunk; }
+        const bool new_chunk = nchunk != chunk;
+        load_a(rs_w7, stage + 1);
+        if (new_chunk) load_x(nchunk);
+        mma_stage(stage);
+        if (new_chunk) {
+            __syncthreads();
+            store_x();
+        }
+        store_a((stage + 1) & 1);
+        __syncthreads();
+        tap = ntap; chunk = nchunk;
+    }
+    load_a(rs_w1, 0);
+    mma_stage(nstages - 1);
+
+    // ---- Snake on the accumulators; repack them as the B fragments of the 1x1 conv (k step kk = 2 mi + g/2)
+    u32x4 mid[CH / 16];
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int c = mi * 32 + 8 * g + 4 * h;
+            const float4 a4 = *reinterpret_cast<const float4*>(&prm[CH + c]);
+            const float4 i4 = *reinterpret_cast<const float4*>(&prm[2 * CH + c]);
+            u32x4& f = mid[2 * mi + g / 2];
+            f[2 * (g & 1) + 0] = pack_bf16x2(snake_fast(acc[mi][4 * g + 0], a4.x, i4.x), snake_fast(acc[mi][4 * g + 1], a4.y, i4.y));
+            f[2 * (g & 1) + 1] = pack_bf16x2(snake_fast(acc[mi][4 * g + 2], a4.z, i4.z), snake_fast(acc[mi][4 * g + 3], a4.w, i4.w));
+        }
+
+    // ---- 1x1 conv: K = 256 channels straight from registers, weights streamed through the two weight buffers
+    __syncthreads();                                   // all waves are done with the last stage's operands
+    store_a(0);
+    init_acc(3);
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < W_NCHUNKS; ++c) {
+        const bool more = c + 1 < W_NCHUNKS;
+        if (more) load_a(rs_w1, c + 1);
+        const uint16_t* abase = &As[(c & 1) * CH * LDK + j * LDK + h * 8];
+#pragma unroll
+        for (int mo = 0; mo < TM; ++mo) {
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(abase + mo * 32 * LDK);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(abase + mo * 32 * LDK + 16);
+            acc[mo] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, __builtin_bit_cast(bf16x8, mid[2 * c]), acc[mo], 0, 0, 0);
+            acc[mo] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, __builtin_bit_cast(bf16x8, mid[2 * c + 1]), acc[mo], 0, 0, 0);
+        }
+        if (more) {
+            store_a((c + 1) & 1);
+            __syncthreads();
+        }
+    }
+
+    // ---- residual add, half store in place, optional Snake + bf16 operand for the next layer.  Each wave transposes
+    // its 32 columns through a private LDS block, 64 channels at a time, so that a lane owns 4 consecutive channels
+    // and 16 consecutive lanes a 128-byte run of a row.  Rows past out_hi are outside the descriptors and dropped.
+    __syncthreads();                                   // all waves are done with the weight buffers
+    float* stage = reinterpret_cast<float*>(smem) + wn * (32 * W_LDT);
+    constexpr int LPR = W_GRP / 4;                     // lanes per row
+    constexpr int RPI = 64 / LPR;                      // rows per instruction
+    const int cl = lane % LPR, rl = lane / LPR;
+    u32x2 resv[CH / W_GRP][32 / RPI];                  // all residual values of this lane, requested at once
+#pragma unroll
+    for (int grp = 0; grp < CH / W_GRP; ++grp)
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it)
+            resv[grp][it] = __builtin_amdgcn_raw_buffer_load_b64(
+                rs_y, (unsigned)((n0 + wn * 32 + it * RPI + rl) * CH + grp * W_GRP + 4 * cl) * 2u, 0, 0);
+#pragma unroll
+    for (int grp = 0; grp < CH / W_GRP; ++grp) {
+        float4 a4 = make_float4(0, 0, 0, 0), i4 = a4;
+        if (EMIT) {
+            a4 = *reinterpret_cast<const float4*>(p.a3 + grp * W_GRP + 4 * cl);
+            i4 = *reinterpret_cast<const float4*>(p.ib3 + grp * W_GRP + 4 * cl);
+        }
+#pragma unroll
+        for (int m2 = 0; m2 < W_GRP / 32; ++m2)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x16& a = acc[grp * (W_GRP / 32) + m2];
+                *reinterpret_cast<float4*>(&stage[j * W_LDT + m2 * 32 + 8 * g + 4 * h]) =
+                    make_float4(a[4 * g + 0], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
+            }
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int row = it * RPI + rl;
+            const float4 t4 = *reinterpret_cast<const float4*>(&stage[row * W_LDT + 4 * cl]);
+            const unsigned e = (unsigned)((n0 + wn * 32 + row) * CH + grp * W_GRP + 4 * cl);
+            const f16x4 r = __builtin_bit_cast(f16x4, resv[grp][it]);
+            float v0 = t4.x + (float)r[0], v1 = t4.y + (float)r[1], v2 = t4.z + (float)r[2], v3 = t4.w + (float)r[3];
+            hres_store4(rs_y, e, v0, v1, v2, v3);
+            if (EMIT) {
+                // the next layer's operand is Snake of the STORED value
+                v0 = snake_fast(hres_round(v0), a4.x, i4.x); v1 = snake_fast(hres_round(v1), a4.y, i4.y);
+                v2 = snake_fast(hres_round(v2), a4.z, i4.z); v3 = snake_fast(hres_round(v3), a4.w, i4.w);
+                const u32x2 sh = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
+                __builtin_amdgcn_raw_buffer_store_b64(sh, rs_a, e * 2u, 0, 0);
+            }
+        }
+    }
+}
+
+}  // namespace
+
+// W1 [256][256] -> 8 blocks of 256 rows x 32 k-slots, the K axis in the accumulator row order of the narrow fused unit
+void pack_w1_wide(const float* w, uint16_t* dst)
+{
+    for (int c = 0; c < W_NCHUNKS; ++c)
+        for (int o = 0; o < W_CH; ++o)
+            for (int e = 0; e < W_KC; ++e) {
+                const int kp = c * W_KC + e, kk = kp / 16, h = (kp / 8) % 2, q = kp % 8;
+                const int ch = 32 * (kk / 2) + 8 * (2 * (kk % 2) + q / 4) + 4 * h + q % 4;
+                dst[((size_t)c * W_CH + o) * W_KC + e] = f32_to_bf16_rne(w[(size_t)o * W_CH + ch]);
+            }
+}
+
+hipError_t launch_res_unit_wide(const WideArgs& a, hipStream_t stream)
+{
+    WideParams p;
+    p.xa = a.xa; p.y = (hres_t*)a.y; p.ya = a.ya; p.w7 = a.w7; p.w1 = a.w1; p.b7 = a.b7; p.b1 = a.b1;
+    p.a2 = a.a2; p.ib2 = a.ib2; p.a3 = a.a3; p.ib3 = a.ib3;
+    p.slots = a.slots; p.r = a.r; p.ntaps = a.ntaps;
+    p.tap0 = -((a.ntaps - 1) / 2) * a.dil; p.tap_step = a.dil; p.margin = a.margin;
+    if (a.c != W_CH || a.ntaps < 1 || (a.ntaps - 1) * a.dil > W_MAXSPAN || a.margin < 0 || !a.xa || !a.y || a.xa == a.ya) return hipErrorInvalidValue;
+    if (a.ya && (!a.a3 || !a.ib3)) return hipErrorInvalidValue;
+    // one window's activation plane must fit a 32-bit byte offset (buffer descriptors)
+    if ((long long)a.max_len * a.r * a.c * 2 > 0xf0000000ll) return hipErrorInvalidValue;
+    const long long out_rows = std::min((long long)a.max_int * a.r + 2ll * a.margin, (long long)a.max_len * a.r);
+    dim3 grid((unsigned)((out_rows + W_NT - 1) / W_NT), (unsigned)a.n_slots);
+    if (a.ya) hipLaunchKernelGGL((res_unit_wide_kernel<true>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((res_unit_wide_kernel<false>), grid, dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace demon

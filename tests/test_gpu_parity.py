@@ -18,6 +18,7 @@ STACK_V1 = di.DecoderSpec(64, (4,), (64,), (1, 3, 9))
 STACK_V2 = di.DecoderSpec(16, (4, 2), (96, 32), (1, 3, 9))
 STACK_SPLIT = di.DecoderSpec(64, (2, 2), (512, 128), (1, 9))      # first block wide enough for split operands
 STACK_ODD = di.DecoderSpec(32, (6, 2), (64, 32), (2, 5), 5, 3, 3)  # other kernels, dilations, 3 output channels
+STACK_WIDE = di.DecoderSpec(64, (2, 2), (256, 64), (1, 3, 9))      # 256 channels: the fused unit that streams its 1x1 weights
 
 
 def test_config0_tiny_fp32_full_and_windowed():
@@ -64,7 +65,7 @@ def test_bf16_x1920_stack_full_and_windowed():
 
 
 @pytest.mark.parametrize("spec,T,window", [(STACK_V0, 300, 64), (STACK_V1, 150, 37), (STACK_V2, 40, 9),
-                                           (STACK_SPLIT, 70, 16), (STACK_ODD, 33, 8)])
+                                           (STACK_SPLIT, 70, 16), (STACK_ODD, 33, 8), (STACK_WIDE, 150, 37)])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_small_stacks_with_distinct_snake_parameters(spec, T, window, dtype):
     """alpha, beta ~ U[0.5, 2] per channel: a wrong channel index is far outside the tolerance."""
@@ -96,7 +97,7 @@ def oracle_layers(spec, w, z):
     return outs
 
 
-@pytest.mark.parametrize("dtype,spec", [("f32", di.TINY), ("bf16", STACK_V2), ("bf16", STACK_SPLIT),
+@pytest.mark.parametrize("dtype,spec", [("f32", di.TINY), ("bf16", STACK_V2), ("bf16", STACK_SPLIT), ("bf16", STACK_WIDE),
                                         ("bf16", di.DecoderSpec(64, (4, 2), (128, 64), (1, 3, 9)))])
 def test_every_layer_against_oracle_primitives(dtype, spec):
     """Reads each layer's activation back through the debug tap (full decode, one window per clip)."""
@@ -249,8 +250,8 @@ def test_workspace_and_argument_errors():
     vae.close()
 
 
-def test_unfused_kernels_for_64_and_128_channels_in_a_subprocess():
-    """DEMON_VAE_NO_FUSED=1 (read when the library loads) keeps the 64- and 128-channel residual units on the
+def test_unfused_kernels_for_64_128_and_256_channels_in_a_subprocess():
+    """DEMON_VAE_NO_FUSED=1 (read when the library loads) keeps the 64-, 128- and 256-channel residual units on the
     two-kernel path; same parity bar, and bit-identical windowed == full there too."""
     import os
     import subprocess
@@ -261,7 +262,8 @@ sys.path.insert(0, os.path.join(os.getcwd(), "tests")); sys.path.insert(0, os.ge
 import numpy as np
 import demon_inputs as di, oracle
 from gpu_util import make, to_device, assert_close
-for spec, T in ((di.DecoderSpec(64, (2,), (128,), (1, 3, 9)), 150), (di.DecoderSpec(64, (4,), (64,), (1, 3, 9)), 150)):
+for spec, T in ((di.DecoderSpec(64, (2,), (128,), (1, 3, 9)), 150), (di.DecoderSpec(64, (4,), (64,), (1, 3, 9)), 150),
+                (di.DecoderSpec(64, (2, 2), (256, 64), (1, 3, 9)), 150)):
     vae, w, z = make(spec, "bf16", T, snake="uniform", max_extended_frames=8 * T)
     zt = to_device(z, "bf16")
     full = vae.decode(zt).cpu().numpy()
