@@ -83,20 +83,22 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
     const unsigned x_voff = ((unsigned)((n0 + minoff + xr0) * CH) + seg * 8u) * 2u;      // may wrap "negative": out of range
     constexpr unsigned x_row_step = RPP * CH * 2u;
 
-    u32x4 ra[A_ITERS];
+    u32x4 ra[A_ITERS], rb[A_ITERS];     // rb: second set, only for the blocks of the 1x1 weights (requested two ahead)
     u32x4 rx[X_ITERS];
-    auto load_a = [&](__amdgpu_buffer_rsrc_t rs, int block) __attribute__((always_inline)) {
+    auto load_set = [&](u32x4 (&r)[A_ITERS], __amdgpu_buffer_rsrc_t rs, int block) __attribute__((always_inline)) {
         const unsigned base = (unsigned)block * (W_A_CH * 16u);
 #pragma unroll
-        for (int it = 0; it < A_ITERS; ++it) ra[it] = __builtin_amdgcn_raw_buffer_load_b128(rs, a_voff, base + it * 4096u, 0);
+        for (int it = 0; it < A_ITERS; ++it) r[it] = __builtin_amdgcn_raw_buffer_load_b128(rs, a_voff, base + it * 4096u, 0);
     };
-    auto store_a = [&](int buf) __attribute__((always_inline)) {
+    auto store_set = [&](const u32x4 (&r)[A_ITERS], int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it) {
             const int q = tid + it * 256;
-            *reinterpret_cast<u32x4*>(&As[buf * CH * LDK + (q / SEGS) * LDK + (q % SEGS) * 8]) = ra[it];
+            *reinterpret_cast<u32x4*>(&As[buf * CH * LDK + (q / SEGS) * LDK + (q % SEGS) * 8]) = r[it];
         }
     };
+    auto load_a = [&](__amdgpu_buffer_rsrc_t rs, int block) __attribute__((always_inline)) { load_set(ra, rs, block); };
+    auto store_a = [&](int buf) __attribute__((always_inline)) { store_set(ra, buf); };
     auto load_x = [&](int chunk) __attribute__((always_inline)) {
         const unsigned coff = x_voff + (unsigned)(chunk * KC) * 2u;
 #pragma unroll
@@ -193,15 +195,27 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
             f[2 * (g & 1) + 1] = pack_bf16x2(snake_fast(acc[mi][4 * g + 2], a4.z, i4.z), snake_fast(acc[mi][4 * g + 3], a4.w, i4.w));
         }
 
-    // ---- 1x1 conv: K = 256 channels straight from registers, weights streamed through the two weight buffers
+    // ---- 1x1 conv: K = 256 channels straight from registers, weights streamed through the two weight buffers; block
+    // c + 2 is requested before block c is used (odd blocks travel in ra, even ones in rb).  The residual values of
+    // the epilogue are requested in the second half of the loop, where the fragments already used have freed registers.
     __syncthreads();                                   // all waves are done with the last stage's operands
     store_a(0);
+    load_set(ra, rs_w1, 1);
+    load_set(rb, rs_w1, 2);
     init_acc(3);
     __syncthreads();
+    constexpr int LPR = W_GRP / 4;                     // epilogue: lanes per row
+    constexpr int RPI = 64 / LPR;                      // rows per instruction
+    const int cl = lane % LPR, rl = lane / LPR;
+    u32x2 resv[CH / W_GRP][32 / RPI];
+    auto load_res = [&](int grp) __attribute__((always_inline)) {
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it)
+            resv[grp][it] = __builtin_amdgcn_raw_buffer_load_b64(
+                rs_y, (unsigned)((n0 + wn * 32 + it * RPI + rl) * CH + grp * W_GRP + 4 * cl) * 2u, 0, 0);
+    };
 #pragma unroll
     for (int c = 0; c < W_NCHUNKS; ++c) {
-        const bool more = c + 1 < W_NCHUNKS;
-        if (more) load_a(rs_w1, c + 1);
         const uint16_t* abase = &As[(c & 1) * CH * LDK + j * LDK + h * 8];
 #pragma unroll
         for (int mo = 0; mo < TM; ++mo) {
@@ -210,27 +224,20 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
             acc[mo] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, __builtin_bit_cast(bf16x8, mid[2 * c]), acc[mo], 0, 0, 0);
             acc[mo] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, __builtin_bit_cast(bf16x8, mid[2 * c + 1]), acc[mo], 0, 0, 0);
         }
-        if (more) {
-            store_a((c + 1) & 1);
+        if (c + 1 < W_NCHUNKS) {
+            if ((c + 1) & 1) store_set(ra, (c + 1) & 1); else store_set(rb, (c + 1) & 1);
             __syncthreads();
+            if (c + 3 < W_NCHUNKS) { if ((c + 3) & 1) load_set(ra, rs_w1, c + 3); else load_set(rb, rs_w1, c + 3); }
         }
+        if (c >= W_NCHUNKS / 2) load_res(c - W_NCHUNKS / 2);        // chunks 4..7 request groups 0..3
     }
+    static_assert(W_NCHUNKS / 2 == CH / W_GRP, "one residual group per chunk of the second half");
 
     // ---- residual add, half store in place, optional Snake + bf16 operand for the next layer.  Each wave transposes
     // its 32 columns through a private LDS block, 64 channels at a time, so that a lane owns 4 consecutive channels
     // and 16 consecutive lanes a 128-byte run of a row.  Rows past out_hi are outside the descriptors and dropped.
     __syncthreads();                                   // all waves are done with the weight buffers
     float* stage = reinterpret_cast<float*>(smem) + wn * (32 * W_LDT);
-    constexpr int LPR = W_GRP / 4;                     // lanes per row
-    constexpr int RPI = 64 / LPR;                      // rows per instruction
-    const int cl = lane % LPR, rl = lane / LPR;
-    u32x2 resv[CH / W_GRP][32 / RPI];                  // all residual values of this lane, requested at once
-#pragma unroll
-    for (int grp = 0; grp < CH / W_GRP; ++grp)
-#pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it)
-            resv[grp][it] = __builtin_amdgcn_raw_buffer_load_b64(
-                rs_y, (unsigned)((n0 + wn * 32 + it * RPI + rl) * CH + grp * W_GRP + 4 * cl) * 2u, 0, 0);
 #pragma unroll
     for (int grp = 0; grp < CH / W_GRP; ++grp) {
         float4 a4 = make_float4(0, 0, 0, 0), i4 = a4;
