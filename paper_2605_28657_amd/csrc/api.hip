@@ -25,6 +25,8 @@ constexpr int kSplitWidth = 512;
 // DEMON_VAE_NO_FUSED=1 in the environment keeps every residual unit on the two-kernel path (A/B timing and
 // parity tests of the unfused kernels at 64 and 128 channels).
 const bool g_allow_fused = getenv("DEMON_VAE_NO_FUSED") == nullptr;
+// DEMON_VAE_ONE_STREAM=1 keeps the layer sequence of the bf16 path on the caller's stream only (A/B timing).
+const bool g_dual_stream = getenv("DEMON_VAE_ONE_STREAM") == nullptr;
 
 struct ConvLayer {
     int cin = 0, cout = 0, ntaps = 0, dil = 1, stride = 0, variant = -1;
@@ -46,6 +48,13 @@ struct Plan {
     int n_clips = 0, n_frames = 0, frame_begin = 0, frame_end = 0, window = 0, halo = 0;
     int n_slots = 0, max_len = 0, max_int = 0;
     long long total_frames = 0;
+    // The windows form one or two groups of consecutive table entries.  A group owns the workspace region that starts
+    // at frame0 x (largest per-frame activation size), and the rows of its windows count from the region's start: two
+    // groups can then be at different layers at the same time without touching each other's bytes (the bytes a window
+    // occupies depend on the layer's rate x width).
+    int n_groups = 1;
+    int g_first[2] = {0, 0}, g_count[2] = {0, 0};
+    long long g_frame0[2] = {0, 0}, g_frames[2] = {0, 0};
     Slot* d_slots = nullptr;
     unsigned long long last_use = 0;
 };
@@ -58,6 +67,7 @@ struct demon_vae {
     int max_frames = 0, max_clips = 0;
     long long cap_frames = 0;
     size_t act_elems = 0;              // elements one activation buffer holds
+    long long per_frame = 0;           // largest rate x width of a layer: elements of one latent frame at its widest
     int rf_left = 0, rf_right = 0;
     int device = 0;
 
@@ -74,6 +84,8 @@ struct demon_vae {
     void* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     float* head_out = nullptr;                     // planar window waveforms [out_channels, cap_frames*S]
     Slot* d_slot_arena = nullptr;
+    hipStream_t stream2 = nullptr;                 // second lane of the bf16 layer sequence (default priority, non-blocking)
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     Slot* h_slot_stage = nullptr;                  // pinned staging of the window tables, one region per cached plan
     hipEvent_t plan_copied[kPlanCache] = {};       // recorded after a table's upload: its staging region is free again
     Plan plans[kPlanCache];
@@ -174,13 +186,14 @@ void build_slots(int n_clips, int n_frames, int fb, int fe, int window, int halo
 // Looks the window grid up in the plan cache; on a miss builds the table, writes it to the pinned staging region of the
 // least recently used entry and uploads it with a copy on the decode stream, so the call stays asynchronous: kernels of
 // earlier calls that still read the replaced table precede the copy on that stream.
-demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, int window, int halo, hipStream_t stream, Plan** out)
+demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, int window, int halo, bool two_groups,
+                      hipStream_t stream, Plan** out)
 {
     ++v->use_counter;
     Plan* victim = &v->plans[0];
     for (Plan& p : v->plans) {
         if (p.valid && p.n_clips == n_clips && p.n_frames == n_frames && p.frame_begin == fb && p.frame_end == fe &&
-            p.window == window && p.halo == halo) {
+            p.window == window && p.halo == halo && (p.n_groups == 2) == (two_groups && p.n_slots >= 2)) {
             p.last_use = v->use_counter;
             *out = &p;
             return DEMON_OK;
@@ -201,6 +214,18 @@ demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, i
     if (e != hipSuccess) return hip_fail(e, "hipStreamIsCapturing");
     if (cap != hipStreamCaptureStatusNone)
         return fail(DEMON_ERR_INVALID_ARG, "this window grid is not cached: issue the call once outside the stream capture first");
+    // two groups of about equal size (in frames) for the bf16 path, whose layer sequence can run on two streams
+    int n_groups = 1, split = (int)slots.size();
+    if (two_groups && slots.size() >= 2) {
+        long long best = -1;
+        for (size_t i = 1; i < slots.size(); ++i) {
+            const long long a = slots[i].row0, d = a > total - a ? a - (total - a) : (total - a) - a;
+            if (best < 0 || d < best) { best = d; split = (int)i; }
+        }
+        n_groups = 2;
+    }
+    const long long frame0_b = n_groups == 2 ? slots[split].row0 : 0;
+    for (size_t i = (size_t)split; i < slots.size(); ++i) slots[i].row0 -= (int)frame0_b;
     const int idx = (int)(victim - v->plans);
     // the staging region may still be the source of this entry's previous upload
     e = hipEventSynchronize(v->plan_copied[idx]);
@@ -217,6 +242,9 @@ demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, i
     victim->window = window; victim->halo = halo;
     victim->n_slots = (int)slots.size(); victim->max_len = max_len; victim->max_int = max_int;
     victim->total_frames = total; victim->d_slots = d; victim->last_use = v->use_counter;
+    victim->n_groups = n_groups;
+    victim->g_first[0] = 0; victim->g_count[0] = split; victim->g_frame0[0] = 0; victim->g_frames[0] = n_groups == 2 ? frame0_b : total;
+    victim->g_first[1] = split; victim->g_count[1] = (int)slots.size() - split; victim->g_frame0[1] = frame0_b; victim->g_frames[1] = total - frame0_b;
     *out = victim;
     return DEMON_OK;
 }
@@ -227,16 +255,30 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
                         int window, int halo, float* d_out, int16_t* d_pcm, hipStream_t stream)
 {
     Plan* plan = nullptr;
-    demon_status rc = get_plan(v, n_clips, n_frames, fb, fe, window, halo, stream, &plan);
-    if (rc != DEMON_OK) return rc;
     const bool bf = v->dtype == DEMON_BF16;
+    // two window groups on two streams unless a mode wants one ordered launch sequence (per-launch timing, debug tap)
+    const bool dual = bf && v->stream2 && v->timing < 2 && !(v->tap_layer >= 0 && v->tap_dst);
+    demon_status rc = get_plan(v, n_clips, n_frames, fb, fe, window, halo, dual, stream, &plan);
+    if (rc != DEMON_OK) return rc;
     const Slot* slots = plan->d_slots;
     const int ns = plan->n_slots, ml = plan->max_len;
+
+    // the convolution launches address a group of windows (gs, gn) on a stream gst: all windows on the caller's
+    // stream, or two halves on two streams (see the bf16 path below)
+    const Slot* gs = slots;
+    int gn = ns, g = 0;
+    hipStream_t gst = stream;
+    bool marks_on = true;
+    auto select_group = [&](int which, hipStream_t on) {
+        g = which; gs = slots + plan->g_first[which]; gn = plan->g_count[which]; gst = on;
+    };
+    // element offset of the current group's region in every activation buffer
+    auto goff = [&]() -> size_t { return (size_t)plan->g_frame0[g] * (size_t)v->per_frame; };
 
     v->n_marks = 0;
     const int ring_base = (v->timed_calls % kTimingRing) * v->marks_per_call;
     auto mark = [&](int level) -> hipError_t {
-        if (v->timing < level || v->n_marks >= v->marks_per_call) return hipSuccess;
+        if (!marks_on || v->timing < level || v->n_marks >= v->marks_per_call) return hipSuccess;
         return hipEventRecord(v->events[ring_base + v->n_marks++], stream);
     };
     // level 1 marks: start, after gather, after the last convolution, after head, after stitch.
@@ -251,15 +293,17 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
     auto tap = [&](const void* x, int c) -> hipError_t {
         const int id = layer_id++;
         if (id != v->tap_layer || !v->tap_dst) return hipSuccess;
-        const size_t n = std::min<size_t>(v->tap_cap, (size_t)plan->total_frames * r * c);
-        return launch_to_f32(x, v->tap_dst, n, bf ? 2 : 0, stream);
+        // the groups' regions are apart in the workspace; the tap lays them end to end
+        const size_t first = (size_t)plan->g_frame0[g] * r * c, want = (size_t)plan->g_frames[g] * r * c;
+        if (first >= v->tap_cap) return hipSuccess;
+        return launch_to_f32(x, v->tap_dst + first, std::min(want, v->tap_cap - first), bf ? 2 : 0, gst);
     };
     auto conv_args = [&](const ConvLayer& L, const void* x, void* y, const void* res) {
         ConvArgs a;
         a.x = x; a.y = y; a.res = res; a.w = L.w; a.bias = L.bias;
         a.in_alpha = L.in_alpha; a.in_inv_beta = L.in_inv_beta;
         a.out_alpha = L.out_alpha; a.out_inv_beta = L.out_inv_beta;
-        a.slots = slots; a.n_slots = ns; a.max_len = ml; a.max_int = plan->max_int; a.margin = L.margin; a.r_in = r;
+        a.slots = gs; a.n_slots = gn; a.max_len = ml; a.max_int = plan->max_int; a.margin = L.margin; a.r_in = r;
         a.cin = L.cin; a.cout = L.cout; a.ntaps = L.ntaps; a.dil = L.dil; a.stride = L.stride;
         a.split_in = L.split_in; a.split_out = L.split_out;
         a.in_lo_off = a.out_lo_off = lo_off;
@@ -312,12 +356,17 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
             if (ui + 1 < (int)B.res.size()) return B.res[ui + 1].fused ? nullptr : &B.res[ui + 1].dilated;
             return bi + 1 < n_blocks ? &v->blocks[bi + 1].up : nullptr;
         };
-        {
+        for (int gi = 0; gi < plan->n_groups; ++gi) {
+            select_group(gi, stream);
             const ConvLayer& U0 = v->blocks[0].up;
-            HIP_TRY(launch_gather(d_latent, nullptr, v->st.c0, n_frames, true, slots, ns, ml, stream, acur,
+            HIP_TRY(launch_gather(d_latent, nullptr, v->st.c0, n_frames, true, gs, gn, ml, stream, (uint16_t*)v->buf[3] + goff(),
                                   U0.split_in ? lo_off : 0, U0.in_alpha, U0.in_inv_beta), "gather");
-            HIP_TRY(mark(1), "event");
         }
+        HIP_TRY(mark(1), "event");
+        auto layers = [&]() -> demon_status {
+        cur = (uint16_t*)v->buf[0] + goff(); other = (uint16_t*)v->buf[1] + goff();      // half: 2 bytes
+        acur = (uint16_t*)v->buf[3] + goff(); aoth = (uint16_t*)v->buf[4] + goff(); mid = (uint16_t*)v->buf[2] + goff();
+        r = 1; layer_id = 0;
         for (size_t bi = 0; bi < n_blocks; ++bi) {
             const Block& B = v->blocks[bi];
             const bool last_block = bi + 1 == n_blocks;
@@ -325,7 +374,7 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
                 ConvArgs a = conv_args(B.up, acur, other, nullptr);
                 const ConvLayer* C = consumer(bi, -1);
                 if (C) { a.ya = aoth; a.out_alpha = C->in_alpha; a.out_inv_beta = C->in_inv_beta; a.split_out = C->split_in; }
-                HIP_TRY(launch_conv_bf16(a, B.up.variant, stream), "transposed convolution");
+                HIP_TRY(launch_conv_bf16(a, B.up.variant, gst), "transposed convolution");
                 if (C) std::swap(acur, aoth);
             }
             HIP_TRY(mark(last_block && B.res.empty() ? 1 : 2), "event");
@@ -343,10 +392,10 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
                     f.b7 = U.dilated.bias; f.b1 = U.pointwise.bias;
                     f.a1 = U.dilated.in_alpha; f.ib1 = U.dilated.in_inv_beta;
                     f.a2 = U.dilated.out_alpha; f.ib2 = U.dilated.out_inv_beta;
-                    f.slots = slots; f.n_slots = ns; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
+                    f.slots = gs; f.n_slots = gn; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
                     f.r = r; f.c = U.dilated.cin; f.ntaps = U.dilated.ntaps; f.dil = U.dilated.dil;
                     if (C && C->split_in) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a split-operand layer");
-                    HIP_TRY(launch_res_unit_fused(f, stream), "fused residual unit");
+                    HIP_TRY(launch_res_unit_fused(f, gst), "fused residual unit");
                     std::swap(cur, other);
                     HIP_TRY(mark(2), "event");
                 } else if (U.wide) {
@@ -356,38 +405,74 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
                     f.w7 = (const uint16_t*)U.dilated.w; f.w1 = U.w1_fused;
                     f.b7 = U.dilated.bias; f.b1 = U.pointwise.bias;
                     f.a2 = U.dilated.out_alpha; f.ib2 = U.dilated.out_inv_beta;
-                    f.slots = slots; f.n_slots = ns; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
+                    f.slots = gs; f.n_slots = gn; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
                     f.r = r; f.c = U.dilated.cin; f.ntaps = U.dilated.ntaps; f.dil = U.dilated.dil;
                     if (C && C->split_in) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a split-operand layer");
-                    HIP_TRY(launch_res_unit_wide(f, stream), "fused residual unit (256 channels)");
+                    HIP_TRY(launch_res_unit_wide(f, gst), "fused residual unit (256 channels)");
                     if (C) std::swap(acur, aoth);
                     HIP_TRY(mark(2), "event");
                 } else {
                     ConvArgs d = conv_args(U.dilated, acur, nullptr, nullptr);
                     d.ya = mid;                                   // Snake between the convolutions: the layer's own out_alpha
-                    HIP_TRY(launch_conv_bf16(d, U.dilated.variant, stream), "dilated convolution");
+                    HIP_TRY(launch_conv_bf16(d, U.dilated.variant, gst), "dilated convolution");
                     HIP_TRY(mark(2), "event");
                     ConvArgs q = conv_args(U.pointwise, mid, cur, cur);   // in place on the residual stream
                     if (C) { q.ya = acur; q.out_alpha = C->in_alpha; q.out_inv_beta = C->in_inv_beta; q.split_out = C->split_in; }
-                    HIP_TRY(launch_conv_bf16(q, U.pointwise.variant, stream), "pointwise convolution");
+                    HIP_TRY(launch_conv_bf16(q, U.pointwise.variant, gst), "pointwise convolution");
                 }
                 HIP_TRY(mark(last_block && ui + 1 == B.res.size() ? 1 : 2), "event");
                 HIP_TRY(tap(cur, U.pointwise.cout), "debug tap");
             }
         }
+        return DEMON_OK;
+        };
+        // Windows are independent through the whole stack, so the layer sequence can run as two sequences over half of
+        // the windows each, on two streams: the ramp and tail of one sequence's launches (a last round of workgroups
+        // that fills a fraction of the CUs, prologues, epilogues) overlap with the other's.  Not with per-launch
+        // timing or the debug tap, which want one ordered sequence.
+        const bool two = dual && plan->n_groups == 2;
+        if (two) {
+            marks_on = false;
+            HIP_TRY(hipEventRecord(v->ev_fork, stream), "event");
+            HIP_TRY(hipStreamWaitEvent(v->stream2, v->ev_fork, 0), "hipStreamWaitEvent");
+        }
+        for (int gi = 0; gi < plan->n_groups; ++gi) {
+            select_group(gi, two && gi == 1 ? v->stream2 : stream);
+            const demon_status lrc = layers();
+            if (lrc != DEMON_OK) return lrc;
+        }
+        if (two) {
+            HIP_TRY(hipEventRecord(v->ev_join, v->stream2), "event");
+            HIP_TRY(hipStreamWaitEvent(stream, v->ev_join, 0), "hipStreamWaitEvent");
+            marks_on = true;
+            HIP_TRY(mark(1), "event");                       // after the last convolution
+        }
     }
+    // head and stitch, group by group on the caller's stream; the window waveforms are planar [channel][all rows]
     const long long total_rows = plan->total_frames * r;
-    if (v->head_wfrag) {
-        HIP_TRY(launch_head_mfma(cur, v->head_out, v->head_wfrag, v->head_bias, v->head_alpha, v->head_inv_beta, v->head_cin,
-                                 v->st.out_channels, v->st.head_kernel, r, total_rows, slots, ns, ml, plan->max_int, stream), "head");
-    } else
-    HIP_TRY(launch_head(cur, bf, v->head_out, v->head_w, v->head_bias, v->head_alpha, v->head_inv_beta, v->head_cin,
-                        v->st.out_channels, v->st.head_kernel, r, total_rows, bf, slots, ns, plan->max_int, stream), "head");
+    const size_t hbytes = bf ? 2 : sizeof(float);                           // half or fp32 residual stream
+    const char* final_base = (const char*)cur - goff() * hbytes;           // the buffer the last layer wrote, without the group offset
+    for (int gi = 0; gi < plan->n_groups; ++gi) {
+        select_group(gi, stream);
+        const void* x = final_base + goff() * hbytes;
+        float* y = v->head_out + plan->g_frame0[gi] * r;
+        if (v->head_wfrag) {
+            HIP_TRY(launch_head_mfma(x, y, v->head_wfrag, v->head_bias, v->head_alpha, v->head_inv_beta, v->head_cin,
+                                     v->st.out_channels, v->st.head_kernel, r, total_rows, gs, gn, ml, plan->max_int, stream), "head");
+        } else {
+            HIP_TRY(launch_head(x, bf, y, v->head_w, v->head_bias, v->head_alpha, v->head_inv_beta, v->head_cin,
+                                v->st.out_channels, v->st.head_kernel, r, total_rows, bf, gs, gn, plan->max_int, stream), "head");
+        }
+    }
     HIP_TRY(mark(1), "event");
-    if (d_pcm)
-        HIP_TRY(launch_stitch_pcm16(v->head_out, d_pcm, v->st.out_channels, r, n_frames, total_rows, slots, ns, plan->max_int, stream), "stitch");
-    else
-        HIP_TRY(launch_stitch(v->head_out, d_out, v->st.out_channels, r, n_frames, total_rows, slots, ns, plan->max_int, stream), "stitch");
+    for (int gi = 0; gi < plan->n_groups; ++gi) {
+        select_group(gi, stream);
+        const float* y = v->head_out + plan->g_frame0[gi] * r;
+        if (d_pcm)
+            HIP_TRY(launch_stitch_pcm16(y, d_pcm, v->st.out_channels, r, n_frames, total_rows, gs, gn, plan->max_int, stream), "stitch");
+        else
+            HIP_TRY(launch_stitch(y, d_out, v->st.out_channels, r, n_frames, total_rows, gs, gn, plan->max_int, stream), "stitch");
+    }
     HIP_TRY(mark(1), "event");
     if (v->timing > 0) ++v->timed_calls;
     return DEMON_OK;
@@ -546,6 +631,7 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
     // ---- device memory
     const size_t act_elems = (size_t)v->cap_frames * (size_t)per_frame;
     v->act_elems = act_elems;
+    v->per_frame = per_frame;
     const size_t head_bytes = (size_t)v->cap_frames * (size_t)rate * oc * sizeof(float);
     auto cleanup = [&]() {
         if (v->d_params) (void)hipFree(v->d_params);
@@ -554,6 +640,9 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
         if (v->d_slot_arena) (void)hipFree(v->d_slot_arena);
         if (v->h_slot_stage) (void)hipHostFree(v->h_slot_stage);
         for (hipEvent_t ev : v->plan_copied) if (ev) (void)hipEventDestroy(ev);
+        if (v->ev_fork) (void)hipEventDestroy(v->ev_fork);
+        if (v->ev_join) (void)hipEventDestroy(v->ev_join);
+        if (v->stream2) (void)hipStreamDestroy(v->stream2);
     };
     hipError_t e = hipMalloc(&v->d_params, ar.bytes.size());
     // fp32 path: 4 bytes per element; bf16 path: half residual stream (2 bytes), bf16 operand buffers with hi and lo planes (4)
@@ -562,6 +651,11 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
     if (e == hipSuccess) e = hipMalloc((void**)&v->d_slot_arena, sizeof(Slot) * kMaxSlots * kPlanCache);
     if (e == hipSuccess) e = hipHostMalloc((void**)&v->h_slot_stage, sizeof(Slot) * kMaxSlots * kPlanCache, hipHostMallocDefault);
     for (int i = 0; e == hipSuccess && i < kPlanCache; ++i) e = hipEventCreateWithFlags(&v->plan_copied[i], hipEventDisableTiming);
+    if (e == hipSuccess && bf && g_dual_stream) {
+        e = hipStreamCreateWithFlags(&v->stream2, hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&v->ev_fork, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&v->ev_join, hipEventDisableTiming);
+    }
     if (e == hipSuccess) e = hipMemcpy(v->d_params, ar.bytes.data(), ar.bytes.size(), hipMemcpyHostToDevice);
     if (e != hipSuccess) { cleanup(); return hip_fail(e, "allocating decoder memory"); }
 
@@ -592,6 +686,9 @@ void demon_vae_destroy(demon_vae* v)
     (void)hipHostFree(v->h_slot_stage);
     for (hipEvent_t e : v->plan_copied) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : v->events) (void)hipEventDestroy(e);
+    if (v->ev_fork) (void)hipEventDestroy(v->ev_fork);
+    if (v->ev_join) (void)hipEventDestroy(v->ev_join);
+    if (v->stream2) (void)hipStreamDestroy(v->stream2);
     delete v;
 }
 
