@@ -20,6 +20,10 @@
  * used by one host thread at a time, and its decode calls must go to one
  * stream (or be ordered by the caller): they share the handle's workspace.
  * Decode calls are asynchronous on the given HIP stream and allocate nothing.
+ * With two or more windows the bf16 path runs half of the windows on a second,
+ * internal stream that it forks from and joins back into the given stream
+ * within the call, so the call is ordered on the given stream like any other
+ * work and can be captured into a graph.
  * A window grid (clips, frames, range, window, halo) seen for the first time
  * has its table uploaded by a small copy on the same stream; the 8 most
  * recent grids are kept.  Under stream capture only cached grids are
