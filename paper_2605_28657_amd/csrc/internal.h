@@ -49,7 +49,7 @@ struct Slot {
 
 struct ConvArgs {
     const void* x;        // input activation [rows_in, cin] (fp32 path: fp32; bf16 path: activated bf16 operand)
-    void* y;              // output activation [rows_out, cout] (fp32); bf16 dilated conv: unused
+    void* y;              // output activation [rows_out, cout] (fp32 path: fp32; bf16 path: half); bf16 dilated conv: unused
     void* ya = nullptr;   // bf16 path: activated bf16 copy of the output for the next layer (Snake out_alpha/out_inv_beta)
     const void* res;      // residual (same layout as y) or nullptr; bf16 path: must equal y (in place)
     const void* w;        // packed weights (layout private to each kernel family)

@@ -7,8 +7,8 @@
 //                                     column m, row mu lands on output sample m s - p + phi, channel o,
 //                                     i.e. on the contiguous run ((m s - p) cout + mu) of the time-major output.
 //
-// Data flow.  The residual stream h is fp32 in HBM (rounding it to bf16 after every layer alone would
-// use up the error budget of the bf16 path).  MFMA operands are bf16 and are produced exactly once, by
+// Data flow.  The residual stream h is IEEE half in HBM (rounding it to bf16 after every layer alone would
+// use up the error budget of the bf16 path; all arithmetic on it is fp32).  MFMA operands are bf16 and are produced exactly once, by
 // the kernel that computes the value: every epilogue that writes h also writes a = bf16(snake(h)) with
 // the Snake parameters of the layer that will consume it, so the GEMM kernels stage their activation
 // operand with plain 16-byte copies (no transcendental work in the K loop, none repeated per row tile
@@ -37,8 +37,8 @@ namespace demon {
 constexpr int MAXSPAN = 64;    // largest (max tap offset - min tap offset) the LDS tile is sized for
 
 enum { MODE_ACT = 0,   // bias + Snake, bf16 out only                     (dilated conv of a residual unit)
-       MODE_RES = 1,   // bias + fp32 residual add, fp32 out in place     (1x1 conv of a residual unit)
-       MODE_UP  = 2 }; // bias, polyphase scatter, fp32 out               (ConvTranspose1d)
+       MODE_RES = 1,   // bias + residual add in fp32, half out in place  (1x1 conv of a residual unit)
+       MODE_UP  = 2 }; // bias, polyphase scatter, half out               (ConvTranspose1d)
 // MODE_RES and MODE_UP may in addition emit the activated bf16 copy for the next layer (EMIT > 0).
 
 struct MfmaParams {
