@@ -559,9 +559,12 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
                 P.variant = choose_variant_bf16(c, c, P.split_in);
                 if (D.variant < 0 || P.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for %d channels", c);
             }
-            U.fused = bf && (c == 64 || c == 128) && (st.res_kernel - 1) * st.dilations[j] <= 64 && !D.split_out && g_allow_fused;
+            // a fused unit writes single-plane operands: the last unit of a block stays on the two-kernel path when the
+            // next block's transposed conv wants its input as a hi + lo pair
+            const bool feeds_split = j + 1 == st.dilations.size() && l + 1 < st.strides.size() && st.widths[l + 1] >= kSplitWidth;
+            U.fused = bf && (c == 64 || c == 128) && (st.res_kernel - 1) * st.dilations[j] <= 64 && !D.split_out && g_allow_fused && !feeds_split;
             if (U.fused) D.variant = (c == 64) ? 1 : 0;      // weight blocks of C x 64
-            U.wide = bf && c == 256 && (st.res_kernel - 1) * st.dilations[j] <= 64 && !D.split_out && g_allow_fused;
+            U.wide = bf && c == 256 && (st.res_kernel - 1) * st.dilations[j] <= 64 && !D.split_out && g_allow_fused && !feeds_split;
             if (U.wide) D.variant = 3;                       // weight blocks of 256 x 32
             Pending pd{&D, 0, 0, {}, {}, true, true};
             pd.in = pack_snake(ar, w, w + c, c, bf);     w += 2 * c;

@@ -19,6 +19,7 @@ STACK_V2 = di.DecoderSpec(16, (4, 2), (96, 32), (1, 3, 9))
 STACK_SPLIT = di.DecoderSpec(64, (2, 2), (512, 128), (1, 9))      # first block wide enough for split operands
 STACK_ODD = di.DecoderSpec(32, (6, 2), (64, 32), (2, 5), 5, 3, 3)  # other kernels, dilations, 3 output channels
 STACK_WIDE = di.DecoderSpec(64, (2, 2), (256, 64), (1, 3, 9))      # 256 channels: the fused unit that streams its 1x1 weights
+STACK_GROW = di.DecoderSpec(32, (2, 2, 2), (128, 256, 512), (1, 3))  # fused units whose block feeds a split-operand transposed conv
 
 
 def test_config0_tiny_fp32_full_and_windowed():
@@ -65,7 +66,8 @@ def test_bf16_x1920_stack_full_and_windowed():
 
 
 @pytest.mark.parametrize("spec,T,window", [(STACK_V0, 300, 64), (STACK_V1, 150, 37), (STACK_V2, 40, 9),
-                                           (STACK_SPLIT, 70, 16), (STACK_ODD, 33, 8), (STACK_WIDE, 150, 37)])
+                                           (STACK_SPLIT, 70, 16), (STACK_ODD, 33, 8), (STACK_WIDE, 150, 37),
+                                           (STACK_GROW, 21, 6)])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_small_stacks_with_distinct_snake_parameters(spec, T, window, dtype):
     """alpha, beta ~ U[0.5, 2] per channel: a wrong channel index is far outside the tolerance."""
@@ -77,6 +79,36 @@ def test_small_stacks_with_distinct_snake_parameters(spec, T, window, dtype):
     assert_close(full, ref, dtype, "full")
     assert np.array_equal(win, full)
     vae.close()
+
+
+def test_random_small_stacks():
+    """Seeded random layer stacks (widths that select every tile variant and fusion, odd kernels, several dilations,
+    1-3 output channels, 1-2 clips, windows from one frame to longer than the clip): parity with the oracle and
+    windowed == full, in both precisions."""
+    rng = np.random.default_rng(2024)
+    done = 0
+    while done < 10:
+        nb = int(rng.integers(1, 4))
+        strides = tuple(int(rng.choice([2, 4, 6])) for _ in range(nb))
+        widths = tuple(int(rng.choice([32, 64, 96, 128, 160, 192, 256, 320, 512])) for _ in range(nb))
+        c0 = int(rng.choice([16, 32, 48, 64]))
+        dil = tuple(int(x) for x in rng.choice([1, 2, 3, 5, 9], size=int(rng.integers(1, 4))))
+        rk, hk, oc = int(rng.choice([3, 5, 7])), int(rng.choice([3, 7])), int(rng.choice([1, 2, 3]))
+        T, ncl = int(rng.integers(3, 30)), int(rng.integers(1, 3))
+        window = int(rng.integers(1, T + 3))
+        spec = di.DecoderSpec(c0, strides, widths, dil, rk, hk, oc)
+        if (rk - 1) * max(dil) > 64 or T * spec.total_stride * max(widths) > 8e6:
+            continue
+        H = max(oracle.receptive_field(spec))
+        for dtype in ("bf16", "f32"):
+            vae, w, z = make(spec, dtype, T, n_clips=ncl, snake="uniform",
+                             max_extended_frames=ncl * (T + 2 * H) * (T // window + 2))
+            zt = to_device(z, dtype)
+            full = vae.decode(zt).cpu().numpy()
+            assert_close(full, oracle.decode(spec, w, z), dtype, f"{spec} T={T} clips={ncl}")
+            assert np.array_equal(vae.decode_windowed(zt, window=window, halo=-1).cpu().numpy(), full), (spec, T, window)
+            vae.close()
+        done += 1
 
 
 def oracle_layers(spec, w, z):
