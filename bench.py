@@ -266,6 +266,16 @@ def main():
                 fn()
             torch.cuda.synchronize()
             small[name + "_ms"] = (time.perf_counter() - q0) * 1e3 / 200
+        # the playback-window decode behind the gate, flags read on the device: decoded (flag 0) and skipped (flag 1)
+        for name, flags in (("gated_decoded", torch.zeros(wl.n_clips, dtype=torch.int32, device="cuda:0")),
+                            ("gated_skipped", torch.ones(wl.n_clips, dtype=torch.int32, device="cuda:0"))):
+            fn = lambda: vae.decode_windowed_gated(z, flags, out, window=pw, halo=-1, frame_begin=pb, frame_end=pb + pw)
+            fn(); torch.cuda.synchronize()
+            q0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            small[name + "_ms"] = (time.perf_counter() - q0) * 1e3 / reps
         result["playback_window"].update(small)
 
     if args.power:

@@ -193,6 +193,18 @@ demon_status demon_vae_latent_similarity(const void* d_curr, const void* d_prev,
                                          demon_dtype dtype, float threshold, float* d_mse, int* d_unchanged, void* stream);
 
 /*
+ * Windowed decode behind the similarity gate (section 3.5: a clip whose latent is nearly unchanged
+ * skips the decode and keeps its previous audio).  d_skip: device, int [n_clips], read when the call
+ * executes on the stream, e.g. the d_unchanged output of demon_vae_latent_similarity issued to the same
+ * stream before: no host round trip.  Clips with a non-zero flag are not decoded and their part of
+ * d_out is left as it is; the other clips are decoded exactly as by demon_vae_decode_windowed.
+ * All other arguments, limits and errors as there; INVALID_ARG also for a NULL d_skip.
+ */
+demon_status demon_vae_decode_windowed_gated(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
+                                             int frame_begin, int frame_end, int window, int halo,
+                                             const int* d_skip, float* d_out, void* stream);
+
+/*
  * Equal-power crossfade of a chunk boundary of the playback stream (the paper crossfades each
  * decoded chunk into the output stream and names a 50 ms equal-power fade, 2400 samples at 48 kHz):
  *   d_out[c][i] = cos(t_i) * d_prev_tail[c][i] + sin(t_i) * d_next_head[c][i],  t_i = (pi/2)(i + 1/2)/n_samples

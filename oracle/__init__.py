@@ -5,4 +5,4 @@ package; it shares no code with the HIP library and never calls it.
 """
 from .oracle import (conv1d, convT1d, snake, decode, decode_windowed, window_grid,  # noqa: F401
                      receptive_field, backward_interval, forward_interval, omp_threads, pcm16,
-                     latent_mse, latent_unchanged, crossfade)
+                     latent_mse, latent_unchanged, crossfade, decode_gated)

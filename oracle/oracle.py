@@ -214,6 +214,20 @@ def latent_unchanged(curr, prev, threshold=1e-3):
     return latent_mse(curr, prev) < threshold
 
 
+def decode_gated(spec, weights, curr, prev, prev_audio, window, halo, threshold=1e-3):
+    """The decode behind the similarity filter (section 3.5), clip by clip: a clip whose latent moved by less than
+    the threshold keeps its previous audio, every other clip is decoded (windowed, section 3.6).
+    curr, prev: [n_clips, C, T]; prev_audio: [n_clips, out_channels, T * total_stride].  Returns (audio, skipped)."""
+    out = np.array(prev_audio, dtype=np.float64, copy=True)
+    skipped = []
+    for c in range(len(curr)):
+        skip = latent_unchanged(curr[c], prev[c], threshold)
+        skipped.append(bool(skip))
+        if not skip:
+            out[c] = decode_windowed(spec, weights, curr[c], window=window, halo=halo)
+    return out, skipped
+
+
 def crossfade(prev_tail, next_head):
     """Equal-power crossfade of two [channels, N] segments that overlap in time (the chunk boundary of the
     playback stream; the paper names a 50 ms equal-power crossfade without printing the gain curve).  Reading

@@ -66,6 +66,7 @@ def load_library() -> ctypes.CDLL:
     lib.demon_vae_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     lib.demon_vae_decode_windowed.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 6 + [ctypes.c_void_p, ctypes.c_void_p]
     lib.demon_vae_decode_windowed_pcm16.argtypes = lib.demon_vae_decode_windowed.argtypes
+    lib.demon_vae_decode_windowed_gated.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 6 + [ctypes.c_void_p] * 3
     lib.demon_vae_latent_similarity.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_int,
                                                 ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.demon_vae_crossfade.argtypes = [ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p, ctypes.c_longlong,
@@ -175,6 +176,12 @@ def demon_vae_decode_windowed_pcm16(handle: int, d_latent: int, n_clips: int, n_
                                     frame_end: int, window: int, halo: int, d_pcm: int, stream: int = 0):
     _check(load_library().demon_vae_decode_windowed_pcm16(handle, d_latent, n_clips, n_frames, frame_begin,
                                                           frame_end, window, halo, d_pcm, stream))
+
+
+def demon_vae_decode_windowed_gated(handle: int, d_latent: int, n_clips: int, n_frames: int, frame_begin: int,
+                                    frame_end: int, window: int, halo: int, d_skip: int, d_out: int, stream: int = 0):
+    _check(load_library().demon_vae_decode_windowed_gated(handle, d_latent, n_clips, n_frames, frame_begin, frame_end,
+                                                          window, halo, d_skip, d_out, stream))
 
 
 def demon_vae_latent_similarity(d_curr: int, d_prev: int, n_clips: int, elems_per_clip: int, dtype: int,
@@ -298,6 +305,18 @@ class DemonVAE:
             frame_end = t
         demon_vae_decode_windowed(self.handle, latent.data_ptr(), n_clips, t, frame_begin, frame_end, window, halo,
                                   out.data_ptr(), stream)
+        return out
+
+    def decode_windowed_gated(self, latent, skip, out, window: int, halo: int = -1, frame_begin: int = 0,
+                              frame_end: Optional[int] = None):
+        """skip: int32 device tensor [n_clips]; clips with a non-zero flag keep what `out` holds."""
+        import torch
+        latent, out, n_clips, t, stream = self._prep(latent, out)
+        assert skip.is_cuda and skip.dtype == torch.int32 and skip.is_contiguous() and skip.numel() == n_clips
+        if frame_end is None:
+            frame_end = t
+        demon_vae_decode_windowed_gated(self.handle, latent.data_ptr(), n_clips, t, frame_begin, frame_end, window, halo,
+                                        skip.data_ptr(), out.data_ptr(), stream)
         return out
 
     def decode_windowed_pcm16(self, latent, window: int, halo: int = -1, frame_begin: int = 0,

@@ -84,6 +84,7 @@ struct demon_vae {
     void* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     float* head_out = nullptr;                     // planar window waveforms [out_channels, cap_frames*S]
     Slot* d_slot_arena = nullptr;
+    Slot* d_slot_gated = nullptr;                  // per-call copy of a window table with the skipped clips emptied (gated decode)
     hipStream_t stream2 = nullptr;                 // second lane of the bf16 layer sequence (default priority, non-blocking)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     Slot* h_slot_stage = nullptr;                  // pinned staging of the window tables, one region per cached plan
@@ -252,7 +253,7 @@ demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, i
 #define HIP_TRY(expr, what) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_fail(e_, what); } while (0)
 
 demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_frames, int fb, int fe,
-                        int window, int halo, float* d_out, int16_t* d_pcm, hipStream_t stream)
+                        int window, int halo, const int* d_skip, float* d_out, int16_t* d_pcm, hipStream_t stream)
 {
     Plan* plan = nullptr;
     const bool bf = v->dtype == DEMON_BF16;
@@ -262,6 +263,11 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
     if (rc != DEMON_OK) return rc;
     const Slot* slots = plan->d_slots;
     const int ns = plan->n_slots, ml = plan->max_len;
+    if (d_skip) {
+        // gated decode: every kernel reads a copy of the table in which the skipped clips' windows are empty
+        HIP_TRY(launch_gate_slots(plan->d_slots, v->d_slot_gated, ns, d_skip, stream), "decode gate");
+        slots = v->d_slot_gated;
+    }
 
     // the convolution launches address a group of windows (gs, gn) on a stream gst: all windows on the caller's
     // stream, or two halves on two streams (see the bf16 path below)
@@ -641,6 +647,7 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
         for (void* b : v->buf) if (b) (void)hipFree(b);
         if (v->head_out) (void)hipFree(v->head_out);
         if (v->d_slot_arena) (void)hipFree(v->d_slot_arena);
+        if (v->d_slot_gated) (void)hipFree(v->d_slot_gated);
         if (v->h_slot_stage) (void)hipHostFree(v->h_slot_stage);
         for (hipEvent_t ev : v->plan_copied) if (ev) (void)hipEventDestroy(ev);
         if (v->ev_fork) (void)hipEventDestroy(v->ev_fork);
@@ -652,6 +659,7 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
     for (int i = 0; e == hipSuccess && i < (bf ? 5 : 3); ++i) e = hipMalloc(&v->buf[i], act_elems * ((bf && i < 2) ? 2 : 4));
     if (e == hipSuccess) e = hipMalloc((void**)&v->head_out, head_bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&v->d_slot_arena, sizeof(Slot) * kMaxSlots * kPlanCache);
+    if (e == hipSuccess) e = hipMalloc((void**)&v->d_slot_gated, sizeof(Slot) * kMaxSlots);
     if (e == hipSuccess) e = hipHostMalloc((void**)&v->h_slot_stage, sizeof(Slot) * kMaxSlots * kPlanCache, hipHostMallocDefault);
     for (int i = 0; e == hipSuccess && i < kPlanCache; ++i) e = hipEventCreateWithFlags(&v->plan_copied[i], hipEventDisableTiming);
     if (e == hipSuccess && bf && g_dual_stream) {
@@ -686,6 +694,7 @@ void demon_vae_destroy(demon_vae* v)
     for (void* b : v->buf) if (b) (void)hipFree(b);
     (void)hipFree(v->head_out);
     (void)hipFree(v->d_slot_arena);
+    (void)hipFree(v->d_slot_gated);
     (void)hipHostFree(v->h_slot_stage);
     for (hipEvent_t e : v->plan_copied) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : v->events) (void)hipEventDestroy(e);
@@ -703,7 +712,7 @@ demon_status demon_vae_receptive_field(const demon_vae* v, int* halo_left, int* 
 }
 
 static demon_status decode_checked(demon_vae* v, const void* d_latent, int n_clips, int n_frames,
-                                   int frame_begin, int frame_end, int window, int halo,
+                                   int frame_begin, int frame_end, int window, int halo, const int* d_skip,
                                    float* d_out, int16_t* d_pcm, void* stream)
 {
     clear_error();
@@ -718,7 +727,7 @@ static demon_status decode_checked(demon_vae* v, const void* d_latent, int n_cli
     if (n_frames > v->max_frames) return fail(DEMON_ERR_WORKSPACE, "n_frames %d exceeds max_frames %d", n_frames, v->max_frames);
     if (n_clips > v->max_clips) return fail(DEMON_ERR_WORKSPACE, "n_clips %d exceeds max_clips %d", n_clips, v->max_clips);
     if (halo == -1) halo = std::max(v->rf_left, v->rf_right);
-    return run_decode(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, d_out, d_pcm, (hipStream_t)stream);
+    return run_decode(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, d_skip, d_out, d_pcm, (hipStream_t)stream);
 }
 
 demon_status demon_vae_decode_windowed(demon_vae* v, const void* d_latent, int n_clips, int n_frames,
@@ -726,7 +735,15 @@ demon_status demon_vae_decode_windowed(demon_vae* v, const void* d_latent, int n
                                        float* d_out, void* stream)
 {
     if (!d_out) { clear_error(); return fail(DEMON_ERR_INVALID_ARG, "NULL argument"); }
-    return decode_checked(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, d_out, nullptr, stream);
+    return decode_checked(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, nullptr, d_out, nullptr, stream);
+}
+
+demon_status demon_vae_decode_windowed_gated(demon_vae* v, const void* d_latent, int n_clips, int n_frames,
+                                             int frame_begin, int frame_end, int window, int halo,
+                                             const int* d_skip, float* d_out, void* stream)
+{
+    if (!d_out || !d_skip) { clear_error(); return fail(DEMON_ERR_INVALID_ARG, "NULL argument"); }
+    return decode_checked(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, d_skip, d_out, nullptr, stream);
 }
 
 demon_status demon_vae_decode_windowed_pcm16(demon_vae* v, const void* d_latent, int n_clips, int n_frames,
@@ -734,7 +751,7 @@ demon_status demon_vae_decode_windowed_pcm16(demon_vae* v, const void* d_latent,
                                              int16_t* d_pcm, void* stream)
 {
     if (!d_pcm) { clear_error(); return fail(DEMON_ERR_INVALID_ARG, "NULL argument"); }
-    return decode_checked(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, nullptr, d_pcm, stream);
+    return decode_checked(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, nullptr, nullptr, d_pcm, stream);
 }
 
 demon_status demon_vae_decode(demon_vae* v, const void* d_latent, int n_clips, int n_frames, float* d_out, void* stream)

@@ -144,6 +144,8 @@ hipError_t launch_stitch(const float* y, float* out, int oc, int S, int n_frames
 // crop + stitch + 16-bit render: planar slot waveform -> d_pcm [n_clips, n_frames*S, oc] interleaved int16
 hipError_t launch_stitch_pcm16(const float* y, int16_t* pcm, int oc, int S, int n_frames, long long total_rows,
                                const Slot* slots, int n_slots, int max_int, hipStream_t stream);
+// decode gate: dst = src with the windows of clips whose skip flag is set emptied
+hipError_t launch_gate_slots(const Slot* src, Slot* dst, int n, const int* skip, hipStream_t stream);
 // latent similarity filter: per clip mse = mean((a-b)^2) over n elements and the gate mse < threshold
 hipError_t launch_latent_mse(const void* a, const void* b, int n_clips, long long n, bool bf16, float threshold,
                              float* mse, int* unchanged, hipStream_t stream);

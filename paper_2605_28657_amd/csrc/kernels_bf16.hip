@@ -144,6 +144,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     const int nrows_o = s.len * r_out;
     const int out_lo = max(0, s.crop * r_out - p.margin);
     const int out_hi = min(nrows_o, (s.crop + s.n_int) * r_out + p.margin);
+    if (out_hi <= out_lo) return;                           // an empty window (a gated clip)
     // GEMM columns: output rows (conv) or input positions m whose s outputs m s - p .. m s - p + s - 1 touch them
     const int col_lo = (MODE == MODE_UP) ? (out_lo + p.stride / 2) / p.stride : out_lo;
     const int ncols = (MODE == MODE_UP) ? (out_hi - 1 + p.stride / 2) / p.stride + 1 : out_hi;

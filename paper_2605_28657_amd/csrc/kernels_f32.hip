@@ -61,6 +61,7 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(ConvArgs a)
     const long long r_out = a.stride > 0 ? (long long)a.r_in * a.stride : a.r_in;
     const long long out_lo = max(0ll, s.crop * r_out - a.margin);
     const long long out_hi = min(s.len * r_out, (s.crop + s.n_int) * r_out + a.margin);
+    if (out_hi <= out_lo) return;                        // an empty window (a gated clip)
     const long long col_lo = a.stride > 0 ? (out_lo + a.stride / 2) / a.stride : out_lo;
     const long long col_hi = a.stride > 0 ? (out_hi - 1 + a.stride / 2) / a.stride + 1 : out_hi;
     const long long e = (long long)blockIdx.x * 256 + threadIdx.x;

@@ -482,6 +482,25 @@ hipError_t launch_stitch_pcm16(const float* y, int16_t* pcm, int oc, int S, int 
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------- decode gate
+// Copy of a window table in which the windows of skipped clips are empty (no rows, no interior): every kernel of the
+// decode derives its work from the table, so those clips cost (almost) nothing and their output is left untouched.
+__global__ __launch_bounds__(256) void gate_slots_kernel(const Slot* __restrict__ src, Slot* __restrict__ dst, int n,
+                                                         const int* __restrict__ skip)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    Slot s = src[i];
+    if (skip[s.clip] != 0) { s.len = 0; s.n_int = 0; s.crop = 0; }
+    dst[i] = s;
+}
+
+hipError_t launch_gate_slots(const Slot* src, Slot* dst, int n, const int* skip, hipStream_t stream)
+{
+    hipLaunchKernelGGL(gate_slots_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, src, dst, n, skip);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------- latent similarity filter
 // One workgroup per clip: squared differences accumulate in double in a fixed order (thread-strided partial sums, then a
 // tree over the workgroup), so the result does not depend on scheduling.  mse and the gate go out as fp32 / int.

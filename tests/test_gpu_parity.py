@@ -377,6 +377,96 @@ def test_filter_and_crossfade_argument_errors():
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("dtype,spec,T,window", [("f32", di.TINY, 40, 16), ("bf16", STACK_WIDE, 70, 16),
+                                                 ("bf16", STACK_V0, 33, 33)])
+def test_gated_decode_skips_unchanged_clips_without_a_host_round_trip(dtype, spec, T, window):
+    """Filter and decode issued back to back to one stream: the flags never visit the host.  A skipped clip keeps
+    what the output buffer held (its previous audio), a decoded clip equals the ungated decode bit for bit, and the
+    whole result meets the oracle's gated decode."""
+    bf = dtype == "bf16"
+    S, C, n = spec.total_stride, spec.latent_channels, 5
+    vae, w, prev = make(spec, dtype, T, n_clips=n, max_extended_frames=8 * n * T)
+    rng = np.random.default_rng(5)
+    drift = lambda z, a: (di.round_to_bf16(z + a * rng.standard_normal(z.shape).astype(np.float32)) if bf
+                          else z + np.float32(a) * rng.standard_normal(z.shape).astype(np.float32))
+    curr = prev.copy()
+    curr[0] = di.make_latent(C, T, 91, bf16=bf)            # new content
+    curr[2] = drift(prev[2], 0.01)                         # mse ~ 1e-4: kept
+    curr[3] = drift(prev[3], 0.1)                          # mse ~ 1e-2: decoded
+    zp, zc = to_device(prev, dtype), to_device(curr, dtype)
+    old = vae.decode_windowed(zp, window=window, halo=-1)
+    plain = vae.decode_windowed(zc, window=window, halo=-1)
+    buf = old.clone()
+    mse, flag = pa.latent_similarity(zc, zp, 1e-3)
+    vae.decode_windowed_gated(zc, flag, buf, window=window, halo=-1)
+    expect_skip = [False, True, True, False, True]
+    assert flag.cpu().numpy().astype(bool).tolist() == expect_skip
+    for c in range(n):
+        assert torch.equal(buf[c], old[c] if expect_skip[c] else plain[c]), c
+    hl = max(oracle.receptive_field(spec))
+    ref, skipped = oracle.decode_gated(spec, w, curr, prev, old.cpu().numpy(), window=window, halo=hl)
+    assert skipped == expect_skip
+    assert_close(buf.cpu().numpy(), ref, dtype, "gated decode")
+    # all clips skipped: nothing is written; none skipped: the ungated decode; a partial range composes with the gate
+    buf.fill_(5.0)
+    vae.decode_windowed_gated(zc, torch.ones(n, dtype=torch.int32, device="cuda:0"), buf, window=window, halo=-1)
+    assert float((buf - 5.0).abs().max()) == 0.0
+    vae.decode_windowed_gated(zc, torch.zeros(n, dtype=torch.int32, device="cuda:0"), buf, window=window, halo=-1)
+    assert torch.equal(buf, plain)
+    buf.fill_(5.0)
+    fb, fe = 2, min(T, 2 + window + 3)
+    vae.decode_windowed_gated(zc, flag, buf, window=window, halo=-1, frame_begin=fb, frame_end=fe)
+    for c in range(n):
+        if expect_skip[c]:
+            assert float((buf[c] - 5.0).abs().max()) == 0.0
+        else:
+            assert torch.equal(buf[c, :, fb * S:fe * S], plain[c, :, fb * S:fe * S])
+            assert bool(torch.all(buf[c, :, :fb * S] == 5.0)) and bool(torch.all(buf[c, :, fe * S:] == 5.0))
+    # the ungated entry points are not affected by an earlier gated call on the same window grid
+    assert torch.equal(vae.decode_windowed(zc, window=window, halo=-1), plain)
+    with pytest.raises(pa.DemonError):
+        pa.demon_vae_decode_windowed_gated(vae.handle, zc.data_ptr(), n, T, 0, T, window, -1, 0, buf.data_ptr(), 0)
+    vae.close()
+
+
+def test_filter_and_gated_decode_replay_from_one_hip_graph():
+    """Similarity filter and gated decode captured together: which clips are decoded is decided on the device at every
+    replay from the latents then in the buffers."""
+    spec = di.DecoderSpec(64, (4, 2), (128, 64), (1, 3, 9))
+    T, S, n = 40, spec.total_stride, 3
+    vae, w, prev = make(spec, "bf16", T, n_clips=n, max_extended_frames=4 * n * T)
+    zp = to_device(prev, "bf16")
+    zc = zp.clone()
+    args = dict(window=13, halo=-1)
+    audio = vae.decode_windowed(zp, **args).clone()             # the previous audio; also caches the plan
+    mse = torch.empty(n, dtype=torch.float32, device="cuda:0")
+    flag = torch.empty(n, dtype=torch.int32, device="cuda:0")
+    st = torch.cuda.current_stream().cuda_stream
+    elems = spec.latent_channels * T
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        cs = torch.cuda.current_stream().cuda_stream
+        pa.demon_vae_latent_similarity(zc.data_ptr(), zp.data_ptr(), n, elems, pa.DEMON_BF16, 1e-3,
+                                       mse.data_ptr(), flag.data_ptr(), cs)
+        vae.decode_windowed_gated(zc, flag, audio, **args)
+    for rep, changed in enumerate(([1], [], [0, 2], [0, 1, 2])):
+        before = audio.clone()
+        for c in changed:
+            zc[c].copy_(to_device(di.make_latent(spec.latent_channels, T, 200 + 10 * rep + c, bf16=True), "bf16"))
+        expect = vae.decode_windowed(zc, **args).clone()        # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert flag.cpu().numpy().tolist() == [0 if c in changed else 1 for c in range(n)], rep
+        for c in range(n):
+            assert torch.equal(audio[c], expect[c] if c in changed else before[c]), (rep, c)
+        zp.copy_(zc)                                            # the streaming loop: current becomes previous
+    ref = oracle.decode(spec, w, zc.float().cpu().numpy())
+    assert_close(audio.cpu().numpy(), ref, "bf16", "after the last replay")
+    vae.close()
+
+
 def test_playback_window_decode_replays_from_a_hip_graph():
     """The decode allocates nothing and records no memset once its window plan is cached, so a caller may capture it
     (the playback-window call of a streaming loop) and replay it; every replay is checked against the eager result,

@@ -233,3 +233,27 @@ def test_affine_when_snake_is_identity():
     rhs = 0.3 * (D(z1) - d0) - 0.7 * (D(z2) - d0)
     assert np.abs(lhs).max() > 1e-3
     np.testing.assert_allclose(lhs, rhs, rtol=0, atol=1e-12)
+
+
+def test_gated_decode_keeps_or_replaces_whole_clips():
+    """Section 3.5's gate composed with the decode: pinned by its two limits (nothing below the threshold: the plain
+    windowed decode; everything below: the previous audio, whatever it holds) and by a mixed case clip by clip."""
+    spec = di.TINY
+    w = di.make_weights(spec, 3)
+    T, S = 12, spec.total_stride
+    hl = max(oracle.receptive_field(spec))
+    prev = np.stack([di.make_latent(spec.latent_channels, T, 60 + c) for c in range(3)])
+    old = np.full((3, spec.out_channels, T * S), 7.0)
+    curr = prev + 1.0                                             # mse 1: every clip decoded
+    out, skipped = oracle.decode_gated(spec, w, curr, prev, old, window=5, halo=hl)
+    assert skipped == [False] * 3 and np.array_equal(out, oracle.decode_windowed(spec, w, curr, 5, hl))
+    out, skipped = oracle.decode_gated(spec, w, prev, prev, old, window=5, halo=hl)
+    assert skipped == [True] * 3 and np.array_equal(out, old)
+    curr = prev.copy()
+    curr[1] += 0.01                                               # mse 1e-4 < 1e-3: kept
+    curr[2] += 0.1                                                # mse 1e-2: decoded
+    out, skipped = oracle.decode_gated(spec, w, curr, prev, old, window=5, halo=hl)
+    assert skipped == [True, True, False]
+    assert np.array_equal(out[:2], old[:2]) and np.array_equal(out[2], oracle.decode(spec, w, curr[2]))
+    out, skipped = oracle.decode_gated(spec, w, curr, prev, old, window=5, halo=hl, threshold=1e-5)
+    assert skipped == [True, False, False]
