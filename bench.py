@@ -21,7 +21,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # measured with rocprofv3 --pmc (see profiles/full_60s_bf16_hbm_traffic.txt); not collectable inside this process
-TRAFFIC_BYTES_PER_STEP = {"full_60s_bf16": 17004812701}
+TRAFFIC_BYTES_PER_STEP = {"full_60s_bf16": 15663489478}
 
 
 def conv_flops_per_frame(spec):
@@ -174,7 +174,11 @@ def main():
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": args.workload, "latent": [wl.n_clips, spec.latent_channels, wl.n_frames],
                    "window": wl.window, "halo": halo, "n_windows": n_windows,
-                   "strides": list(spec.strides), "widths": list(spec.widths)},
+                   "strides": list(spec.strides), "widths": list(spec.widths),
+                   # the 16-bit formats of the bf16 path (bf16 and f16 MFMA have the same peak rate)
+                   "operands": ("weights: bf16 values; activation operands: bf16 below 512 channels, IEEE half from 512 "
+                                "channels on (f16 MFMA); fp32 accumulation; residual stream stored as IEEE half")
+                   if wl.bf16 else "fp32"},
         "roofline": {
             "kernel": "MFMA convolution kernels (conv_mfma_kernel + res_unit_fused_kernel: all convolution launches of a step, "
                       "%d layers)" % n_conv_launches,

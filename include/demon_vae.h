@@ -51,7 +51,9 @@ typedef enum {
 
 typedef enum {
     DEMON_F32 = 0, /* fp32 storage and arithmetic (reference-precision path)            */
-    DEMON_BF16 = 1 /* bf16 weights/activations, fp32 MFMA accumulation and epilogues    */
+    DEMON_BF16 = 1 /* bf16 weights and latent, 16-bit MFMA operands (bf16; IEEE half on levels
+                      of 512 channels and more), fp32 accumulation and epilogues, residual
+                      stream stored as IEEE half: values beyond the half range overflow      */
 } demon_dtype;
 
 /* Layer stack and workspace limits.  Arrays are read during the call only. */

@@ -17,11 +17,17 @@ namespace {
 constexpr int kMaxSlots = 4096;
 constexpr int kPlanCache = 8;
 constexpr int kTimingRing = 32;        // decode calls whose events are kept for demon_vae_get_timing
-// bf16 path: blocks at least this wide carry the inputs of their transposed conv and of their 1x1
-// convs as hi + lo bf16 pairs.  There the branch gain (weight std x sqrt(fan-in)) is about one, so
-// operand rounding passes into the output at full strength, while the extra MFMA work is small
-// (these GEMMs have short K).
+// bf16 path: blocks at least this wide carry their MFMA operands with more mantissa bits than bf16.  There the
+// branch gain (weight std x sqrt(fan-in)) is about one, so operand rounding passes into the output at full
+// strength.  Default: IEEE half operands on the f16 MFMA for every convolution of such a block (same rate as bf16;
+// the operands have the range of the half residual stream they are computed from).  DEMON_VAE_WIDE_OPERANDS=bf16x2
+// in the environment selects hi + lo bf16 pairs instead, for the inputs of the block's transposed conv and of its
+// 1x1 convs (two MFMAs per k-step there; the dilated convs then take plain bf16).
 constexpr int kSplitWidth = 512;
+const int g_wide_fmt = [] {
+    const char* e = getenv("DEMON_VAE_WIDE_OPERANDS");
+    return (e && strcmp(e, "bf16x2") == 0) ? (int)OP_BF16X2 : (int)OP_F16;
+}();
 // DEMON_VAE_NO_FUSED=1 in the environment keeps every residual unit on the two-kernel path (A/B timing and
 // parity tests of the unfused kernels at 64 and 128 channels).
 const bool g_allow_fused = getenv("DEMON_VAE_NO_FUSED") == nullptr;
@@ -30,7 +36,7 @@ const bool g_dual_stream = getenv("DEMON_VAE_ONE_STREAM") == nullptr;
 
 struct ConvLayer {
     int cin = 0, cout = 0, ntaps = 0, dil = 1, stride = 0, variant = -1;
-    bool split_in = false, split_out = false;
+    int in_fmt = OP_BF16;              // bf16 path: format of the activation operand (the weights are packed to match)
     int margin = 0;                    // output rows beyond the interior that later layers read
     const void* w = nullptr;
     const float* bias = nullptr;
@@ -144,7 +150,7 @@ size_t pack_conv(Arena& ar, const float* w, ConvLayer& L, bool bf16)
     if (bf16) {
         const size_t n = packed_bf16_count(L.cin, L.cout, L.ntaps, L.stride, L.variant);
         const size_t off = ar.reserve(n * 2);
-        pack_bf16(w, L.cin, L.cout, L.ntaps, L.stride, L.variant, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
+        pack_bf16(w, L.cin, L.cout, L.ntaps, L.stride, L.variant, L.in_fmt == OP_F16, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
         return off;
     }
     const size_t n = packed_f32_count(L.cin, L.cout, L.ntaps, L.stride);
@@ -311,7 +317,7 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
         a.out_alpha = L.out_alpha; a.out_inv_beta = L.out_inv_beta;
         a.slots = gs; a.n_slots = gn; a.max_len = ml; a.max_int = plan->max_int; a.margin = L.margin; a.r_in = r;
         a.cin = L.cin; a.cout = L.cout; a.ntaps = L.ntaps; a.dil = L.dil; a.stride = L.stride;
-        a.split_in = L.split_in; a.split_out = L.split_out;
+        a.in_fmt = L.in_fmt;
         a.in_lo_off = a.out_lo_off = lo_off;
         return a;
     };
@@ -366,7 +372,7 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
             select_group(gi, stream);
             const ConvLayer& U0 = v->blocks[0].up;
             HIP_TRY(launch_gather(d_latent, nullptr, v->st.c0, n_frames, true, gs, gn, ml, stream, (uint16_t*)v->buf[3] + goff(),
-                                  U0.split_in ? lo_off : 0, U0.in_alpha, U0.in_inv_beta), "gather");
+                                  U0.in_fmt, lo_off, U0.in_alpha, U0.in_inv_beta), "gather");
         }
         HIP_TRY(mark(1), "event");
         auto layers = [&]() -> demon_status {
@@ -379,7 +385,7 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
             {
                 ConvArgs a = conv_args(B.up, acur, other, nullptr);
                 const ConvLayer* C = consumer(bi, -1);
-                if (C) { a.ya = aoth; a.out_alpha = C->in_alpha; a.out_inv_beta = C->in_inv_beta; a.split_out = C->split_in; }
+                if (C) { a.ya = aoth; a.out_alpha = C->in_alpha; a.out_inv_beta = C->in_inv_beta; a.out_fmt = C->in_fmt; }
                 HIP_TRY(launch_conv_bf16(a, B.up.variant, gst), "transposed convolution");
                 if (C) std::swap(acur, aoth);
             }
@@ -400,7 +406,7 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
                     f.a2 = U.dilated.out_alpha; f.ib2 = U.dilated.out_inv_beta;
                     f.slots = gs; f.n_slots = gn; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
                     f.r = r; f.c = U.dilated.cin; f.ntaps = U.dilated.ntaps; f.dil = U.dilated.dil;
-                    if (C && C->split_in) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a split-operand layer");
+                    if (C && C->in_fmt != OP_BF16) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a layer with wide operands");
                     HIP_TRY(launch_res_unit_fused(f, gst), "fused residual unit");
                     std::swap(cur, other);
                     HIP_TRY(mark(2), "event");
@@ -413,17 +419,17 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
                     f.a2 = U.dilated.out_alpha; f.ib2 = U.dilated.out_inv_beta;
                     f.slots = gs; f.n_slots = gn; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
                     f.r = r; f.c = U.dilated.cin; f.ntaps = U.dilated.ntaps; f.dil = U.dilated.dil;
-                    if (C && C->split_in) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a split-operand layer");
+                    if (C && C->in_fmt != OP_BF16) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a layer with wide operands");
                     HIP_TRY(launch_res_unit_wide(f, gst), "fused residual unit (256 channels)");
                     if (C) std::swap(acur, aoth);
                     HIP_TRY(mark(2), "event");
                 } else {
                     ConvArgs d = conv_args(U.dilated, acur, nullptr, nullptr);
-                    d.ya = mid;                                   // Snake between the convolutions: the layer's own out_alpha
+                    d.ya = mid; d.out_fmt = U.pointwise.in_fmt;   // Snake between the convolutions: the layer's own out_alpha
                     HIP_TRY(launch_conv_bf16(d, U.dilated.variant, gst), "dilated convolution");
                     HIP_TRY(mark(2), "event");
                     ConvArgs q = conv_args(U.pointwise, mid, cur, cur);   // in place on the residual stream
-                    if (C) { q.ya = acur; q.out_alpha = C->in_alpha; q.out_inv_beta = C->in_inv_beta; q.split_out = C->split_in; }
+                    if (C) { q.ya = acur; q.out_alpha = C->in_alpha; q.out_inv_beta = C->in_inv_beta; q.out_fmt = C->in_fmt; }
                     HIP_TRY(launch_conv_bf16(q, U.pointwise.variant, gst), "pointwise convolution");
                 }
                 HIP_TRY(mark(last_block && ui + 1 == B.res.size() ? 1 : 2), "event");
@@ -542,9 +548,9 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
         {
             ConvLayer& L = B.up;
             L.cin = cin; L.cout = c; L.ntaps = 2; L.stride = s;
-            L.split_in = bf && c >= kSplitWidth;
+            L.in_fmt = (bf && c >= kSplitWidth) ? g_wide_fmt : (int)OP_BF16;
             if (bf) {
-                L.variant = choose_variant_bf16(cin, s * c, L.split_in);
+                L.variant = choose_variant_bf16(cin, s * c);
                 if (L.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for a %d -> %d stride-%d upsampling", cin, c, s);
             }
             Pending p{&L, 0, 0, {}, {}, true, false};
@@ -559,18 +565,20 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
             D.cin = c; D.cout = c; D.ntaps = st.res_kernel; D.dil = st.dilations[j];
             ConvLayer& P = U.pointwise;
             P.cin = c; P.cout = c; P.ntaps = 1; P.dil = 1;
-            D.split_out = P.split_in = bf && c >= kSplitWidth;
+            const bool wide_ops = bf && c >= kSplitWidth;
+            P.in_fmt = wide_ops ? g_wide_fmt : (int)OP_BF16;
+            D.in_fmt = (wide_ops && g_wide_fmt == OP_F16) ? (int)OP_F16 : (int)OP_BF16;
             if (bf) {
-                D.variant = choose_variant_bf16(c, c, D.split_in);
-                P.variant = choose_variant_bf16(c, c, P.split_in);
+                D.variant = choose_variant_bf16(c, c);
+                P.variant = choose_variant_bf16(c, c);
                 if (D.variant < 0 || P.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for %d channels", c);
             }
-            // a fused unit writes single-plane operands: the last unit of a block stays on the two-kernel path when the
-            // next block's transposed conv wants its input as a hi + lo pair
+            // a fused unit writes plain bf16 operands: the last unit of a block stays on the two-kernel path when the
+            // next block's transposed conv wants its input in a wider format
             const bool feeds_split = j + 1 == st.dilations.size() && l + 1 < st.strides.size() && st.widths[l + 1] >= kSplitWidth;
-            U.fused = bf && (c == 64 || c == 128) && (st.res_kernel - 1) * st.dilations[j] <= 64 && !D.split_out && g_allow_fused && !feeds_split;
+            U.fused = bf && (c == 64 || c == 128) && (st.res_kernel - 1) * st.dilations[j] <= 64 && !wide_ops && g_allow_fused && !feeds_split;
             if (U.fused) D.variant = (c == 64) ? 1 : 0;      // weight blocks of C x 64
-            U.wide = bf && c == 256 && (st.res_kernel - 1) * st.dilations[j] <= 64 && !D.split_out && g_allow_fused && !feeds_split;
+            U.wide = bf && c == 256 && (st.res_kernel - 1) * st.dilations[j] <= 64 && !wide_ops && g_allow_fused && !feeds_split;
             if (U.wide) D.variant = 3;                       // weight blocks of 256 x 32
             Pending pd{&D, 0, 0, {}, {}, true, true};
             pd.in = pack_snake(ar, w, w + c, c, bf);     w += 2 * c;

@@ -71,6 +71,14 @@ __device__ __forceinline__ float keep_f32(float v)
     return v;
 }
 
+// two fp32 values -> one dword of two halves (lo in bits 0..15), round to nearest even
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
+{
+    const f16x2 v = {(_Float16)lo, (_Float16)hi};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
 // four consecutive elements starting at element index e of the buffer
 __device__ __forceinline__ float4 hres_load4(__amdgpu_buffer_rsrc_t rs, unsigned e)
 {

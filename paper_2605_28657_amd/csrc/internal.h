@@ -47,6 +47,11 @@ struct Slot {
 // ---- kernels (launchers; all asynchronous on `stream`) -----------------------------------------
 // Activations live in "row-major time x channels" layout: element (row, c) at row*C + c.
 
+// MFMA operand formats of the bf16 path.  Weights are bf16 values in every format (exact in half as well).
+enum OperandFmt { OP_BF16 = 0,     // one bf16 plane
+                  OP_BF16X2 = 1,   // hi + lo bf16 planes, two MFMAs per k-step
+                  OP_F16 = 2 };    // one IEEE half plane, f16 MFMA
+
 struct ConvArgs {
     const void* x;        // input activation [rows_in, cin] (fp32 path: fp32; bf16 path: activated bf16 operand)
     void* y;              // output activation [rows_out, cout] (fp32 path: fp32; bf16 path: half); bf16 dilated conv: unused
@@ -67,9 +72,9 @@ struct ConvArgs {
     int ntaps;            // conv: kernel size; convT: 2
     int dil;              // conv: dilation; convT: unused
     int stride;           // 0 = Conv1d; s > 0 = ConvTranspose1d(kernel 2s, stride s, padding s/2)
-    // bf16 path only: operands carried as hi + lo bf16 pairs (see kernels_bf16.hip)
-    bool split_in = false, split_out = false;
-    long long in_lo_off = 0, out_lo_off = 0;
+    // bf16 path only: format of the MFMA operand read (x) and of the one emitted (ya), see kernels_bf16.hip
+    int in_fmt = OP_BF16, out_fmt = OP_BF16;
+    long long in_lo_off = 0, out_lo_off = 0;     // OP_BF16X2: element offset of the lo plane
 };
 
 hipError_t launch_conv_f32(const ConvArgs& a, hipStream_t stream);   // in_alpha must be nullptr (see launch_snake_f32)
@@ -81,10 +86,12 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream);
 // Packed weight sizes / packing (host).  w_src is the PyTorch layout: conv [cout, cin, k]; convT [cin, cout, 2s].
 size_t packed_f32_count(int cin, int cout, int ntaps, int stride);
 void pack_f32(const float* w_src, int cin, int cout, int ntaps, int stride, float* dst);
-int  choose_variant_bf16(int cin, int m, bool split_in);   // -1 if unsupported
+int  choose_variant_bf16(int cin, int m);   // -1 if unsupported
 size_t packed_bf16_count(int cin, int cout, int ntaps, int stride, int variant);
-void pack_bf16(const float* w_src, int cin, int cout, int ntaps, int stride, int variant, uint16_t* dst);
+// `as_half`: the 16-bit weights are IEEE half (for a layer whose activation operand is OP_F16), else bf16
+void pack_bf16(const float* w_src, int cin, int cout, int ntaps, int stride, int variant, bool as_half, uint16_t* dst);
 uint16_t f32_to_bf16_rne(float v);
+uint16_t f32_to_f16_rne(float v);
 
 // Fused residual unit (bf16 path, C = 64 or 128): y = x + W1 snake2(W7 (*) snake1(x) + b7) + b1, x != y.
 struct FusedArgs {
@@ -120,11 +127,11 @@ struct IoArgs {
     const Slot* slots; int n_slots; int max_len;
 };
 // latent [n_clips, c0, n_frames] (fp32 or bf16) -> level-0 activation [frames, c0] fp32; with `xa` (bf16 path) the
-// activated operand bf16(snake(x; alpha, inv_beta)) instead, as hi plane and (xa_lo_off != 0) lo plane
+// activated operand snake(x; alpha, inv_beta) instead, in operand format xa_fmt (lo plane at xa + xa_lo_off)
 hipError_t launch_gather(const void* latent, float* x0, int c0, int n_frames, bool bf16,
                          const Slot* slots, int n_slots, int max_len, hipStream_t stream,
-                         uint16_t* xa = nullptr, long long xa_lo_off = 0, const float* alpha = nullptr,
-                         const float* inv_beta = nullptr);
+                         uint16_t* xa = nullptr, int xa_fmt = OP_BF16, long long xa_lo_off = 0,
+                         const float* alpha = nullptr, const float* inv_beta = nullptr);
 // head: Snake -> Conv1d(k, cin -> oc) -> tanh; output planar fp32 [oc, total_rows]
 // `fast` selects the hardware-sine Snake (alpha given in revolutions) used by the bf16 path.
 // `x_half`: the input is the bf16 path's half-precision residual stream, else fp32.

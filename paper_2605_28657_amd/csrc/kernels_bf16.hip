@@ -15,9 +15,11 @@
 // or per halo).  Activations are time-major [rows, channels]: the 8 consecutive K values an MFMA lane
 // needs are 16 contiguous bytes, and a tap is a row offset into the same LDS tile.
 //
-// Split operands: where rounding an operand to bf16 costs too much accuracy (the wide, low-rate levels,
-// whose branch gain is about one), it is carried as hi + lo, hi = bf16(v), lo = bf16(v - hi), in two
-// planes, and every k-step issues two MFMAs against the same weight fragment.
+// Operand formats.  Where rounding an activation operand to bf16 costs too much accuracy (the wide, low-rate
+// levels, whose branch gain is about one) it is carried with more mantissa bits: as IEEE half (11 bits) on the
+// f16 MFMA, which runs at the bf16 rate -- the weights, bf16 values, are exact in half, and the operand has the
+// range of the half residual stream it is computed from -- or as hi + lo, hi = bf16(v), lo = bf16(v - hi), in
+// two planes with two bf16 MFMAs per k-step against the same weight fragment (16 bits, at twice the MFMA work).
 //
 // All global accesses go through buffer descriptors that cover exactly one window (rows of other
 // windows, rows before the window and rows past the part of the cone being computed are out of range:
@@ -39,14 +41,15 @@ constexpr int MAXSPAN = 64;    // largest (max tap offset - min tap offset) the 
 enum { MODE_ACT = 0,   // bias + Snake, bf16 out only                     (dilated conv of a residual unit)
        MODE_RES = 1,   // bias + residual add in fp32, half out in place  (1x1 conv of a residual unit)
        MODE_UP  = 2 }; // bias, polyphase scatter, half out               (ConvTranspose1d)
-// MODE_RES and MODE_UP may in addition emit the activated bf16 copy for the next layer (EMIT > 0).
+// MODE_RES and MODE_UP may in addition emit the activated operand of the next layer: EMIT = 0 none, else the
+// operand format + 1 (1 bf16, 2 bf16 hi + lo, 3 half).  IN is the operand format of the input.
 
 struct MfmaParams {
-    const uint16_t* xa;      // activated input, bf16 [rows][cin]; lo plane at xa + in_lo_off
+    const uint16_t* xa;      // activated input, 16-bit [rows][cin] in the kernel's IN format; lo plane at xa + in_lo_off
     const uint16_t* w;       // packed weight blocks
     const float* bias;
     hres_t* y;               // residual-stream output; MODE_RES: also the residual source (in place); unused in MODE_ACT
-    uint16_t* ya;            // bf16 activated output; lo plane at ya + out_lo_off
+    uint16_t* ya;            // activated output in the kernel's EMIT format; lo plane at ya + out_lo_off
     const float* out_alpha; const float* out_inv_beta;   // Snake applied before writing ya
     const Slot* slots;
     int r_in, cin, cout, ntaps, tap0, tap_step, stride, nchunks, margin;
@@ -60,9 +63,8 @@ struct Variant { int MT, NT, KC; };
 // variant 3 only names a weight layout: blocks of 256 x 32 for the fused 256-channel unit (kernels_bf16_wide.hip)
 static const Variant kVariants[4] = {{128, 128, 64}, {64, 256, 64}, {32, 128, 16}, {256, 128, 32}};
 
-int choose_variant_bf16(int cin, int m, bool split_in)
+int choose_variant_bf16(int cin, int m)
 {
-    (void)split_in;
     if (cin % 64 == 0 && m % 128 == 0) return 0;
     if (cin % 64 == 0 && m % 64 == 0) return 1;
     if (cin % 16 == 0 && m % 32 == 0) return 2;
@@ -78,6 +80,25 @@ uint16_t f32_to_bf16_rne(float v)
     return (uint16_t)(u >> 16);
 }
 
+uint16_t f32_to_f16_rne(float v)
+{
+    uint32_t u;
+    __builtin_memcpy(&u, &v, 4);
+    const uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    const uint32_t a = u & 0x7fffffffu;
+    if (a > 0x7f800000u) return (uint16_t)(sign | 0x7e00u);                       // NaN
+    if (a >= 0x477ff000u) return (uint16_t)(sign | 0x7c00u);                      // rounds to >= 2^16: infinity
+    if (a < 0x33000001u) return sign;                                             // <= 2^-25: rounds to zero
+    if (a < 0x38800000u) {                                                        // subnormal half: units of 2^-24
+        const int shift = 126 - (int)(a >> 23);                                   // 14 .. 24
+        const uint32_t m = (a & 0x7fffffu) | 0x800000u;
+        const uint32_t q = m >> shift, rem = m & ((1u << shift) - 1u), halfway = 1u << (shift - 1);
+        return (uint16_t)(sign | (q + ((rem > halfway || (rem == halfway && (q & 1u))) ? 1u : 0u)));
+    }
+    const uint32_t r = a + 0xfffu + ((a >> 13) & 1u);                             // normal: round the 13 dropped bits
+    return (uint16_t)(sign | ((r - 0x38000000u) >> 13));
+}
+
 // Packed layout: [M/MT][chunk][tap] blocks of MT x KC bf16 (row-major), the order the kernel walks them.
 size_t packed_bf16_count(int cin, int cout, int ntaps, int stride, int variant)
 {
@@ -86,7 +107,7 @@ size_t packed_bf16_count(int cin, int cout, int ntaps, int stride, int variant)
     return M * (size_t)ntaps * cin;
 }
 
-void pack_bf16(const float* w, int cin, int cout, int ntaps, int stride, int variant, uint16_t* dst)
+void pack_bf16(const float* w, int cin, int cout, int ntaps, int stride, int variant, bool as_half, uint16_t* dst)
 {
     const Variant v = kVariants[variant];
     const int M = stride > 0 ? stride * cout : cout;
@@ -105,11 +126,20 @@ void pack_bf16(const float* w, int cin, int cout, int ntaps, int stride, int var
                             const int phi = mu / cout, o = mu - phi * cout;
                             val = w[((size_t)ci * cout + o) * (2 * stride) + phi + t * stride];
                         }
-                        dst[pos++] = f32_to_bf16_rne(val);
+                        // bf16 values in either case: the half form of the rounded value (exact unless tiny)
+                        const uint16_t b = f32_to_bf16_rne(val);
+                        if (as_half) {
+                            const uint32_t bits = (uint32_t)b << 16;
+                            float bv;
+                            __builtin_memcpy(&bv, &bits, 4);
+                            dst[pos++] = f32_to_f16_rne(bv);
+                        } else {
+                            dst[pos++] = b;
+                        }
                     }
 }
 
-template <int MT, int NT, int KC, int WM, int WN, int MODE, bool SPLIT_IN, int EMIT>
+template <int MT, int NT, int KC, int WM, int WN, int MODE, int IN, int EMIT>
 __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
 {
     constexpr int NTH = 64 * WM * WN;           // threads per workgroup
@@ -124,6 +154,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     constexpr int A_CH = MT * SEGS;             // 16-byte chunks of an A block
     constexpr int A_ITERS = (A_CH + NTH - 1) / NTH;
     constexpr int X_ITERS = (XR_MAX + RPP - 1) / RPP;
+    constexpr bool SPLIT_IN = IN == OP_BF16X2;
     constexpr int NP = SPLIT_IN ? 2 : 1;        // operand planes (hi, lo)
     static_assert(WM * WN == 4 || WM * WN == 8, "four or eight waves per workgroup");
     static_assert(MODE != MODE_ACT || EMIT > 0, "the dilated conv only has the activated output");
@@ -284,21 +315,25 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
         const int xoff = (wn * WTN + j + off) * LDK + h * 8;
 #pragma unroll
         for (int ks = 0; ks < KC / 16; ++ks) {
-            bf16x8 af[TM], bfr[NP][TN];
+            u32x4 af[TM], bfr[NP][TN];
 #pragma unroll
-            for (int mi = 0; mi < TM; ++mi) af[mi] = *reinterpret_cast<const bf16x8*>(abase + mi * 32 * LDK + ks * 16);
+            for (int mi = 0; mi < TM; ++mi) af[mi] = *reinterpret_cast<const u32x4*>(abase + mi * 32 * LDK + ks * 16);
 #pragma unroll
             for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
                 for (int ni = 0; ni < TN; ++ni)
-                    bfr[pl][ni] = *reinterpret_cast<const bf16x8*>(&Xs[pl][xoff + ni * 32 * LDK + ks * 16]);
+                    bfr[pl][ni] = *reinterpret_cast<const u32x4*>(&Xs[pl][xoff + ni * 32 * LDK + ks * 16]);
 #pragma unroll
             for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-                    for (int pl = 0; pl < NP; ++pl)
-                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[pl][ni], acc[mi][ni], 0, 0, 0);
+                    for (int pl = 0; pl < NP; ++pl) {
+                        if (IN == OP_F16)
+                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, af[mi]), __builtin_bit_cast(f16x8, bfr[pl][ni]), acc[mi][ni], 0, 0, 0);
+                        else
+                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[mi]), __builtin_bit_cast(bf16x8, bfr[pl][ni]), acc[mi][ni], 0, 0, 0);
+                    }
         }
 
         if (more) {
@@ -321,7 +356,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     __syncthreads();                                   // all waves are done with the operand tiles
     float* stage = reinterpret_cast<float*>(smem) + wave * (32 * LDT);
     const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.ya + rowbase_o * p.cout, EMIT > 0 ? out_rows * p.cout * 2u : 0u);
-    const __amdgpu_buffer_rsrc_t rs_al = make_rsrc(p.ya + p.out_lo_off + rowbase_o * p.cout, EMIT > 1 ? out_rows * p.cout * 2u : 0u);
+    const __amdgpu_buffer_rsrc_t rs_al = make_rsrc(p.ya + p.out_lo_off + rowbase_o * p.cout, EMIT == 2 ? out_rows * p.cout * 2u : 0u);
     const int mu = m0 + wm * WTM + 4 * cl;             // this lane's 4 GEMM rows
     const int o = (MODE == MODE_UP) ? mu % p.cout : mu;   // ... are 4 consecutive output channels
     float4 oa = make_float4(0, 0, 0, 0), ob = oa;
@@ -360,9 +395,10 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
             if (EMIT > 0) {
                 v0 = snake_fast(v0, oa.x, ob.x); v1 = snake_fast(v1, oa.y, ob.y);
                 v2 = snake_fast(v2, oa.z, ob.z); v3 = snake_fast(v3, oa.w, ob.w);
-                const u32x2 sh = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
+                if (EMIT == 3) { v0 = keep_f32(v0); v1 = keep_f32(v1); v2 = keep_f32(v2); v3 = keep_f32(v3); }   // fp32 Snake, then one rounding
+                const u32x2 sh = {EMIT == 3 ? pack_f16x2(v0, v1) : pack_bf16x2(v0, v1), EMIT == 3 ? pack_f16x2(v2, v3) : pack_bf16x2(v2, v3)};
                 __builtin_amdgcn_raw_buffer_store_b64(sh, rs_a, e * 2u, 0, 0);
-                if (EMIT > 1) {
+                if (EMIT == 2) {
                     // lo plane: what the hi plane's rounding left over
                     const u32x2 sl = {pack_bf16x2(v0 - __uint_as_float(sh[0] << 16), v1 - __uint_as_float(sh[0] & 0xffff0000u)),
                                       pack_bf16x2(v2 - __uint_as_float(sh[1] << 16), v3 - __uint_as_float(sh[1] & 0xffff0000u))};
@@ -374,23 +410,27 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
 }
 
 template <int MT, int NT, int KC, int WM, int WN>
-static hipError_t launch_variant(const MfmaParams& p, int mode, bool split_in, int emit, dim3 grid, hipStream_t stream)
+static hipError_t launch_variant(const MfmaParams& p, int mode, int in_fmt, int emit, dim3 grid, hipStream_t stream)
 {
-#define DEMON_LAUNCH(MODE_, SI_, EM_) \
-    hipLaunchKernelGGL((conv_mfma_kernel<MT, NT, KC, WM, WN, MODE_, SI_, EM_>), grid, dim3(64 * WM * WN), 0, stream, p)
-#define DEMON_LAUNCH_SI(MODE_, EM_) do { \
-        if (!split_in) DEMON_LAUNCH(MODE_, false, EM_); \
-        else DEMON_LAUNCH(MODE_, true, EM_); } while (0)
+    // input format x emitted format: the pairs the layer sequence can ask for.  A layer with hi + lo input never emits
+    // half and one with half input never emits hi + lo (a stack uses one of the two for its wide levels).
+#define DEMON_LAUNCH(MODE_, IN_, EM_) \
+    hipLaunchKernelGGL((conv_mfma_kernel<MT, NT, KC, WM, WN, MODE_, IN_, EM_>), grid, dim3(64 * WM * WN), 0, stream, p)
+#define DEMON_CASE(MODE_, IN_, EM_) if (in_fmt == IN_ && emit == EM_) { DEMON_LAUNCH(MODE_, IN_, EM_); return hipGetLastError(); }
     if (mode == MODE_ACT) {
-        if (emit == 2) DEMON_LAUNCH_SI(MODE_ACT, 2); else DEMON_LAUNCH_SI(MODE_ACT, 1);
+        DEMON_CASE(MODE_ACT, OP_BF16, 1) DEMON_CASE(MODE_ACT, OP_BF16, 2) DEMON_CASE(MODE_ACT, OP_F16, 3)
     } else if (mode == MODE_RES) {
-        if (emit == 2) DEMON_LAUNCH_SI(MODE_RES, 2); else if (emit == 1) DEMON_LAUNCH_SI(MODE_RES, 1); else DEMON_LAUNCH_SI(MODE_RES, 0);
+        DEMON_CASE(MODE_RES, OP_BF16, 0) DEMON_CASE(MODE_RES, OP_BF16, 1) DEMON_CASE(MODE_RES, OP_BF16, 2) DEMON_CASE(MODE_RES, OP_BF16, 3)
+        DEMON_CASE(MODE_RES, OP_BF16X2, 0) DEMON_CASE(MODE_RES, OP_BF16X2, 1) DEMON_CASE(MODE_RES, OP_BF16X2, 2)
+        DEMON_CASE(MODE_RES, OP_F16, 0) DEMON_CASE(MODE_RES, OP_F16, 1) DEMON_CASE(MODE_RES, OP_F16, 3)
     } else {
-        if (emit == 2) DEMON_LAUNCH_SI(MODE_UP, 2); else if (emit == 1) DEMON_LAUNCH_SI(MODE_UP, 1); else DEMON_LAUNCH_SI(MODE_UP, 0);
+        DEMON_CASE(MODE_UP, OP_BF16, 0) DEMON_CASE(MODE_UP, OP_BF16, 1)
+        DEMON_CASE(MODE_UP, OP_BF16X2, 1) DEMON_CASE(MODE_UP, OP_BF16X2, 2)
+        DEMON_CASE(MODE_UP, OP_F16, 1) DEMON_CASE(MODE_UP, OP_F16, 3)
     }
-#undef DEMON_LAUNCH_SI
+#undef DEMON_CASE
 #undef DEMON_LAUNCH
-    return hipGetLastError();
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
@@ -412,7 +452,8 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     int mode;
     if (a.stride > 0) { p.tap0 = 0; p.tap_step = -1; mode = MODE_UP; }
     else { p.tap0 = -((a.ntaps - 1) / 2) * a.dil; p.tap_step = a.dil; mode = a.res ? MODE_RES : MODE_ACT; }
-    const int emit = a.ya ? (a.split_out ? 2 : 1) : 0;
+    if (a.in_fmt < OP_BF16 || a.in_fmt > OP_F16 || a.out_fmt < OP_BF16 || a.out_fmt > OP_F16) return hipErrorInvalidValue;
+    const int emit = a.ya ? a.out_fmt + 1 : 0;
     const int span = (a.ntaps - 1) * (a.stride > 0 ? 1 : a.dil);
     // shape checks: everything the kernel's indexing assumes
     if (span > (mode == MODE_ACT ? MAXSPAN : 8) || M % v.MT != 0 || a.cin % v.KC != 0 || a.cout % 4 != 0 || a.margin < 0) return hipErrorInvalidValue;
@@ -443,9 +484,9 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     p.xcd_group = w_fits_l2 ? 1 : 0;
     dim3 grid(m_fastest ? (unsigned)(ntiles8 * mtiles) : (unsigned)ntiles, (unsigned)a.n_slots, m_fastest ? 1u : (unsigned)mtiles);
     switch (variant) {
-        case 0: return launch_variant<128, 128, 64, 2, 2>(p, mode, a.split_in, emit, grid, stream);
-        case 1: return launch_variant<64, 256, 64, 1, 4>(p, mode, a.split_in, emit, grid, stream);
-        default: return launch_variant<32, 128, 16, 1, 4>(p, mode, a.split_in, emit, grid, stream);
+        case 0: return launch_variant<128, 128, 64, 2, 2>(p, mode, a.in_fmt, emit, grid, stream);
+        case 1: return launch_variant<64, 256, 64, 1, 4>(p, mode, a.in_fmt, emit, grid, stream);
+        default: return launch_variant<32, 128, 16, 1, 4>(p, mode, a.in_fmt, emit, grid, stream);
     }
 }
 

@@ -26,10 +26,10 @@ __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ laten
     x0[((size_t)s.row0 + r) * c0 + c] = load_act<T>(latent + ((size_t)s.clip * c0 + c) * n_frames + s.lo + r);
 }
 
-// bf16 path: the first layer's MFMA operand directly, bf16(snake(latent)) as hi (+ lo) plane
+// bf16 path: the first layer's MFMA operand directly, snake(latent) in operand format fmt
 template <typename T>
 __global__ __launch_bounds__(256) void gather_act_kernel(const T* __restrict__ latent, uint16_t* __restrict__ xa,
-                                                         long long lo_off, const float* __restrict__ alpha,
+                                                         int fmt, long long lo_off, const float* __restrict__ alpha,
                                                          const float* __restrict__ inv_beta, int c0, int n_frames,
                                                          const Slot* __restrict__ slots)
 {
@@ -39,21 +39,25 @@ __global__ __launch_bounds__(256) void gather_act_kernel(const T* __restrict__ l
     const int r = e / c0, c = e - r * c0;
     const float v = snake_fast(load_act<T>(latent + ((size_t)s.clip * c0 + c) * n_frames + s.lo + r), alpha[c], inv_beta[c]);
     const size_t idx = ((size_t)s.row0 + r) * c0 + c;
+    if (fmt == OP_F16) {
+        xa[idx] = __builtin_bit_cast(uint16_t, (_Float16)v);
+        return;
+    }
     const uint16_t hi = f32_to_bf16_bits(v);
     xa[idx] = hi;
-    if (lo_off) xa[lo_off + idx] = f32_to_bf16_bits(v - bf16_bits_to_f32(hi));
+    if (fmt == OP_BF16X2) xa[lo_off + idx] = f32_to_bf16_bits(v - bf16_bits_to_f32(hi));
 }
 
 hipError_t launch_gather(const void* latent, float* x0, int c0, int n_frames, bool bf16,
                          const Slot* slots, int n_slots, int max_len, hipStream_t stream,
-                         uint16_t* xa, long long xa_lo_off, const float* alpha, const float* inv_beta)
+                         uint16_t* xa, int xa_fmt, long long xa_lo_off, const float* alpha, const float* inv_beta)
 {
     dim3 grid((unsigned)(((size_t)max_len * c0 + 255) / 256), (unsigned)n_slots);
     if (xa) {
         if (bf16)
-            hipLaunchKernelGGL(gather_act_kernel<uint16_t>, grid, dim3(256), 0, stream, (const uint16_t*)latent, xa, xa_lo_off, alpha, inv_beta, c0, n_frames, slots);
+            hipLaunchKernelGGL(gather_act_kernel<uint16_t>, grid, dim3(256), 0, stream, (const uint16_t*)latent, xa, xa_fmt, xa_lo_off, alpha, inv_beta, c0, n_frames, slots);
         else
-            hipLaunchKernelGGL(gather_act_kernel<float>, grid, dim3(256), 0, stream, (const float*)latent, xa, xa_lo_off, alpha, inv_beta, c0, n_frames, slots);
+            hipLaunchKernelGGL(gather_act_kernel<float>, grid, dim3(256), 0, stream, (const float*)latent, xa, xa_fmt, xa_lo_off, alpha, inv_beta, c0, n_frames, slots);
     } else if (bf16)
         hipLaunchKernelGGL(gather_kernel<uint16_t>, grid, dim3(256), 0, stream, (const uint16_t*)latent, x0, c0, n_frames, slots);
     else

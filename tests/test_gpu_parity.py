@@ -16,10 +16,10 @@ pytestmark = pytest.mark.gpu
 STACK_V0 = di.DecoderSpec(64, (2,), (128,), (1, 3, 9))
 STACK_V1 = di.DecoderSpec(64, (4,), (64,), (1, 3, 9))
 STACK_V2 = di.DecoderSpec(16, (4, 2), (96, 32), (1, 3, 9))
-STACK_SPLIT = di.DecoderSpec(64, (2, 2), (512, 128), (1, 9))      # first block wide enough for split operands
+STACK_SPLIT = di.DecoderSpec(64, (2, 2), (512, 128), (1, 9))      # first block wide enough for the wide operand format
 STACK_ODD = di.DecoderSpec(32, (6, 2), (64, 32), (2, 5), 5, 3, 3)  # other kernels, dilations, 3 output channels
 STACK_WIDE = di.DecoderSpec(64, (2, 2), (256, 64), (1, 3, 9))      # 256 channels: the fused unit that streams its 1x1 weights
-STACK_GROW = di.DecoderSpec(32, (2, 2, 2), (128, 256, 512), (1, 3))  # fused units whose block feeds a split-operand transposed conv
+STACK_GROW = di.DecoderSpec(32, (2, 2, 2), (128, 256, 512), (1, 3))  # fused units whose block feeds a transposed conv with wide operands
 
 
 def test_config0_tiny_fp32_full_and_windowed():
@@ -307,6 +307,37 @@ print("ok")
 '''
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     env = dict(os.environ, DEMON_VAE_NO_FUSED="1")
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=240)
+    assert r.returncode == 0 and "ok" in r.stdout, r.stdout + r.stderr
+
+
+def test_wide_levels_with_hi_lo_bf16_operands_in_a_subprocess():
+    """DEMON_VAE_WIDE_OPERANDS=bf16x2 (read when the library loads) carries the operands of the levels that are at least
+    512 channels wide as hi + lo bf16 pairs instead of half; same parity bar, bit-identical windowed == full, also on
+    the first two levels of the x1920 stack and on a stack whose width grows into the wide range."""
+    import os
+    import subprocess
+    import sys
+    code = r'''
+import sys, os
+sys.path.insert(0, os.path.join(os.getcwd(), "tests")); sys.path.insert(0, os.getcwd())
+import numpy as np
+import demon_inputs as di, oracle
+from gpu_util import make, to_device, assert_close
+for spec, T, window in ((di.DecoderSpec(64, (2, 2), (512, 128), (1, 9)), 60, 23),
+                        (di.DecoderSpec(32, (2, 2, 2), (128, 256, 512), (1, 3)), 40, 17),
+                        (di.DecoderSpec(64, (10, 6, 2), (1024, 512, 64), (1, 3, 9)), 12, 5)):
+    vae, w, z = make(spec, "bf16", T, max_extended_frames=8 * T)
+    zt = to_device(z, "bf16")
+    full = vae.decode(zt).cpu().numpy()
+    win = vae.decode_windowed(zt, window=window, halo=-1).cpu().numpy()
+    assert_close(full, oracle.decode(spec, w, z), "bf16", "hi + lo operands")
+    assert np.array_equal(win, full)
+    vae.close()
+print("ok")
+'''
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, DEMON_VAE_WIDE_OPERANDS="bf16x2")
     r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=240)
     assert r.returncode == 0 and "ok" in r.stdout, r.stdout + r.stderr
 

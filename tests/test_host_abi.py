@@ -107,6 +107,34 @@ def test_null_handle_calls_return_invalid_arg():
     lib.demon_vae_destroy(None)      # ignored
 
 
+def test_host_conversion_to_half_rounds_to_nearest_even():
+    """The weights of the layers with half operands are converted on the host: the conversion against numpy's on random
+    bit patterns, on every tie between neighbouring halves and its two neighbours, around the subnormal range and at
+    the overflow threshold."""
+    lib = pa.load_library()
+    f = lib._ZN5demon14f32_to_f16_rneEf
+    f.argtypes = [ctypes.c_float]; f.restype = ctypes.c_uint16
+    rng = np.random.default_rng(0)
+    bits = [rng.integers(0, 2 ** 32, 50000, dtype=np.uint64).astype(np.uint32),
+            np.arange(0x32000000, 0x39000000, 0x2477, dtype=np.uint32),
+            np.array([0x477fefff, 0x477ff000, 0x477ff001, 0x7f800000, 0x33000000, 0x33000001, 0], dtype=np.uint32)]
+    h = np.arange(0, 0x7c00, 3, dtype=np.uint16)
+    lo, hi = h.view(np.float16).astype(np.float64), (h + 1).astype(np.uint16).view(np.float16).astype(np.float64)
+    mid = ((lo + hi) / 2)[np.isfinite(hi)].astype(np.float32)           # exact in fp32
+    bits += [mid.view(np.uint32), mid.view(np.uint32) - 1, mid.view(np.uint32) + 1]
+    bits = np.concatenate(bits)
+    bits = np.concatenate([bits, bits | np.uint32(0x80000000)])
+    vals = bits.view(np.float32)
+    with np.errstate(over="ignore"):
+        ref = vals.astype(np.float16).view(np.uint16)
+    for v, r in zip(vals.tolist(), ref.tolist()):
+        g = f(v)
+        if v != v:
+            assert (g & 0x7c00) == 0x7c00 and (g & 0x3ff) != 0
+        else:
+            assert g == r, (v, hex(g), hex(r))
+
+
 def test_half_conversions_keep_the_fp32_rounding():
     """The device code converts fp32 results to half in unrolled loops.  If the compiler fuses the producing
     arithmetic with the conversion (one mixed-precision instruction that rounds once) it does so in some iterations
