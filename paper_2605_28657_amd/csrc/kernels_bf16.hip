@@ -56,6 +56,7 @@ struct MfmaParams {
     int mtiles_x;            // > 0: blockIdx.x enumerates (column tile, row tile), see the kernel; 0: blockIdx.z = row tile
     int xcd_group;           // with mtiles_x: 1 = all row tiles of a column tile on one XCD, 0 = row tiles dealt over the XCDs
     unsigned w_bytes;
+    int pack_ratio;          // the weights are packed in blocks of pack_ratio * MT rows (1, or 2 for the small-grid tile)
     long long in_lo_off, out_lo_off;     // element offsets of the lo planes
 };
 
@@ -216,7 +217,10 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     const __amdgpu_buffer_rsrc_t rs_xl = make_rsrc(p.xa + p.in_lo_off + rowbase * p.cin, SPLIT_IN ? (unsigned)nrows * p.cin * 2u : 0u);
 
     const int nstages = p.nchunks * p.ntaps;
-    const unsigned w_tile0 = (unsigned)mtile * nstages * (A_CH * 16u);
+    // a row tile's blocks are nstages apart in the packed order; with blocks packed for a tile of pack_ratio * MT rows
+    // this tile is a contiguous slice of every such block
+    const unsigned w_blk = (unsigned)p.pack_ratio * (A_CH * 16u);
+    const unsigned w_tile0 = (unsigned)(mtile / p.pack_ratio) * nstages * w_blk + (unsigned)(mtile % p.pack_ratio) * (A_CH * 16u);
     const unsigned a_voff = tid * 16u;
     const unsigned x_voff = ((unsigned)((n0 + minoff + xr0) * p.cin) + seg * 8u) * 2u;    // may wrap "negative": out of range
     const unsigned x_row_step = (unsigned)(RPP * p.cin) * 2u;
@@ -225,7 +229,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     u32x4 rx[X_ITERS][NP];
 
     auto load_a = [&](int stage) __attribute__((always_inline)) {
-        const unsigned base = w_tile0 + (unsigned)stage * (A_CH * 16u);
+        const unsigned base = w_tile0 + (unsigned)stage * w_blk;
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it)
             if (A_CH % NTH == 0 || tid + it * NTH < A_CH)
@@ -433,10 +437,18 @@ static hipError_t launch_variant(const MfmaParams& p, int mode, int in_fmt, int 
     return hipErrorInvalidValue;
 }
 
+// Launches of the 128 x 128 tile that would leave most CUs without a workgroup (one playback window at the wide, low-rate
+// levels) use a 64 x 64 tile on the same packed weights instead: four times the workgroups, and the same K order, so
+// the results are bit-identical to the large tile's.  DEMON_VAE_SMALL_TILE_WGS overrides the threshold (0: never).
+static const long long g_small_tile_wgs = [] {
+    const char* e = getenv("DEMON_VAE_SMALL_TILE_WGS");
+    return e ? atoll(e) : 256ll;
+}();
+
 hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
 {
     if (variant < 0 || variant > 2) return hipErrorInvalidValue;
-    const Variant v = kVariants[variant];
+    Variant v = kVariants[variant];
     const int M = a.stride > 0 ? a.stride * a.cout : a.cout;
     MfmaParams p;
     p.xa = (const uint16_t*)a.x; p.w = (const uint16_t*)a.w; p.bias = a.bias;
@@ -475,6 +487,12 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     //  * W larger, more than 8 row tiles: ids run over row tiles first, so XCD x owns the row tiles = x mod 8 (an
     //    eighth of W, resident) and reads all activations: about 8 X + W.
     //  * else column tiles fastest (blockIdx.x): workgroups in flight share one row tile of the weights: mtiles X + W.
+    p.pack_ratio = 1;
+    bool small_tile = false;
+    if (variant == 0 && ((ncols + v.NT - 1) / v.NT) * (M / v.MT) * a.n_slots <= g_small_tile_wgs) {
+        small_tile = true;
+        v.MT = 64; v.NT = 64; p.pack_ratio = 2;
+    }
     const long long ntiles = (ncols + v.NT - 1) / v.NT;
     const int mtiles = M / v.MT;
     const long long ntiles8 = (ntiles + 7) / 8 * 8;           // whole groups of 8 column tiles; the surplus exits at once
@@ -484,7 +502,8 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     p.xcd_group = w_fits_l2 ? 1 : 0;
     dim3 grid(m_fastest ? (unsigned)(ntiles8 * mtiles) : (unsigned)ntiles, (unsigned)a.n_slots, m_fastest ? 1u : (unsigned)mtiles);
     switch (variant) {
-        case 0: return launch_variant<128, 128, 64, 2, 2>(p, mode, a.in_fmt, emit, grid, stream);
+        case 0: return small_tile ? launch_variant<64, 64, 64, 2, 2>(p, mode, a.in_fmt, emit, grid, stream)
+                                  : launch_variant<128, 128, 64, 2, 2>(p, mode, a.in_fmt, emit, grid, stream);
         case 1: return launch_variant<64, 256, 64, 1, 4>(p, mode, a.in_fmt, emit, grid, stream);
         default: return launch_variant<32, 128, 16, 1, 4>(p, mode, a.in_fmt, emit, grid, stream);
     }

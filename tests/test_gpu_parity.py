@@ -311,6 +311,43 @@ print("ok")
     assert r.returncode == 0 and "ok" in r.stdout, r.stdout + r.stderr
 
 
+def test_small_grid_tile_is_bit_identical_to_the_large_tile(tmp_path):
+    """Launches with few workgroups use a 64 x 64 tile on the same packed weights (here: every generic launch, the
+    inputs are short); DEMON_VAE_SMALL_TILE_WGS=0 in a subprocess keeps the 128 x 128 tile.  Same K order, so the two
+    decodes must agree bit for bit."""
+    import os
+    import subprocess
+    import sys
+    code = r'''
+import sys, os
+sys.path.insert(0, os.path.join(os.getcwd(), "tests")); sys.path.insert(0, os.getcwd())
+import numpy as np
+import demon_inputs as di
+from gpu_util import make, to_device
+outs = []
+for spec, T in ((di.DecoderSpec(64, (2, 2), (512, 128), (1, 9)), 60), (di.DecoderSpec(64, (10, 6, 2), (1024, 512, 64), (1, 3, 9)), 12),
+                (di.DecoderSpec(64, (2, 2), (256, 128), (1, 3)), 50)):
+    vae, w, z = make(spec, "bf16", T, n_clips=2, max_extended_frames=8 * T)
+    outs.append(vae.decode_windowed(to_device(z, "bf16"), window=T // 2 + 1, halo=-1).cpu().numpy().ravel())
+    vae.close()
+np.save(sys.argv[1], np.concatenate(outs))
+print("ok")
+'''
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    got = {}
+    for name, wgs in (("small", None), ("large", "0")):
+        env = dict(os.environ)
+        env.pop("DEMON_VAE_SMALL_TILE_WGS", None)
+        if wgs is not None:
+            env["DEMON_VAE_SMALL_TILE_WGS"] = wgs
+        path = str(tmp_path / (name + ".npy"))
+        r = subprocess.run([sys.executable, "-c", code, path], cwd=root, env=env, capture_output=True, text=True, timeout=240)
+        assert r.returncode == 0 and "ok" in r.stdout, r.stdout + r.stderr
+        got[name] = np.load(path)
+    assert got["small"].shape == got["large"].shape and np.array_equal(got["small"], got["large"])
+    assert np.all(np.isfinite(got["small"])) and np.abs(got["small"]).max() > 1e-3
+
+
 def test_wide_levels_with_hi_lo_bf16_operands_in_a_subprocess():
     """DEMON_VAE_WIDE_OPERANDS=bf16x2 (read when the library loads) carries the operands of the levels that are at least
     512 channels wide as hi + lo bf16 pairs instead of half; same parity bar, bit-identical windowed == full, also on
