@@ -218,6 +218,30 @@ def main():
     vae.set_timing(0)
 
     if not args.no_extras:
+        # every step on its own (synchronised before and after): median and fastest of 20
+        singles = []
+        for _ in range(20):
+            torch.cuda.synchronize()
+            s0 = time.perf_counter()
+            step()
+            torch.cuda.synchronize()
+            singles.append((time.perf_counter() - s0) * 1e3)
+        result["ms_per_step_single"] = {"median": float(np.median(singles)), "min": float(np.min(singles))}
+        # what a plain device copy reaches on this GPU (256 MiB read + 256 MiB written per call): the HBM fractions above
+        # can be read against it as well as against the published 8 TB/s
+        src = torch.empty(1 << 26, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        s0 = time.perf_counter()
+        for _ in range(20):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        copy_gbs = 20 * 2 * src.numel() * 4 / (time.perf_counter() - s0) / 1e9
+        result["hbm_kernels"]["device_copy_256MiB"] = {"GB/s": copy_gbs, "frac": copy_gbs / PEAK_HBM_GBS}
+        del src, dst
+
         # Latency of re-decoding one playback window (3 s = 75 latent frames in the middle of the clip, analytic halo)
         # into the resident waveform buffer: the call the paper's 8x windowed-decode figure is about (section 3.6).
         pw = min(75, wl.n_frames)

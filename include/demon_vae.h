@@ -28,6 +28,16 @@
  * has its table uploaded by a small copy on the same stream; the 8 most
  * recent grids are kept.  Under stream capture only cached grids are
  * accepted (issue the call once before capturing).
+ *
+ * Environment switches, read once when the library is loaded (A/B timing and
+ * tests of the alternative kernels; results stay within the same tolerances):
+ *   DEMON_VAE_WIDE_OPERANDS=bf16x2  bf16 path: levels of 512 channels and more carry the inputs of
+ *                                   their transposed and 1x1 convolutions as hi + lo bf16 pairs
+ *                                   instead of IEEE half operands
+ *   DEMON_VAE_NO_FUSED=1            every residual unit as two kernels (no fused units)
+ *   DEMON_VAE_ONE_STREAM=1          no internal second stream
+ *   DEMON_VAE_SMALL_TILE_WGS=n      launches of at most n 128 x 128 tiles use 64 x 64 tiles
+ *                                   (default 256, 0 = never; bit-identical results)
  */
 #ifndef DEMON_VAE_H
 #define DEMON_VAE_H
