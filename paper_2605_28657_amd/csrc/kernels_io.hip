@@ -295,7 +295,11 @@ __global__ __launch_bounds__(256) void head_mfma_kernel(const _Float16* __restri
     float al[8], ib[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) { al[e] = alpha[seg * 8 + e]; ib[e] = inv_beta[seg * 8 + e]; }
-    const float b = (j < oc) ? bias[j] : 0.f;
+    float b[16];                                           // accumulator register 4g + q of lane (j, h) is output channel 8g + 4h + q
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) b[4 * g + q] = (8 * g + 4 * h + q < oc) ? bias[8 * g + 4 * h + q] : 0.f;
 
     // The raw rows of a sub-tile are fetched one sub-tile ahead, so that their latency hides behind the MFMAs and the
     // tanh epilogue of the previous one.  Rows outside the window are out of range of the descriptor and read as
@@ -331,7 +335,7 @@ __global__ __launch_bounds__(256) void head_mfma_kernel(const _Float16* __restri
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-            for (int q = 0; q < 16; ++q) acc[mi][q] = b;
+            for (int q = 0; q < 16; ++q) acc[mi][q] = b[q];
         for (int t = 0; t < k; ++t) {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
@@ -339,27 +343,25 @@ __global__ __launch_bounds__(256) void head_mfma_kernel(const _Float16* __restri
 #pragma unroll
                 for (int mi = 0; mi < 2; ++mi) {
                     const f16x8v av = *reinterpret_cast<const f16x8v*>(&Xs[(wave * 64 + mi * 32 + j + t) * LDX + ks * 16 + h * 8]);
-                    acc[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bw, acc[mi], 0, 0, 0);
+                    // weights as the row operand: the accumulator tile is [output channel][time]
+                    acc[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bw, av, acc[mi], 0, 0, 0);
                 }
             }
         }
-        // lane (j, h) holds output channel j, rows 8g + 4h + {0..3}
-        if (j < oc) {
+        // lane (j, h) holds time column j and output channels 8g + 4h + {0..3}: with a few output channels the tanh work
+        // sits in the first registers of half of the lanes, and a channel's 32 samples are one contiguous store
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
+        for (int mi = 0; mi < 2; ++mi) {
+            const int n = n0 + wave * 64 + mi * 32 + j;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + wave * 64 + mi * 32 + 8 * g + 4 * h;
-                    float* dst = y + (size_t)j * total_rows + rowbase + n;
-                    if (n + 4 <= hi && (r % 4) == 0) {
-                        *reinterpret_cast<float4*>(dst) = make_float4(tanhf(acc[mi][4 * g + 0]), tanhf(acc[mi][4 * g + 1]),
-                                                                      tanhf(acc[mi][4 * g + 2]), tanhf(acc[mi][4 * g + 3]));
-                    } else {
+            for (int g = 0; g < 4; ++g) {
+                if (8 * g >= oc) break;                        // uniform
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            if (n + q < hi) dst[q] = tanhf(acc[mi][4 * g + q]);
-                    }
+                for (int q = 0; q < 4; ++q) {
+                    const int c = 8 * g + 4 * h + q;
+                    if (c < oc && n < hi) y[(size_t)c * total_rows + rowbase + n] = tanhf(acc[mi][4 * g + q]);
                 }
+            }
         }
     }
 }
