@@ -10,9 +10,15 @@
 // j, eight K values per lane.  So after bias + Snake the accumulators ARE the B fragments of the 1x1
 // conv, provided its K axis is permuted to the accumulator's row order: k-slot (kk, h, e) <-> channel
 // 32 (kk/2) + 8 (2 (kk%2) + e/4) + 4 h + e%4.  The 1x1 weights are packed in that order at create.
+// In the 1x1 conv the roles are swapped: these fragments are the row operand (rows = time) and the weights the
+// column operand, so its accumulator tile is [time][output channel] and a lane holds one output-channel slot j of
+// each of the C/32 channel tiles.  The weight rows are packed so that slot j of tile mo is channel j C/32 + mo:
+// a lane then owns C/32 consecutive channels of a time row, 32 lanes a whole row, and residual loads and
+// stores are contiguous without a transposition through LDS.
 // The result is written to a second buffer (neighbouring tiles still read this tile's input rows).
 // With EMIT the kernel also writes bf16(snake_next(h_out)), the operand of the next (unfused) layer.
 #include <algorithm>
+#include <type_traits>
 
 #include "device_common.h"
 
@@ -42,8 +48,11 @@ static inline int fused_k_to_channel(int kp)
 
 void pack_w1_fused(const float* w /*[C][C]*/, int C, uint16_t* dst)
 {
-    for (int o = 0; o < C; ++o)
-        for (int kp = 0; kp < C; ++kp) dst[(size_t)o * C + kp] = f32_to_bf16_rne(w[(size_t)o * C + fused_k_to_channel(kp)]);
+    const int tm = C / 32;
+    for (int slot = 0; slot < C; ++slot) {
+        const int o = (slot % 32) * tm + slot / 32;        // row slot (mo, j) holds output channel j * tm + mo
+        for (int kp = 0; kp < C; ++kp) dst[(size_t)slot * C + kp] = f32_to_bf16_rne(w[(size_t)o * C + fused_k_to_channel(kp)]);
+    }
 }
 
 template <int CH, int TN, bool EMIT>
@@ -65,11 +74,8 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     static_assert(A_CH % 256 == 0 && W1_CH % 256 == 0, "staging loops assume whole passes");
     static_assert(CH * LD1 <= 2 * CH * LDK, "the 1x1 weights reuse the dilated-conv weight buffers");
 
-    // epilogue staging: every wave transposes its output through a private 32-column block
-    constexpr int LDT = CH + 4;
-    constexpr int STG_BYTES = 4 * 32 * LDT * 4;
     constexpr int AS_BYTES = 2 * CH * LDK * 2, XS_BYTES = XR_MAX * LDK * 2;
-    constexpr int SMEM_BYTES = (AS_BYTES + XS_BYTES > STG_BYTES) ? AS_BYTES + XS_BYTES : STG_BYTES;
+    constexpr int SMEM_BYTES = AS_BYTES + XS_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
     // per-channel vectors used after the K loop (bias of both convolutions, Snake between them): read from global
     // memory where they are used, each load would be waited for in turn
@@ -173,18 +179,22 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     // ahead of time: loaded where they are used, each would be waited for in turn, a chain of memory latencies per
     // tile.  With 64 channels there are registers to hold them through the K loop; with 128 they are fetched after
     // it, in the shadow of the Snake and the 1x1 convolution.
-    constexpr int LPR = CH / 4;                        // lanes per row
-    constexpr int RPI = 64 / LPR;                      // rows per instruction
     constexpr bool EARLY_RES = CH == 64;
-    const int cl = lane % LPR, rl = lane / LPR;
-    u32x2 resv[TN][32 / RPI];
+    // epilogue geometry: lane (j, h) owns channels j TM .. j TM + TM - 1 of time rows 8g + 4h + q of every 32-column tile
+    using res_t = std::conditional_t<TM == 2, uint32_t, u32x2>;         // TM halves
+    res_t resv[TN][16];
+    auto res_offset = [&](int ni, int gq) -> unsigned {
+        const int col = n0 + wn * WTN + ni * 32 + 8 * (gq >> 2) + 4 * h + (gq & 3);
+        return (unsigned)(col * CH + j * TM) * 2u;
+    };
     auto load_res = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-            for (int it = 0; it < 32 / RPI; ++it)
-                resv[ni][it] = __builtin_amdgcn_raw_buffer_load_b64(
-                    rs_x, (unsigned)((n0 + wn * WTN + ni * 32 + it * RPI + rl) * CH + 4 * cl) * 2u, 0, 0);
+            for (int gq = 0; gq < 16; ++gq) {
+                if constexpr (TM == 2) resv[ni][gq] = __builtin_amdgcn_raw_buffer_load_b32(rs_x, res_offset(ni, gq), 0, 0);
+                else resv[ni][gq] = __builtin_amdgcn_raw_buffer_load_b64(rs_x, res_offset(ni, gq), 0, 0);
+            }
     };
     if (EARLY_RES) load_res();
     store_a(0);
@@ -279,18 +289,16 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     }
     __syncthreads();
 
-    // ---- 1x1 conv: K = C channels straight from registers; accumulators start at its bias
+    // ---- 1x1 conv: K = C channels straight from registers, as the row operand (rows = time); the accumulator tile
+    // [time][channel slot] starts at the bias of the lane's channel j TM + mo
 #pragma unroll
-    for (int mi = 0; mi < TM; ++mi)
+    for (int mo = 0; mo < TM; ++mo) {
+        const float b1v = prm[3 * CH + j * TM + mo];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const float4 b4 = *reinterpret_cast<const float4*>(&prm[3 * CH + mi * 32 + 8 * g + 4 * h]);
+        for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-            for (int ni = 0; ni < TN; ++ni) {
-                acc[mi][ni][4 * g + 0] = b4.x; acc[mi][ni][4 * g + 1] = b4.y;
-                acc[mi][ni][4 * g + 2] = b4.z; acc[mi][ni][4 * g + 3] = b4.w;
-            }
-        }
+            for (int q = 0; q < 16; ++q) acc[mo][ni][q] = b1v;
+    }
 #pragma unroll
     for (int kk = 0; kk < CH / 16; ++kk) {
         bf16x8 af[TM];
@@ -300,47 +308,47 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
         for (int mo = 0; mo < TM; ++mo)
 #pragma unroll
             for (int ni = 0; ni < TN; ++ni)
-                acc[mo][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mo], __builtin_bit_cast(bf16x8, mid[kk][ni]), acc[mo][ni], 0, 0, 0);
+                acc[mo][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, mid[kk][ni]), af[mo], acc[mo][ni], 0, 0, 0);
     }
 
-    // ---- bias + residual, fp32 store to the other buffer.  Each wave transposes 32 columns at a time
-    // through a private LDS block so that a lane owns 4 consecutive channels and CH/4 consecutive lanes a
-    // whole row: residual loads and stores are contiguous runs.  Rows past out_hi are outside the
-    // descriptors and dropped.
-    __syncthreads();                                   // all waves are done with the 1x1 weights in LDS
-    float* stage = reinterpret_cast<float*>(smem) + wn * (32 * LDT);
-    float4 a4 = make_float4(0, 0, 0, 0), i4 = a4;
-    if (EMIT) {
-        a4 = *reinterpret_cast<const float4*>(p.a3 + 4 * cl);
-        i4 = *reinterpret_cast<const float4*>(p.ib3 + 4 * cl);
+    // ---- residual add and half store to the other buffer, straight from the accumulators: register 4g + q of tile
+    // (mo, ni) is time row 8g + 4h + q, channel j TM + mo.  Rows past out_hi are outside the descriptors and dropped.
+    float a3v[TM], i3v[TM];
+#pragma unroll
+    for (int mo = 0; mo < TM; ++mo) {
+        a3v[mo] = EMIT ? p.a3[j * TM + mo] : 0.f;
+        i3v[mo] = EMIT ? p.ib3[j * TM + mo] : 0.f;
     }
 #pragma unroll
-    for (int ni = 0; ni < TN; ++ni) {
+    for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-        for (int mo = 0; mo < TM; ++mo)
+        for (int gq = 0; gq < 16; ++gq) {
+            const unsigned off = res_offset(ni, gq);
+            float v[TM];
+            typedef _Float16 halfs_t __attribute__((ext_vector_type(TM)));
+            const halfs_t r = __builtin_bit_cast(halfs_t, resv[ni][gq]);
+            static_assert(sizeof(halfs_t) == sizeof(res_t), "TM halves");
+            halfs_t o;
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
-                *reinterpret_cast<float4*>(&stage[j * LDT + mo * 32 + 8 * g + 4 * h]) =
-                    make_float4(acc[mo][ni][4 * g + 0], acc[mo][ni][4 * g + 1], acc[mo][ni][4 * g + 2], acc[mo][ni][4 * g + 3]);
-#pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it) {
-            const int row = it * RPI + rl;
-            const float4 t4 = *reinterpret_cast<const float4*>(&stage[row * LDT + 4 * cl]);
-            const int col = n0 + wn * WTN + ni * 32 + row;
-            const unsigned e = (unsigned)(col * CH + 4 * cl);
-            const f16x4 r = __builtin_bit_cast(f16x4, resv[ni][it]);
-            float v0 = t4.x + (float)r[0], v1 = t4.y + (float)r[1], v2 = t4.z + (float)r[2], v3 = t4.w + (float)r[3];
-            hres_store4(rs_y, e, v0, v1, v2, v3);
+            for (int mo = 0; mo < TM; ++mo) {
+                v[mo] = acc[mo][ni][gq] + (float)r[mo];
+                o[mo] = (_Float16)v[mo];                         // round to nearest even
+            }
+            if constexpr (TM == 2) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, o), rs_y, off, 0, 0);
+            else __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), rs_y, off, 0, 0);
             if (EMIT) {
                 // the next layer's operand is Snake of the STORED value
-                v0 = hres_round(v0); v1 = hres_round(v1); v2 = hres_round(v2); v3 = hres_round(v3);
-                v0 = snake_fast(v0, a4.x, i4.x); v1 = snake_fast(v1, a4.y, i4.y);
-                v2 = snake_fast(v2, a4.z, i4.z); v3 = snake_fast(v3, a4.w, i4.w);
-                const u32x2 sh = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
-                __builtin_amdgcn_raw_buffer_store_b64(sh, rs_a, e * 2u, 0, 0);
+                uint32_t sh[TM / 2];
+#pragma unroll
+                for (int mo = 0; mo < TM; mo += 2) {
+                    const float e0 = snake_fast((float)o[mo], a3v[mo], i3v[mo]);
+                    const float e1 = snake_fast((float)o[mo + 1], a3v[mo + 1], i3v[mo + 1]);
+                    sh[mo / 2] = pack_bf16x2(e0, e1);
+                }
+                if constexpr (TM == 2) __builtin_amdgcn_raw_buffer_store_b32(sh[0], rs_a, off, 0, 0);
+                else { const u32x2 s2 = {sh[0], sh[1]}; __builtin_amdgcn_raw_buffer_store_b64(s2, rs_a, off, 0, 0); }
             }
         }
-    }
 }
 
 hipError_t launch_res_unit_fused(const FusedArgs& a, hipStream_t stream)
