@@ -10,6 +10,10 @@
 // unit, a lane of an accumulator tile holds column j and rows 8g + 4h + {0..3}, which after bias + Snake are the
 // B fragments of the 1x1 convolution once its K axis is permuted to that order (fused_k_to_channel); its weights,
 // 128 KB, do not fit the LDS and are streamed through the weight buffers in 8 blocks of 32 k-slots.
+// In the 1x1 convolution the roles are swapped: the fragments are the row operand (rows = time), the weights the
+// column operand, so its accumulator tile is [time][output channel slot]; the weight rows are packed so that slot j
+// of tile mo is channel 8 j + mo.  A lane then owns 8 consecutive channels (16 bytes of half) of a time row and 32
+// lanes the whole row: residual loads and stores are contiguous straight from the accumulators.
 // The residual stream is updated in place (only this tile reads or writes its elements); the emitted operand of
 // the next layer goes to a second buffer because neighbouring tiles still read this tile's input rows.
 #include <algorithm>
@@ -26,8 +30,6 @@ constexpr int W_SEGS = W_KC / 8, W_RPP = 256 / W_SEGS;
 constexpr int W_A_CH = W_CH * W_SEGS, W_A_ITERS = W_A_CH / 256;
 constexpr int W_X_ITERS = (W_XR_MAX + W_RPP - 1) / W_RPP;
 constexpr int W_NCHUNKS = W_CH / W_KC;
-constexpr int W_GRP = 64;                        // channels transposed at a time in the epilogue
-constexpr int W_LDT = W_GRP + 4;
 
 struct WideParams {
     const uint16_t* xa;          // activated input, bf16 [rows][256]
@@ -48,8 +50,7 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
     constexpr int CH = W_CH, KC = W_KC, LDK = W_LDK, NT = W_NT, TM = W_TM;
     constexpr int A_ITERS = W_A_ITERS, X_ITERS = W_X_ITERS, SEGS = W_SEGS, RPP = W_RPP;
     constexpr int AS_BYTES = 2 * CH * LDK * 2, XS_BYTES = W_XR_MAX * LDK * 2;
-    constexpr int STG_BYTES = 4 * 32 * W_LDT * 4;
-    constexpr int SMEM_BYTES = (AS_BYTES + XS_BYTES > STG_BYTES) ? AS_BYTES + XS_BYTES : STG_BYTES;
+    constexpr int SMEM_BYTES = AS_BYTES + XS_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
     __shared__ __attribute__((aligned(16))) float prm[4 * CH];     // b7 | a2 | ib2 | b1
     uint16_t* As = reinterpret_cast<uint16_t*>(smem);
@@ -202,17 +203,17 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
     store_a(0);
     load_set(ra, rs_w1, 1);
     load_set(rb, rs_w1, 2);
-    init_acc(3);
-    __syncthreads();
-    constexpr int LPR = W_GRP / 4;                     // epilogue: lanes per row
-    constexpr int RPI = 64 / LPR;                      // rows per instruction
-    const int cl = lane % LPR, rl = lane / LPR;
-    u32x2 resv[CH / W_GRP][32 / RPI];
-    auto load_res = [&](int grp) __attribute__((always_inline)) {
+    // accumulator tile mo of the 1x1 conv: [time row 8g + 4h + q][channel slot j] = channel 8 j + mo; starts at its bias
 #pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it)
-            resv[grp][it] = __builtin_amdgcn_raw_buffer_load_b64(
-                rs_y, (unsigned)((n0 + wn * 32 + it * RPI + rl) * CH + grp * W_GRP + 4 * cl) * 2u, 0, 0);
+    for (int mo = 0; mo < TM; ++mo) {
+        const float b1v = prm[3 * CH + j * TM + mo];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[mo][q] = b1v;
+    }
+    __syncthreads();
+    u32x4 resv[16];                                    // 8 halves: the lane's channels of time row gq
+    auto row_offset = [&](int gq) -> unsigned {
+        return (unsigned)((n0 + wn * 32 + 8 * (gq >> 2) + 4 * h + (gq & 3)) * CH + j * TM) * 2u;
     };
 #pragma unroll
     for (int c = 0; c < W_NCHUNKS; ++c) {
@@ -221,69 +222,66 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
         for (int mo = 0; mo < TM; ++mo) {
             const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(abase + mo * 32 * LDK);
             const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(abase + mo * 32 * LDK + 16);
-            acc[mo] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, __builtin_bit_cast(bf16x8, mid[2 * c]), acc[mo], 0, 0, 0);
-            acc[mo] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, __builtin_bit_cast(bf16x8, mid[2 * c + 1]), acc[mo], 0, 0, 0);
+            acc[mo] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, mid[2 * c]), a0, acc[mo], 0, 0, 0);
+            acc[mo] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, mid[2 * c + 1]), a1, acc[mo], 0, 0, 0);
         }
         if (c + 1 < W_NCHUNKS) {
             if ((c + 1) & 1) store_set(ra, (c + 1) & 1); else store_set(rb, (c + 1) & 1);
             __syncthreads();
             if (c + 3 < W_NCHUNKS) { if ((c + 3) & 1) load_set(ra, rs_w1, c + 3); else load_set(rb, rs_w1, c + 3); }
         }
-        if (c >= W_NCHUNKS / 2) load_res(c - W_NCHUNKS / 2);        // chunks 4..7 request groups 0..3
-    }
-    static_assert(W_NCHUNKS / 2 == CH / W_GRP, "one residual group per chunk of the second half");
-
-    // ---- residual add, half store in place, optional Snake + bf16 operand for the next layer.  Each wave transposes
-    // its 32 columns through a private LDS block, 64 channels at a time, so that a lane owns 4 consecutive channels
-    // and 16 consecutive lanes a 128-byte run of a row.  Rows past out_hi are outside the descriptors and dropped.
-    __syncthreads();                                   // all waves are done with the weight buffers
-    float* stage = reinterpret_cast<float*>(smem) + wn * (32 * W_LDT);
+        if (c >= W_NCHUNKS / 2) {                      // chunks 4..7 request four time rows each
 #pragma unroll
-    for (int grp = 0; grp < CH / W_GRP; ++grp) {
-        float4 a4 = make_float4(0, 0, 0, 0), i4 = a4;
-        if (EMIT) {
-            a4 = *reinterpret_cast<const float4*>(p.a3 + grp * W_GRP + 4 * cl);
-            i4 = *reinterpret_cast<const float4*>(p.ib3 + grp * W_GRP + 4 * cl);
+            for (int q = 0; q < 4; ++q) {
+                const int gq = (c - W_NCHUNKS / 2) * 4 + q;
+                resv[gq] = __builtin_amdgcn_raw_buffer_load_b128(rs_y, row_offset(gq), 0, 0);
+            }
         }
+    }
+    static_assert(W_NCHUNKS / 2 * 4 == 16, "four time rows per chunk of the second half");
+
+    // ---- residual add, half store in place, optional Snake + bf16 operand for the next layer, straight from the
+    // accumulators.  Rows past out_hi are outside the descriptors and dropped.
+    float a3v[TM], i3v[TM];
 #pragma unroll
-        for (int m2 = 0; m2 < W_GRP / 32; ++m2)
+    for (int mo = 0; mo < TM; ++mo) {
+        a3v[mo] = EMIT ? p.a3[j * TM + mo] : 0.f;
+        i3v[mo] = EMIT ? p.ib3[j * TM + mo] : 0.f;
+    }
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x16& a = acc[grp * (W_GRP / 32) + m2];
-                *reinterpret_cast<float4*>(&stage[j * W_LDT + m2 * 32 + 8 * g + 4 * h]) =
-                    make_float4(a[4 * g + 0], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
-            }
+    for (int gq = 0; gq < 16; ++gq) {
+        const unsigned off = row_offset(gq);
+        const f16x8 r = __builtin_bit_cast(f16x8, resv[gq]);
+        f16x8 o;
 #pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it) {
-            const int row = it * RPI + rl;
-            const float4 t4 = *reinterpret_cast<const float4*>(&stage[row * W_LDT + 4 * cl]);
-            const unsigned e = (unsigned)((n0 + wn * 32 + row) * CH + grp * W_GRP + 4 * cl);
-            const f16x4 r = __builtin_bit_cast(f16x4, resv[grp][it]);
-            float v0 = t4.x + (float)r[0], v1 = t4.y + (float)r[1], v2 = t4.z + (float)r[2], v3 = t4.w + (float)r[3];
-            hres_store4(rs_y, e, v0, v1, v2, v3);
-            if (EMIT) {
-                // the next layer's operand is Snake of the STORED value
-                v0 = snake_fast(hres_round(v0), a4.x, i4.x); v1 = snake_fast(hres_round(v1), a4.y, i4.y);
-                v2 = snake_fast(hres_round(v2), a4.z, i4.z); v3 = snake_fast(hres_round(v3), a4.w, i4.w);
-                const u32x2 sh = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
-                __builtin_amdgcn_raw_buffer_store_b64(sh, rs_a, e * 2u, 0, 0);
-            }
+        for (int mo = 0; mo < TM; ++mo) o[mo] = (_Float16)(acc[mo][gq] + (float)r[mo]);     // round to nearest even
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, o), rs_y, off, 0, 0);
+        if (EMIT) {
+            // the next layer's operand is Snake of the STORED value
+            u32x4 sh;
+#pragma unroll
+            for (int mo = 0; mo < TM; mo += 2)
+                sh[mo / 2] = pack_bf16x2(snake_fast((float)o[mo], a3v[mo], i3v[mo]), snake_fast((float)o[mo + 1], a3v[mo + 1], i3v[mo + 1]));
+            __builtin_amdgcn_raw_buffer_store_b128(sh, rs_a, off, 0, 0);
         }
     }
 }
 
 }  // namespace
 
-// W1 [256][256] -> 8 blocks of 256 rows x 32 k-slots, the K axis in the accumulator row order of the narrow fused unit
+// W1 [256][256] -> 8 blocks of 256 row slots x 32 k-slots, the K axis in the accumulator row order of the narrow fused
+// unit, the rows in the order of the swapped-role accumulator tiles
 void pack_w1_wide(const float* w, uint16_t* dst)
 {
     for (int c = 0; c < W_NCHUNKS; ++c)
-        for (int o = 0; o < W_CH; ++o)
+        for (int slot = 0; slot < W_CH; ++slot) {
+            const int o = (slot % 32) * W_TM + slot / 32;          // row slot (mo, j) holds output channel 8 j + mo
             for (int e = 0; e < W_KC; ++e) {
                 const int kp = c * W_KC + e, kk = kp / 16, h = (kp / 8) % 2, q = kp % 8;
                 const int ch = 32 * (kk / 2) + 8 * (2 * (kk % 2) + q / 4) + 4 * h + q % 4;
-                dst[((size_t)c * W_CH + o) * W_KC + e] = f32_to_bf16_rne(w[(size_t)o * W_CH + ch]);
+                dst[((size_t)c * W_CH + slot) * W_KC + e] = f32_to_bf16_rne(w[(size_t)o * W_CH + ch]);
             }
+        }
 }
 
 hipError_t launch_res_unit_wide(const WideArgs& a, hipStream_t stream)
