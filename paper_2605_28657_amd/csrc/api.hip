@@ -37,6 +37,7 @@ const bool g_dual_stream = getenv("DEMON_VAE_ONE_STREAM") == nullptr;
 struct ConvLayer {
     int cin = 0, cout = 0, ntaps = 0, dil = 1, stride = 0, variant = -1;
     int in_fmt = OP_BF16;              // bf16 path: format of the activation operand (the weights are packed to match)
+    bool generic = true;               // bf16 path: runs on launch_conv_bf16 (row order of its accumulator tiles)
     int margin = 0;                    // output rows beyond the interior that later layers read
     const void* w = nullptr;
     const float* bias = nullptr;
@@ -150,7 +151,7 @@ size_t pack_conv(Arena& ar, const float* w, ConvLayer& L, bool bf16)
     if (bf16) {
         const size_t n = packed_bf16_count(L.cin, L.cout, L.ntaps, L.stride, L.variant);
         const size_t off = ar.reserve(n * 2);
-        pack_bf16(w, L.cin, L.cout, L.ntaps, L.stride, L.variant, L.in_fmt == OP_F16, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
+        pack_bf16(w, L.cin, L.cout, L.ntaps, L.stride, L.variant, L.in_fmt == OP_F16, L.generic, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
         return off;
     }
     const size_t n = packed_f32_count(L.cin, L.cout, L.ntaps, L.stride);
@@ -577,9 +578,9 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
             // next block's transposed conv wants its input in a wider format
             const bool feeds_split = j + 1 == st.dilations.size() && l + 1 < st.strides.size() && st.widths[l + 1] >= kSplitWidth;
             U.fused = bf && (c == 64 || c == 128) && (st.res_kernel - 1) * st.dilations[j] <= 64 && !wide_ops && g_allow_fused && !feeds_split;
-            if (U.fused) D.variant = (c == 64) ? 1 : 0;      // weight blocks of C x 64
+            if (U.fused) { D.variant = (c == 64) ? 1 : 0; D.generic = false; }     // weight blocks of C x 64
             U.wide = bf && c == 256 && (st.res_kernel - 1) * st.dilations[j] <= 64 && !wide_ops && g_allow_fused && !feeds_split;
-            if (U.wide) D.variant = 3;                       // weight blocks of 256 x 32
+            if (U.wide) { D.variant = 3; D.generic = false; }                      // weight blocks of 256 x 32
             Pending pd{&D, 0, 0, {}, {}, true, true};
             pd.in = pack_snake(ar, w, w + c, c, bf);     w += 2 * c;
             pd.w = pack_conv(ar, w, D, bf);              w += (size_t)c * c * st.res_kernel;

@@ -88,8 +88,10 @@ size_t packed_f32_count(int cin, int cout, int ntaps, int stride);
 void pack_f32(const float* w_src, int cin, int cout, int ntaps, int stride, float* dst);
 int  choose_variant_bf16(int cin, int m);   // -1 if unsupported
 size_t packed_bf16_count(int cin, int cout, int ntaps, int stride, int variant);
-// `as_half`: the 16-bit weights are IEEE half (for a layer whose activation operand is OP_F16), else bf16
-void pack_bf16(const float* w_src, int cin, int cout, int ntaps, int stride, int variant, bool as_half, uint16_t* dst);
+// `as_half`: the 16-bit weights are IEEE half (for a layer whose activation operand is OP_F16), else bf16.
+// `permute_rows`: row order of launch_conv_bf16's accumulator tiles (not for the layouts the fused units read).
+void pack_bf16(const float* w_src, int cin, int cout, int ntaps, int stride, int variant, bool as_half, bool permute_rows,
+               uint16_t* dst);
 uint16_t f32_to_bf16_rne(float v);
 uint16_t f32_to_f16_rne(float v);
 

@@ -26,11 +26,19 @@
 // loads return zero = the convolution's zero padding at a clip edge, stores are dropped), so the
 // kernel has no per-row branches and all offsets are 32-bit.
 //
+// Orientation of the accumulators.  The activation fragments are the row operand of the MFMA (rows = time) and the
+// weight fragments the column operand, so a 32 x 32 accumulator tile is [time][GEMM row slot]: lane (j, h) holds slot j
+// of each of the wave's TM row tiles, for the time rows 8g + 4h + {0..3}.  The weights are packed so that slot j of
+// tile mi is GEMM row j TM + mi of the wave's block: a lane owns TM consecutive output channels of a time row and 32
+// lanes a contiguous run of 32 TM channels, so residual loads and all stores go straight from the accumulators in
+// whole runs (no transposition through LDS).
+//
 // Accumulation is fp32 in a fixed order (chunk-major, then tap, then channel), independent of where the
 // tile sits in the window, so a windowed decode reproduces the full decode bit for bit.
 #include <stdlib.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "device_common.h"
 
@@ -108,9 +116,21 @@ size_t packed_bf16_count(int cin, int cout, int ntaps, int stride, int variant)
     return M * (size_t)ntaps * cin;
 }
 
-void pack_bf16(const float* w, int cin, int cout, int ntaps, int stride, int variant, bool as_half, uint16_t* dst)
+// GEMM row held by row slot r of a packed block: within each block of 32 tm slots (the rows of one wave), slot
+// mi * 32 + j is row j tm + mi (see "orientation of the accumulators"); identity for the tiles with 32 rows per wave
+// and for the layouts read by the fused units.
+static inline int slot_to_row(int r, int tm)
+{
+    if (tm <= 1) return r;
+    const int rows = 32 * tm, blk = r / rows, sl = r % rows;
+    return blk * rows + (sl % 32) * tm + sl / 32;
+}
+
+void pack_bf16(const float* w, int cin, int cout, int ntaps, int stride, int variant, bool as_half, bool permute_rows,
+               uint16_t* dst)
 {
     const Variant v = kVariants[variant];
+    const int perm = (permute_rows && v.MT % 64 == 0) ? 2 : 1;
     const int M = stride > 0 ? stride * cout : cout;
     const int nch = cin / v.KC;
     size_t pos = 0;
@@ -119,7 +139,7 @@ void pack_bf16(const float* w, int cin, int cout, int ntaps, int stride, int var
             for (int t = 0; t < ntaps; ++t)
                 for (int i = 0; i < v.MT; ++i)
                     for (int e = 0; e < v.KC; ++e) {
-                        const int mu = mt * v.MT + i, ci = c * v.KC + e;
+                        const int mu = mt * v.MT + slot_to_row(i, perm), ci = c * v.KC + e;
                         float val;
                         if (stride == 0) {
                             val = w[((size_t)mu * cin + ci) * ntaps + t];
@@ -157,14 +177,12 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     constexpr int X_ITERS = (XR_MAX + RPP - 1) / RPP;
     constexpr bool SPLIT_IN = IN == OP_BF16X2;
     constexpr int NP = SPLIT_IN ? 2 : 1;        // operand planes (hi, lo)
-    static_assert(WM * WN == 4 || WM * WN == 8, "four or eight waves per workgroup");
+    static_assert(WM * WN == 2 || WM * WN == 4 || WM * WN == 8, "two, four or eight waves per workgroup");
+    static_assert(TM == 1 || TM == 2 || TM == 4, "a lane owns one, two or four consecutive output channels");
     static_assert(MODE != MODE_ACT || EMIT > 0, "the dilated conv only has the activated output");
 
-    // epilogue staging: every wave transposes its accumulators through a private 32-column block
-    constexpr int LDT = WTM + 4;                // padded row (floats) of the staging block
-    constexpr int STG_BYTES = WM * WN * 32 * LDT * 4;
     constexpr int AS_BYTES = 2 * MT * LDK * 2, XS_BYTES = NP * XR_MAX * LDK * 2;
-    constexpr int SMEM_BYTES = (AS_BYTES + XS_BYTES > STG_BYTES) ? AS_BYTES + XS_BYTES : STG_BYTES;
+    constexpr int SMEM_BYTES = AS_BYTES + XS_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
     uint16_t (*As)[MT * LDK] = reinterpret_cast<uint16_t (*)[MT * LDK]>(smem);
     uint16_t (*Xs)[XR_MAX * LDK] = reinterpret_cast<uint16_t (*)[XR_MAX * LDK]>(smem + AS_BYTES);
@@ -264,38 +282,42 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
         }
     };
 
-    // accumulators start at the bias: lane (j, h) holds GEMM rows m0 + wm*WTM + mi*32 + 8g + 4h + {0..3}
+    // this lane's TM consecutive GEMM rows; the accumulators start at their bias
+    const int mu0 = m0 + wm * WTM + j * TM;
+    const int o0 = (MODE == MODE_UP) ? mu0 % p.cout : mu0;
     f32x16 acc[TM][TN];
 #pragma unroll
-    for (int mi = 0; mi < TM; ++mi)
+    for (int mi = 0; mi < TM; ++mi) {
+        const float bv = p.bias[o0 + mi];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int mu_b = m0 + wm * WTM + mi * 32 + 8 * g + 4 * h;
-            const float4 bb = *reinterpret_cast<const float4*>(p.bias + ((MODE == MODE_UP) ? mu_b % p.cout : mu_b));
+        for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-            for (int ni = 0; ni < TN; ++ni) {
-                acc[mi][ni][4 * g + 0] = bb.x; acc[mi][ni][4 * g + 1] = bb.y;
-                acc[mi][ni][4 * g + 2] = bb.z; acc[mi][ni][4 * g + 3] = bb.w;
-            }
-        }
+            for (int q = 0; q < 16; ++q) acc[mi][ni][q] = bv;
+    }
 
-    // Epilogue geometry (see the epilogue): a lane owns 4 consecutive channels of RPI-strided rows.
-    constexpr int LPR = WTM / 4;                       // lanes per row
-    constexpr int RPI = 64 / LPR;                      // rows per instruction
-    const int cl = lane % LPR, rl = lane / LPR;
+    // Element index (in the window) of this lane's channels at time row gq = 4g + q of time tile ni.  Conv: (col, mu0);
+    // transposed conv: column m, row mu = phi*cout + o lands on sample m s - p + phi, i.e. on the run starting at
+    // (m s - p) cout + mu.  A negative row wraps to a huge offset = out of range.
+    const int s_up = p.stride, p_up = p.stride / 2;
+    auto elem = [&](int ni, int gq) -> unsigned {
+        const int col = n0 + wn * WTN + ni * 32 + 8 * (gq >> 2) + 4 * h + (gq & 3);
+        return (MODE == MODE_UP) ? (unsigned)((col * s_up - p_up) * p.cout + mu0) : (unsigned)(col * p.cout + mu0);
+    };
     const unsigned out_rows = (unsigned)out_hi;
     const __amdgpu_buffer_rsrc_t rs_y = make_rsrc(MODE == MODE_ACT ? nullptr : p.y + rowbase_o * p.cout,
                                                   MODE == MODE_ACT ? 0u : out_rows * p.cout * (unsigned)sizeof(hres_t));
     // The residual values this lane will add are fetched now: issued in the epilogue, each of the loads would be
     // waited for in turn (they cannot move above the in-place stores), a chain of memory latencies per tile.
-    u32x2 resv[MODE == MODE_RES ? TN : 1][32 / RPI];
+    using pack_t = std::conditional_t<TM == 4, uint64_t, std::conditional_t<TM == 2, uint32_t, uint16_t>>;     // TM 16-bit values
+    pack_t resv[MODE == MODE_RES ? TN : 1][16];
     if (MODE == MODE_RES) {
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-            for (int it = 0; it < 32 / RPI; ++it) {
-                const int col = n0 + wn * WTN + ni * 32 + it * RPI + rl;
-                resv[ni][it] = __builtin_amdgcn_raw_buffer_load_b64(rs_y, (unsigned)(col * p.cout + m0 + wm * WTM + 4 * cl) * 2u, 0, 0);
+            for (int gq = 0; gq < 16; ++gq) {
+                if constexpr (TM == 4) resv[ni][gq] = __builtin_bit_cast(uint64_t, __builtin_amdgcn_raw_buffer_load_b64(rs_y, elem(ni, gq) * 2u, 0, 0));
+                else if constexpr (TM == 2) resv[ni][gq] = __builtin_amdgcn_raw_buffer_load_b32(rs_y, elem(ni, gq) * 2u, 0, 0);
+                else resv[ni][gq] = __builtin_amdgcn_raw_buffer_load_b16(rs_y, elem(ni, gq) * 2u, 0, 0);
             }
     }
 
@@ -328,15 +350,16 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
                 for (int ni = 0; ni < TN; ++ni)
                     bfr[pl][ni] = *reinterpret_cast<const u32x4*>(&Xs[pl][xoff + ni * 32 * LDK + ks * 16]);
 #pragma unroll
-            for (int mi = 0; mi < TM; ++mi)
+            for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-                for (int ni = 0; ni < TN; ++ni)
+                for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
                     for (int pl = 0; pl < NP; ++pl) {
+                        // activations are the row operand: the accumulator tile is [time][row slot]
                         if (IN == OP_F16)
-                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, af[mi]), __builtin_bit_cast(f16x8, bfr[pl][ni]), acc[mi][ni], 0, 0, 0);
+                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, bfr[pl][ni]), __builtin_bit_cast(f16x8, af[mi]), acc[mi][ni], 0, 0, 0);
                         else
-                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[mi]), __builtin_bit_cast(bf16x8, bfr[pl][ni]), acc[mi][ni], 0, 0, 0);
+                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfr[pl][ni]), __builtin_bit_cast(bf16x8, af[mi]), acc[mi][ni], 0, 0, 0);
                     }
         }
 
@@ -351,66 +374,64 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
         tap = ntap; chunk = nchunk;
     }
 
-    // ---- epilogue.  A lane of a 32x32 accumulator tile holds ONE time column and rows 8g + 4h + {0..3}:
-    // stored as is, every instruction would touch 32 different rows with 16-32 bytes each.  Instead each
-    // wave transposes 32 columns at a time through a private LDS block and then handles whole rows:
-    // a lane owns 4 consecutive channels, WTM/4 consecutive lanes cover a row, so residual loads and all
-    // stores are full contiguous runs.  Rows past out_hi (and, for the transposed conv, before row 0) are
-    // out of range of the descriptors and dropped.
-    __syncthreads();                                   // all waves are done with the operand tiles
-    float* stage = reinterpret_cast<float*>(smem) + wave * (32 * LDT);
+    // ---- epilogue, straight from the accumulators: register gq of tile (mi, ni) is time row 8g + 4h + q of time tile
+    // ni and GEMM row mu0 + mi.  Rows past out_hi (and, for the transposed conv, before row 0) are out of range of the
+    // descriptors and dropped.
     const __amdgpu_buffer_rsrc_t rs_a = make_rsrc(p.ya + rowbase_o * p.cout, EMIT > 0 ? out_rows * p.cout * 2u : 0u);
     const __amdgpu_buffer_rsrc_t rs_al = make_rsrc(p.ya + p.out_lo_off + rowbase_o * p.cout, EMIT == 2 ? out_rows * p.cout * 2u : 0u);
-    const int mu = m0 + wm * WTM + 4 * cl;             // this lane's 4 GEMM rows
-    const int o = (MODE == MODE_UP) ? mu % p.cout : mu;   // ... are 4 consecutive output channels
-    float4 oa = make_float4(0, 0, 0, 0), ob = oa;
-    if (EMIT > 0) {
-        oa = *reinterpret_cast<const float4*>(p.out_alpha + o);
-        ob = *reinterpret_cast<const float4*>(p.out_inv_beta + o);
+    float oa[TM], ob[TM];
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi) {
+        oa[mi] = EMIT > 0 ? p.out_alpha[o0 + mi] : 0.f;
+        ob[mi] = EMIT > 0 ? p.out_inv_beta[o0 + mi] : 0.f;
     }
-    const int s_up = p.stride, p_up = p.stride / 2;
+    auto store16 = [&](__amdgpu_buffer_rsrc_t rs, unsigned e, const uint16_t (&bits)[TM]) __attribute__((always_inline)) {
+        if constexpr (TM == 4) {
+            const u32x2 v2 = {(uint32_t)bits[0] | ((uint32_t)bits[1] << 16), (uint32_t)bits[2] | ((uint32_t)bits[3] << 16)};
+            __builtin_amdgcn_raw_buffer_store_b64(v2, rs, e * 2u, 0, 0);
+        } else if constexpr (TM == 2) __builtin_amdgcn_raw_buffer_store_b32((uint32_t)bits[0] | ((uint32_t)bits[1] << 16), rs, e * 2u, 0, 0);
+        else __builtin_amdgcn_raw_buffer_store_b16(bits[0], rs, e * 2u, 0, 0);
+    };
 #pragma unroll
-    for (int ni = 0; ni < TN; ++ni) {
+    for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-        for (int mi = 0; mi < TM; ++mi)
+        for (int gq = 0; gq < 16; ++gq) {
+            const unsigned e = elem(ni, gq);
+            float v[TM];
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
-                *reinterpret_cast<float4*>(&stage[j * LDT + mi * 32 + 8 * g + 4 * h]) =
-                    make_float4(acc[mi][ni][4 * g + 0], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2], acc[mi][ni][4 * g + 3]);
-#pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it) {
-            const int row = it * RPI + rl;
-            const float4 t4 = *reinterpret_cast<const float4*>(&stage[row * LDT + 4 * cl]);
-            float v0 = t4.x, v1 = t4.y, v2 = t4.z, v3 = t4.w;
-            const int col = n0 + wn * WTN + ni * 32 + row;
-            // element index inside the window: conv (col, mu); transposed conv: column m, row mu = phi*cout + o
-            // lands on sample m s - p + phi, i.e. on the run starting at (m s - p) cout + mu.  A negative row
-            // wraps to a huge offset = out of range.
-            const unsigned e = (MODE == MODE_UP) ? (unsigned)((col * s_up - p_up) * p.cout + mu) : (unsigned)(col * p.cout + mu);
+            for (int mi = 0; mi < TM; ++mi) v[mi] = acc[mi][ni][gq];
             if (MODE == MODE_RES) {
-                const f16x4 r = __builtin_bit_cast(f16x4, resv[ni][it]);
-                v0 += (float)r[0]; v1 += (float)r[1]; v2 += (float)r[2]; v3 += (float)r[3];
+#pragma unroll
+                for (int mi = 0; mi < TM; ++mi)
+                    v[mi] += (float)__builtin_bit_cast(_Float16, (uint16_t)(resv[ni][gq] >> (16 * mi)));
             }
             if (MODE != MODE_ACT) {
-                hres_store4(rs_y, e, v0, v1, v2, v3);
-                // the next layer's operand is Snake of the STORED value (what a kernel reading h would see)
-                v0 = hres_round(v0); v1 = hres_round(v1); v2 = hres_round(v2); v3 = hres_round(v3);
+                uint16_t hb[TM];
+#pragma unroll
+                for (int mi = 0; mi < TM; ++mi) {
+                    const _Float16 hv = (_Float16)v[mi];           // round to nearest even
+                    hb[mi] = __builtin_bit_cast(uint16_t, hv);
+                    v[mi] = (float)hv;                             // the next layer's operand is Snake of the STORED value
+                }
+                store16(rs_y, e, hb);
             }
             if (EMIT > 0) {
-                v0 = snake_fast(v0, oa.x, ob.x); v1 = snake_fast(v1, oa.y, ob.y);
-                v2 = snake_fast(v2, oa.z, ob.z); v3 = snake_fast(v3, oa.w, ob.w);
-                if (EMIT == 3) { v0 = keep_f32(v0); v1 = keep_f32(v1); v2 = keep_f32(v2); v3 = keep_f32(v3); }   // fp32 Snake, then one rounding
-                const u32x2 sh = {EMIT == 3 ? pack_f16x2(v0, v1) : pack_bf16x2(v0, v1), EMIT == 3 ? pack_f16x2(v2, v3) : pack_bf16x2(v2, v3)};
-                __builtin_amdgcn_raw_buffer_store_b64(sh, rs_a, e * 2u, 0, 0);
-                if (EMIT == 2) {
-                    // lo plane: what the hi plane's rounding left over
-                    const u32x2 sl = {pack_bf16x2(v0 - __uint_as_float(sh[0] << 16), v1 - __uint_as_float(sh[0] & 0xffff0000u)),
-                                      pack_bf16x2(v2 - __uint_as_float(sh[1] << 16), v3 - __uint_as_float(sh[1] & 0xffff0000u))};
-                    __builtin_amdgcn_raw_buffer_store_b64(sl, rs_al, e * 2u, 0, 0);
+                uint16_t ab[TM], lb[TM];
+#pragma unroll
+                for (int mi = 0; mi < TM; ++mi) {
+                    float a = snake_fast(v[mi], oa[mi], ob[mi]);
+                    if (EMIT == 3) {
+                        a = keep_f32(a);                           // fp32 Snake, then one rounding
+                        ab[mi] = __builtin_bit_cast(uint16_t, (_Float16)a);
+                    } else {
+                        ab[mi] = f32_to_bf16_bits(a);
+                        if (EMIT == 2) lb[mi] = f32_to_bf16_bits(a - bf16_bits_to_f32(ab[mi]));   // what the hi plane's rounding left over
+                    }
                 }
+                store16(rs_a, e, ab);
+                if (EMIT == 2) store16(rs_al, e, lb);
             }
         }
-    }
 }
 
 template <int MT, int NT, int KC, int WM, int WN>
@@ -502,7 +523,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     p.xcd_group = w_fits_l2 ? 1 : 0;
     dim3 grid(m_fastest ? (unsigned)(ntiles8 * mtiles) : (unsigned)ntiles, (unsigned)a.n_slots, m_fastest ? 1u : (unsigned)mtiles);
     switch (variant) {
-        case 0: return small_tile ? launch_variant<64, 64, 64, 2, 2>(p, mode, a.in_fmt, emit, grid, stream)
+        case 0: return small_tile ? launch_variant<64, 64, 64, 1, 2>(p, mode, a.in_fmt, emit, grid, stream)
                                   : launch_variant<128, 128, 64, 2, 2>(p, mode, a.in_fmt, emit, grid, stream);
         case 1: return launch_variant<64, 256, 64, 1, 4>(p, mode, a.in_fmt, emit, grid, stream);
         default: return launch_variant<32, 128, 16, 1, 4>(p, mode, a.in_fmt, emit, grid, stream);
