@@ -116,21 +116,21 @@ size_t packed_bf16_count(int cin, int cout, int ntaps, int stride, int variant)
     return M * (size_t)ntaps * cin;
 }
 
-// GEMM row held by row slot r of a packed block: within each block of 32 tm slots (the rows of one wave), slot
-// mi * 32 + j is row j tm + mi (see "orientation of the accumulators"); identity for the tiles with 32 rows per wave
+// GEMM row held by row slot r of a packed block: within each block of 64 slots (the rows of one wave), slot
+// mi * 32 + j is row 2 j + mi (see "orientation of the accumulators"); identity for the tiles with 32 rows per wave
 // and for the layouts read by the fused units.
-static inline int slot_to_row(int r, int tm)
+static inline int slot_to_row(int r, bool permute)
 {
-    if (tm <= 1) return r;
-    const int rows = 32 * tm, blk = r / rows, sl = r % rows;
-    return blk * rows + (sl % 32) * tm + sl / 32;
+    if (!permute) return r;
+    const int blk = r / 64, sl = r % 64;
+    return blk * 64 + (sl % 32) * 2 + sl / 32;
 }
 
 void pack_bf16(const float* w, int cin, int cout, int ntaps, int stride, int variant, bool as_half, bool permute_rows,
                uint16_t* dst)
 {
     const Variant v = kVariants[variant];
-    const int perm = (permute_rows && v.MT % 64 == 0) ? 2 : 1;
+    const bool perm = permute_rows && v.MT % 64 == 0;
     const int M = stride > 0 ? stride * cout : cout;
     const int nch = cin / v.KC;
     size_t pos = 0;
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     constexpr bool SPLIT_IN = IN == OP_BF16X2;
     constexpr int NP = SPLIT_IN ? 2 : 1;        // operand planes (hi, lo)
     static_assert(WM * WN == 2 || WM * WN == 4 || WM * WN == 8, "two, four or eight waves per workgroup");
-    static_assert(TM == 1 || TM == 2 || TM == 4, "a lane owns one, two or four consecutive output channels");
+    static_assert(TM == 1 || TM == 2, "a lane owns one or two consecutive output channels");
     static_assert(MODE != MODE_ACT || EMIT > 0, "the dilated conv only has the activated output");
 
     constexpr int AS_BYTES = 2 * MT * LDK * 2, XS_BYTES = NP * XR_MAX * LDK * 2;
@@ -298,25 +298,27 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     // Element index (in the window) of this lane's channels at time row gq = 4g + q of time tile ni.  Conv: (col, mu0);
     // transposed conv: column m, row mu = phi*cout + o lands on sample m s - p + phi, i.e. on the run starting at
     // (m s - p) cout + mu.  A negative row wraps to a huge offset = out of range.
+    // (one per-lane product; the offsets of the 16 x TN time rows are uniform multiples of the row length)
     const int s_up = p.stride, p_up = p.stride / 2;
+    const int lane_col = n0 + wn * WTN + 4 * h;
+    const unsigned e_lane = (MODE == MODE_UP) ? (unsigned)((lane_col * s_up - p_up) * p.cout + mu0) : (unsigned)(lane_col * p.cout + mu0);
+    const unsigned col_elems = (MODE == MODE_UP) ? (unsigned)(s_up * p.cout) : (unsigned)p.cout;
     auto elem = [&](int ni, int gq) -> unsigned {
-        const int col = n0 + wn * WTN + ni * 32 + 8 * (gq >> 2) + 4 * h + (gq & 3);
-        return (MODE == MODE_UP) ? (unsigned)((col * s_up - p_up) * p.cout + mu0) : (unsigned)(col * p.cout + mu0);
+        return e_lane + (unsigned)(ni * 32 + 8 * (gq >> 2) + (gq & 3)) * col_elems;
     };
     const unsigned out_rows = (unsigned)out_hi;
     const __amdgpu_buffer_rsrc_t rs_y = make_rsrc(MODE == MODE_ACT ? nullptr : p.y + rowbase_o * p.cout,
                                                   MODE == MODE_ACT ? 0u : out_rows * p.cout * (unsigned)sizeof(hres_t));
     // The residual values this lane will add are fetched now: issued in the epilogue, each of the loads would be
     // waited for in turn (they cannot move above the in-place stores), a chain of memory latencies per tile.
-    using pack_t = std::conditional_t<TM == 4, uint64_t, std::conditional_t<TM == 2, uint32_t, uint16_t>>;     // TM 16-bit values
+    using pack_t = std::conditional_t<TM == 2, uint32_t, uint16_t>;     // TM 16-bit values
     pack_t resv[MODE == MODE_RES ? TN : 1][16];
     if (MODE == MODE_RES) {
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
             for (int gq = 0; gq < 16; ++gq) {
-                if constexpr (TM == 4) resv[ni][gq] = __builtin_bit_cast(uint64_t, __builtin_amdgcn_raw_buffer_load_b64(rs_y, elem(ni, gq) * 2u, 0, 0));
-                else if constexpr (TM == 2) resv[ni][gq] = __builtin_amdgcn_raw_buffer_load_b32(rs_y, elem(ni, gq) * 2u, 0, 0);
+                if constexpr (TM == 2) resv[ni][gq] = __builtin_amdgcn_raw_buffer_load_b32(rs_y, elem(ni, gq) * 2u, 0, 0);
                 else resv[ni][gq] = __builtin_amdgcn_raw_buffer_load_b16(rs_y, elem(ni, gq) * 2u, 0, 0);
             }
     }
@@ -385,13 +387,6 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
         oa[mi] = EMIT > 0 ? p.out_alpha[o0 + mi] : 0.f;
         ob[mi] = EMIT > 0 ? p.out_inv_beta[o0 + mi] : 0.f;
     }
-    auto store16 = [&](__amdgpu_buffer_rsrc_t rs, unsigned e, const uint16_t (&bits)[TM]) __attribute__((always_inline)) {
-        if constexpr (TM == 4) {
-            const u32x2 v2 = {(uint32_t)bits[0] | ((uint32_t)bits[1] << 16), (uint32_t)bits[2] | ((uint32_t)bits[3] << 16)};
-            __builtin_amdgcn_raw_buffer_store_b64(v2, rs, e * 2u, 0, 0);
-        } else if constexpr (TM == 2) __builtin_amdgcn_raw_buffer_store_b32((uint32_t)bits[0] | ((uint32_t)bits[1] << 16), rs, e * 2u, 0, 0);
-        else __builtin_amdgcn_raw_buffer_store_b16(bits[0], rs, e * 2u, 0, 0);
-    };
 #pragma unroll
     for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
@@ -406,30 +401,37 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
                     v[mi] += (float)__builtin_bit_cast(_Float16, (uint16_t)(resv[ni][gq] >> (16 * mi)));
             }
             if (MODE != MODE_ACT) {
-                uint16_t hb[TM];
-#pragma unroll
-                for (int mi = 0; mi < TM; ++mi) {
-                    const _Float16 hv = (_Float16)v[mi];           // round to nearest even
-                    hb[mi] = __builtin_bit_cast(uint16_t, hv);
-                    v[mi] = (float)hv;                             // the next layer's operand is Snake of the STORED value
+                // half store of h; the next layer's operand is Snake of the STORED value
+                if constexpr (TM == 2) {
+                    const uint32_t hb = pack_f16x2(v[0], v[1]);           // round to nearest even
+                    __builtin_amdgcn_raw_buffer_store_b32(hb, rs_y, e * 2u, 0, 0);
+                    const f16x2 hv = __builtin_bit_cast(f16x2, hb);
+                    v[0] = (float)hv[0]; v[1] = (float)hv[1];
+                } else {
+                    const _Float16 hv = (_Float16)v[0];
+                    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(uint16_t, hv), rs_y, e * 2u, 0, 0);
+                    v[0] = (float)hv;
                 }
-                store16(rs_y, e, hb);
             }
             if (EMIT > 0) {
-                uint16_t ab[TM], lb[TM];
+                float a[TM];
 #pragma unroll
                 for (int mi = 0; mi < TM; ++mi) {
-                    float a = snake_fast(v[mi], oa[mi], ob[mi]);
-                    if (EMIT == 3) {
-                        a = keep_f32(a);                           // fp32 Snake, then one rounding
-                        ab[mi] = __builtin_bit_cast(uint16_t, (_Float16)a);
-                    } else {
-                        ab[mi] = f32_to_bf16_bits(a);
-                        if (EMIT == 2) lb[mi] = f32_to_bf16_bits(a - bf16_bits_to_f32(ab[mi]));   // what the hi plane's rounding left over
-                    }
+                    a[mi] = snake_fast(v[mi], oa[mi], ob[mi]);
+                    if (EMIT == 3) a[mi] = keep_f32(a[mi]);               // fp32 Snake, then one rounding
                 }
-                store16(rs_a, e, ab);
-                if (EMIT == 2) store16(rs_al, e, lb);
+                if constexpr (TM == 2) {
+                    const uint32_t ab = EMIT == 3 ? pack_f16x2(a[0], a[1]) : pack_bf16x2(a[0], a[1]);
+                    __builtin_amdgcn_raw_buffer_store_b32(ab, rs_a, e * 2u, 0, 0);
+                    if (EMIT == 2)                                         // lo plane: what the hi plane's rounding left over
+                        __builtin_amdgcn_raw_buffer_store_b32(pack_bf16x2(a[0] - __uint_as_float(ab << 16), a[1] - __uint_as_float(ab & 0xffff0000u)),
+                                                              rs_al, e * 2u, 0, 0);
+                } else {
+                    const uint16_t ab = EMIT == 3 ? __builtin_bit_cast(uint16_t, (_Float16)a[0]) : f32_to_bf16_bits(a[0]);
+                    __builtin_amdgcn_raw_buffer_store_b16(ab, rs_a, e * 2u, 0, 0);
+                    if (EMIT == 2)
+                        __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16_bits(a[0] - bf16_bits_to_f32(ab)), rs_al, e * 2u, 0, 0);
+                }
             }
         }
 }
