@@ -56,7 +56,7 @@ void pack_w1_fused(const float* w /*[C][C]*/, int C, uint16_t* dst)
 }
 
 template <int CH, int TN, bool EMIT>
-__global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void res_unit_fused_kernel(FusedParams p)
 {
     constexpr int KC = 64;
     constexpr int LDK = KC + 8;
@@ -72,10 +72,14 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
     constexpr int LD1 = CH + 8;                   // padded row of the 1x1 weight tile
     constexpr int W1_CH = CH * CH / 8;            // 16-byte chunks of the 1x1 weights
     static_assert(A_CH % 256 == 0 && W1_CH % 256 == 0, "staging loops assume whole passes");
-    static_assert(CH * LD1 <= 2 * CH * LDK, "the 1x1 weights reuse the dilated-conv weight buffers");
-
-    constexpr int AS_BYTES = 2 * CH * LDK * 2, XS_BYTES = XR_MAX * LDK * 2;
+    // LDS and registers are budgeted for three workgroups per CU (they hide each other's barriers and latencies
+    // markedly better than two): one weight buffer (the next block waits in registers and is stored between two
+    // barriers), an activation tile without row padding (16-byte pieces XOR-swizzled by the row instead), the 1x1
+    // weights and the residual values requested after the K loop.
+    constexpr int LDX = KC;                       // unpadded row of the activation tile; piece sg of row r sits at sg ^ (r & 7)
+    constexpr int AS_BYTES = CH * LDK * 2, XS_BYTES = XR_MAX * LDX * 2;
     constexpr int SMEM_BYTES = AS_BYTES + XS_BYTES;
+    static_assert(CH * LD1 * 2 <= SMEM_BYTES, "the 1x1 weights reuse the buffers of the dilated conv");
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
     // per-channel vectors used after the K loop (bias of both convolutions, Snake between them): read from global
     // memory where they are used, each load would be waited for in turn
@@ -120,11 +124,11 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it) ra[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, a_voff, base + it * 4096u, 0);
     };
-    auto store_a = [&](int buf) __attribute__((always_inline)) {
+    auto store_a = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it) {
             const int q = tid + it * 256;
-            *reinterpret_cast<u32x4*>(&As[buf * CH * LDK + (q / SEGS) * LDK + (q % SEGS) * 8]) = ra[it];
+            *reinterpret_cast<u32x4*>(&As[(q / SEGS) * LDK + (q % SEGS) * 8]) = ra[it];
         }
     };
     auto load_x = [&](int chunk) __attribute__((always_inline)) {
@@ -153,7 +157,7 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
                 e1 = snake_fast(e1, al[2 * q + 1], ib[2 * q + 1]);
                 v[q] = pack_bf16x2(e0, e1);
             }
-            *reinterpret_cast<u32x4*>(&Xs[xr * LDK + seg * 8]) = v;
+            *reinterpret_cast<u32x4*>(&Xs[xr * LDX + ((seg ^ (xr & 7)) * 8)]) = v;
         }
     };
 
@@ -175,11 +179,9 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
         const float* src = which == 0 ? p.b7 : which == 1 ? p.a2 : which == 2 ? p.ib2 : p.b1;
         pv[it] = src[c];
     }
-    // The residual values this lane adds in the epilogue (4 consecutive channels of RPI-strided rows) are fetched
-    // ahead of time: loaded where they are used, each would be waited for in turn, a chain of memory latencies per
-    // tile.  With 64 channels there are registers to hold them through the K loop; with 128 they are fetched after
-    // it, in the shadow of the Snake and the 1x1 convolution.
-    constexpr bool EARLY_RES = CH == 64;
+    // The residual values this lane adds in the epilogue are requested in one go after the K loop, in the shadow of the
+    // Snake and the 1x1 convolution: loaded where they are used, each would be waited for in turn, a chain of memory
+    // latencies per tile (and held through the K loop they cost the registers of the third workgroup).
     // epilogue geometry: lane (j, h) owns channels j TM .. j TM + TM - 1 of time rows 8g + 4h + q of every 32-column tile
     using res_t = std::conditional_t<TM == 2, uint32_t, u32x2>;         // TM halves
     res_t resv[TN][16];
@@ -196,8 +198,7 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
                 else resv[ni][gq] = __builtin_amdgcn_raw_buffer_load_b64(rs_x, res_offset(ni, gq), 0, 0);
             }
     };
-    if (EARLY_RES) load_res();
-    store_a(0);
+    store_a();
     store_x();
 #pragma unroll
     for (int it = 0; it < PRM_ITERS; ++it) prm[tid + it * 256] = pv[it];
@@ -217,54 +218,44 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
             }
         }
 
-    // ---- dilated conv: K loop over (chunk, tap) stages, fixed order.  The last stage is peeled: its shadow hides the
-    // fetch of the 1x1 weights, and registers that are only written there must not be carried through the loop.
+    // ---- dilated conv: K loop over (chunk, tap) stages, fixed order
     int chunk = 0, tap = 0;
-    auto mma_stage = [&](int stage) __attribute__((always_inline)) {
+    for (int stage = 0; stage < nstages; ++stage) {
+        int ntap = tap + 1, nchunk = chunk;
+        if (ntap == p.ntaps) { ntap = 0; ++nchunk; }
+        const bool more = stage + 1 < nstages;
+        const bool new_chunk = more && nchunk != chunk;
+        if (more) load_a(stage + 1);
+        if (new_chunk) load_x(nchunk);
+
         const int off = p.tap0 + tap * p.tap_step - minoff;
-        const uint16_t* abase = &As[(stage & 1) * CH * LDK + j * LDK + h * 8];
-        const uint16_t* xbase = &Xs[(wn * WTN + j + off) * LDK + h * 8];
+        const uint16_t* abase = &As[j * LDK + h * 8];
+        const int xrow = wn * WTN + j + off;                  // + ni * 32: the same row & 7
+        const uint16_t* xbase = &Xs[xrow * LDX];
+        const int r7 = xrow & 7;
 #pragma unroll
         for (int ks = 0; ks < KC / 16; ++ks) {
             bf16x8 af[TM], bfr[TN];
 #pragma unroll
             for (int mi = 0; mi < TM; ++mi) af[mi] = *reinterpret_cast<const bf16x8*>(abase + mi * 32 * LDK + ks * 16);
 #pragma unroll
-            for (int ni = 0; ni < TN; ++ni) bfr[ni] = *reinterpret_cast<const bf16x8*>(xbase + ni * 32 * LDK + ks * 16);
+            for (int ni = 0; ni < TN; ++ni) bfr[ni] = *reinterpret_cast<const bf16x8*>(xbase + ni * 32 * LDX + (((2 * ks + h) ^ r7) * 8));
 #pragma unroll
             for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < TN; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
         }
-    };
-    for (int stage = 0; stage + 1 < nstages; ++stage) {
-        int ntap = tap + 1, nchunk = chunk;
-        if (ntap == p.ntaps) { ntap = 0; ++nchunk; }
-        const bool new_chunk = nchunk != chunk;
-        load_a(stage + 1);
-        if (new_chunk) load_x(nchunk);
-        mma_stage(stage);
-        if (new_chunk) {
+        if (more) {
+            __syncthreads();                                  // every wave is done with the weight buffer (and the X tile)
+            if (new_chunk) store_x();
+            store_a();
             __syncthreads();
-            store_x();
         }
-        store_a((stage + 1) & 1);
-        __syncthreads();
         tap = ntap; chunk = nchunk;
     }
     load_w1();
-    mma_stage(nstages - 1);
-
-    if (!EARLY_RES) load_res();
-
-    // ---- stage the 1x1 weights into the (now free) weight buffers
-    __syncthreads();
-#pragma unroll
-    for (int it = 0; it < W1_CH / 256; ++it) {
-        const int q = tid + it * 256;
-        *reinterpret_cast<u32x4*>(&As[(q / (CH / 8)) * LD1 + (q % (CH / 8)) * 8]) = rw1[it];
-    }
+    load_res();
 
     // ---- bias + Snake on the accumulators; repack them as the B fragments of the 1x1 conv
     u32x4 mid[CH / 16][TN];      // bf16x8 fragments, built from packed pairs
@@ -286,6 +277,14 @@ __global__ __launch_bounds__(256) void res_unit_fused_kernel(FusedParams p)
                 f[2 * (g & 1) + 1] = pack_bf16x2(v2, v3);
             }
         }
+    }
+
+    // ---- stage the 1x1 weights over the (now free) buffers of the dilated conv
+    __syncthreads();                                   // all waves are done with the last stage's operands
+#pragma unroll
+    for (int it = 0; it < W1_CH / 256; ++it) {
+        const int q = tid + it * 256;
+        *reinterpret_cast<u32x4*>(&As[(q / (CH / 8)) * LD1 + (q % (CH / 8)) * 8]) = rw1[it];
     }
     __syncthreads();
 
