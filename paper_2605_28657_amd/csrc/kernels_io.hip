@@ -261,8 +261,11 @@ void pack_head_mfma(const float* w /*[oc][cin][k]*/, int cin, int oc, int k, uin
 
 typedef _Float16 f16x8v __attribute__((ext_vector_type(8)));
 
-template <int CIN>
-__global__ __launch_bounds__(256) void head_mfma_kernel(const _Float16* __restrict__ x, float* __restrict__ y,
+// OCP: output channels kept in LDS per weight fragment (8 when oc <= 8, else 32): the other lanes of the fragment are
+// zero padding and are not stored, which with the unpadded-weights tile leaves room for three workgroups per CU.
+template <int CIN, int OCP>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCP == 8 ? 3 : 2, OCP == 8 ? 3 : 2)))
+void head_mfma_kernel(const _Float16* __restrict__ x, float* __restrict__ y,
                                                         const uint16_t* __restrict__ wfrag, const float* __restrict__ bias,
                                                         const float* __restrict__ alpha, const float* __restrict__ inv_beta,
                                                         int oc, int k, int r, long long total_rows,
@@ -274,7 +277,7 @@ __global__ __launch_bounds__(256) void head_mfma_kernel(const _Float16* __restri
     constexpr int X_ITERS = (XR_MAX + RPP - 1) / RPP;
     constexpr int KS = CIN / 16;
     __shared__ __attribute__((aligned(16))) _Float16 Xs[XR_MAX * LDX];
-    __shared__ __attribute__((aligned(16))) uint16_t Ws[HM_MAXFRAG * 64 * 8];
+    __shared__ __attribute__((aligned(16))) uint16_t Ws[HM_MAXFRAG * 2 * OCP * 8];       // [fragment][h][channel < OCP][8 halves]
 
     const Slot s = slots[blockIdx.y];
     const int nrows = s.len * r;
@@ -289,17 +292,21 @@ __global__ __launch_bounds__(256) void head_mfma_kernel(const _Float16* __restri
 
     // weights -> LDS once
     {
-        const u32x4* src = reinterpret_cast<const u32x4*>(wfrag);
-        for (int q = tid; q < k * KS * 64; q += 256) reinterpret_cast<u32x4*>(Ws)[q] = src[q];
+        const u32x4* src = reinterpret_cast<const u32x4*>(wfrag);             // [fragment][lane = h * 32 + channel][8 halves]
+        for (int q = tid; q < k * KS * 2 * OCP; q += 256)
+            reinterpret_cast<u32x4*>(Ws)[q] = src[(q / OCP) * 32 + q % OCP];
     }
     float al[8], ib[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) { al[e] = alpha[seg * 8 + e]; ib[e] = inv_beta[seg * 8 + e]; }
-    float b[16];                                           // accumulator register 4g + q of lane (j, h) is output channel 8g + 4h + q
+    // accumulator register 4g + q of lane (j, h) is output channel 8g + 4h + q: with OCP = 8 only g = 0 holds channels
+    constexpr int NB = OCP == 8 ? 4 : 16;
+    float b[NB];
 #pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) b[4 * g + q] = (8 * g + 4 * h + q < oc) ? bias[8 * g + 4 * h + q] : 0.f;
+    for (int q = 0; q < NB; ++q) {
+        const int c = 8 * (q >> 2) + 4 * h + (q & 3);
+        b[q] = (c < oc) ? bias[c] : 0.f;
+    }
 
     // The raw rows of a sub-tile are fetched one sub-tile ahead, so that their latency hides behind the MFMAs and the
     // tanh epilogue of the previous one.  Rows outside the window are out of range of the descriptor and read as
@@ -335,11 +342,12 @@ __global__ __launch_bounds__(256) void head_mfma_kernel(const _Float16* __restri
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-            for (int q = 0; q < 16; ++q) acc[mi][q] = b[q];
+            for (int q = 0; q < 16; ++q) acc[mi][q] = q < NB ? b[q] : 0.f;
         for (int t = 0; t < k; ++t) {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const f16x8v bw = *reinterpret_cast<const f16x8v*>(&Ws[((t * KS + ks) * 64 + lane) * 8]);
+                f16x8v bw = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (j < OCP) bw = *reinterpret_cast<const f16x8v*>(&Ws[(((t * KS + ks) * 2 + h) * OCP + j) * 8]);
 #pragma unroll
                 for (int mi = 0; mi < 2; ++mi) {
                     const f16x8v av = *reinterpret_cast<const f16x8v*>(&Xs[(wave * 64 + mi * 32 + j + t) * LDX + ks * 16 + h * 8]);
@@ -374,8 +382,10 @@ hipError_t launch_head_mfma(const void* x, float* y, const uint16_t* wfrag, cons
     if ((long long)max_len * r * cin * 2 > 0xf0000000ll) return hipErrorInvalidValue;
     const long long rows = (long long)max_int * r;
     dim3 grid((unsigned)((rows + HM_NT * HM_SUB - 1) / (HM_NT * HM_SUB)), (unsigned)n_slots);
-    if (cin == 64) hipLaunchKernelGGL(head_mfma_kernel<64>, grid, dim3(256), 0, stream, (const _Float16*)x, y, wfrag, bias, alpha, inv_beta, oc, k, r, total_rows, slots);
-    else hipLaunchKernelGGL(head_mfma_kernel<32>, grid, dim3(256), 0, stream, (const _Float16*)x, y, wfrag, bias, alpha, inv_beta, oc, k, r, total_rows, slots);
+#define DEMON_HEAD(CIN_, OCP_) hipLaunchKernelGGL((head_mfma_kernel<CIN_, OCP_>), grid, dim3(256), 0, stream, (const _Float16*)x, y, wfrag, bias, alpha, inv_beta, oc, k, r, total_rows, slots)
+    if (cin == 64) { if (oc <= 8) DEMON_HEAD(64, 8); else DEMON_HEAD(64, 32); }
+    else { if (oc <= 8) DEMON_HEAD(32, 8); else DEMON_HEAD(32, 32); }
+#undef DEMON_HEAD
     return hipGetLastError();
 }
 
