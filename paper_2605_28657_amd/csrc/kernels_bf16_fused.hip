@@ -333,8 +333,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
                 v[mo] = acc[mo][ni][gq] + (float)r[mo];
                 o[mo] = (_Float16)v[mo];                         // round to nearest even
             }
-            if constexpr (TM == 2) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, o), rs_y, off, 0, 0);
-            else __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), rs_y, off, 0, 0);
+            if constexpr (TM == 2) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, o), rs_y, off, 0, 2);
+            else __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), rs_y, off, 0, 2);
             if (EMIT) {
                 // the next layer's operand is Snake of the STORED value
                 uint32_t sh[TM / 2];
@@ -344,8 +344,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
                     const float e1 = snake_fast((float)o[mo + 1], a3v[mo + 1], i3v[mo + 1]);
                     sh[mo / 2] = pack_bf16x2(e0, e1);
                 }
-                if constexpr (TM == 2) __builtin_amdgcn_raw_buffer_store_b32(sh[0], rs_a, off, 0, 0);
-                else { const u32x2 s2 = {sh[0], sh[1]}; __builtin_amdgcn_raw_buffer_store_b64(s2, rs_a, off, 0, 0); }
+                if constexpr (TM == 2) __builtin_amdgcn_raw_buffer_store_b32(sh[0], rs_a, off, 0, 2);
+                else { const u32x2 s2 = {sh[0], sh[1]}; __builtin_amdgcn_raw_buffer_store_b64(s2, rs_a, off, 0, 2); }
             }
         }
 }
