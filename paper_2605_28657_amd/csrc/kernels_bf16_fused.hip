@@ -91,7 +91,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const int nrows = s.len * p.r;
     const int out_lo = max(0, s.crop * p.r - p.margin);
     const int out_hi = min(nrows, (s.crop + s.n_int) * p.r + p.margin);
-    const int n0 = out_lo + blockIdx.x * NT;
+    // Workgroups are dealt to the 8 XCDs round-robin by linear id, and each XCD has its own L2: XCD x takes a contiguous
+    // eighth of a window's tiles, in order, so that neighbouring tiles (which share their halo rows) run on the same
+    // XCD at about the same time.  The eighths rotate with the window index (the last one may be short).
+    const int tiles8 = (int)(gridDim.x >> 3);
+    const int tile = (int)((blockIdx.x + blockIdx.y) & 7u) * tiles8 + (int)(blockIdx.x >> 3);
+    const int n0 = out_lo + tile * NT;
     if (n0 >= out_hi) return;
     const long long rowbase = (long long)s.row0 * p.r;
 
@@ -366,12 +371,12 @@ hipError_t launch_res_unit_fused(const FusedArgs& a, hipStream_t stream)
     const bool emit = a.ya != nullptr;
     if (a.c == 64) {
         constexpr int NT = 4 * 32 * 2;
-        dim3 grid((unsigned)((out_rows + NT - 1) / NT), (unsigned)a.n_slots);
+        dim3 grid((unsigned)((out_rows + NT - 1) / NT + 7) / 8 * 8, (unsigned)a.n_slots);       // whole groups of 8 tiles; the surplus exits at once
         if (emit) hipLaunchKernelGGL((res_unit_fused_kernel<64, 2, true>), grid, dim3(256), 0, stream, p);
         else hipLaunchKernelGGL((res_unit_fused_kernel<64, 2, false>), grid, dim3(256), 0, stream, p);
     } else {
         constexpr int NT = 4 * 32 * 1;
-        dim3 grid((unsigned)((out_rows + NT - 1) / NT), (unsigned)a.n_slots);
+        dim3 grid((unsigned)((out_rows + NT - 1) / NT + 7) / 8 * 8, (unsigned)a.n_slots);       // whole groups of 8 tiles; the surplus exits at once
         if (emit) hipLaunchKernelGGL((res_unit_fused_kernel<128, 1, true>), grid, dim3(256), 0, stream, p);
         else hipLaunchKernelGGL((res_unit_fused_kernel<128, 1, false>), grid, dim3(256), 0, stream, p);
     }

@@ -60,7 +60,12 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
     const int nrows = s.len * p.r;
     const int out_lo = max(0, s.crop * p.r - p.margin);
     const int out_hi = min(nrows, (s.crop + s.n_int) * p.r + p.margin);
-    const int n0 = out_lo + blockIdx.x * NT;
+    // Workgroups are dealt to the 8 XCDs round-robin by linear id, and each XCD has its own L2: XCD x takes a contiguous
+    // eighth of a window's tiles, in order, so that neighbouring tiles (which share their halo rows) run on the same
+    // XCD at about the same time.  The eighths rotate with the window index (the last one may be short).
+    const int tiles8 = (int)(gridDim.x >> 3);
+    const int tile = (int)((blockIdx.x + blockIdx.y) & 7u) * tiles8 + (int)(blockIdx.x >> 3);
+    const int n0 = out_lo + tile * NT;
     if (n0 >= out_hi) return;
     const long long rowbase = (long long)s.row0 * p.r;
 
@@ -296,7 +301,7 @@ hipError_t launch_res_unit_wide(const WideArgs& a, hipStream_t stream)
     // one window's activation plane must fit a 32-bit byte offset (buffer descriptors)
     if ((long long)a.max_len * a.r * a.c * 2 > 0xf0000000ll) return hipErrorInvalidValue;
     const long long out_rows = std::min((long long)a.max_int * a.r + 2ll * a.margin, (long long)a.max_len * a.r);
-    dim3 grid((unsigned)((out_rows + W_NT - 1) / W_NT), (unsigned)a.n_slots);
+    dim3 grid((unsigned)((out_rows + W_NT - 1) / W_NT + 7) / 8 * 8, (unsigned)a.n_slots);       // whole groups of 8 tiles; the surplus exits at once
     if (a.ya) hipLaunchKernelGGL((res_unit_wide_kernel<true>), grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL((res_unit_wide_kernel<false>), grid, dim3(256), 0, stream, p);
     return hipGetLastError();
