@@ -21,7 +21,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # measured with rocprofv3 --pmc (see profiles/full_60s_bf16_hbm_traffic.txt); not collectable inside this process
-TRAFFIC_BYTES_PER_STEP = {"full_60s_bf16": 17059053087}
+TRAFFIC_BYTES_PER_STEP = {"full_60s_bf16": 15355420041}
 
 
 def conv_flops_per_frame(spec):
