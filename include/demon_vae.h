@@ -30,7 +30,8 @@
  * accepted (issue the call once before capturing).
  *
  * Environment switches, read once when the library is loaded (A/B timing and
- * tests of the alternative kernels; results stay within the same tolerances):
+ * tests of the alternative kernels; on the benchmark stacks the results stay within
+ * the same tolerances):
  *   DEMON_VAE_WIDE_OPERANDS=bf16x2  bf16 path: levels of 512 channels and more carry the inputs of
  *                                   their transposed and 1x1 convolutions as hi + lo bf16 pairs
  *                                   instead of IEEE half operands
