@@ -187,6 +187,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     // residual values requested after the K loop instead of before it (146 instead of 205 VGPRs).
     constexpr int NBUF = (MT == 128) ? 1 : 2;
     constexpr bool LATE_RES = MT == 128;
+    constexpr bool PF2 = MT == 64 && NT == 64;     // the small-grid tile: weight blocks requested two stages ahead
     constexpr int AS_BYTES = NBUF * MT * LDK * 2, XS_BYTES = NP * XR_MAX * LDK * 2;
     constexpr int SMEM_BYTES = AS_BYTES + XS_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
@@ -249,24 +250,26 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     const unsigned x_voff = ((unsigned)((n0 + minoff + xr0) * p.cin) + seg * 8u) * 2u;    // may wrap "negative": out of range
     const unsigned x_row_step = (unsigned)(RPP * p.cin) * 2u;
 
-    u32x4 ra[A_ITERS];
+    u32x4 ra[A_ITERS], rb[A_ITERS];        // rb: second set, only with PF2
     u32x4 rx[X_ITERS][NP];
 
-    auto load_a = [&](int stage) __attribute__((always_inline)) {
+    auto load_a_to = [&](u32x4 (&r)[A_ITERS], int stage) __attribute__((always_inline)) {
         const unsigned base = w_tile0 + (unsigned)stage * w_blk;
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it)
             if (A_CH % NTH == 0 || tid + it * NTH < A_CH)
-                ra[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, a_voff, base + it * (NTH * 16u), 0);
+                r[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, a_voff, base + it * (NTH * 16u), 0);
     };
-    auto store_a = [&](int buf) __attribute__((always_inline)) {
+    auto store_a_from = [&](const u32x4 (&r)[A_ITERS], int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it) {
             const int q = tid + it * NTH;
             if (A_CH % NTH == 0 || q < A_CH)
-                *reinterpret_cast<u32x4*>(&As[buf][(q / SEGS) * LDK + (q % SEGS) * 8]) = ra[it];
+                *reinterpret_cast<u32x4*>(&As[buf][(q / SEGS) * LDK + (q % SEGS) * 8]) = r[it];
         }
     };
+    auto load_a = [&](int stage) __attribute__((always_inline)) { load_a_to(ra, stage); };
+    auto store_a = [&](int buf) __attribute__((always_inline)) { store_a_from(ra, buf); };
     auto load_x = [&](int chunk) __attribute__((always_inline)) {
         const unsigned coff = x_voff + (unsigned)(chunk * KC) * 2u;
 #pragma unroll
@@ -334,18 +337,12 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     load_a(0);
     load_x(0);
     store_a(0);
+    if (PF2 && nstages > 1) load_a(1);
     store_x();
     __syncthreads();
 
     int chunk = 0, tap = 0;
-    for (int stage = 0; stage < nstages; ++stage) {
-        int ntap = tap + 1, nchunk = chunk;
-        if (ntap == p.ntaps) { ntap = 0; ++nchunk; }
-        const bool more = stage + 1 < nstages;
-        const bool new_chunk = more && nchunk != chunk;
-        if (more) load_a(stage + 1);
-        if (new_chunk) load_x(nchunk);
-
+    auto mma = [&](int stage) __attribute__((always_inline)) {
         const int off = p.tap0 + tap * p.tap_step - minoff;
         const uint16_t* abase = &As[NBUF == 2 ? (stage & 1) : 0][(wm * WTM + j) * LDK + h * 8];
         const int xoff = (wn * WTN + j + off) * LDK + h * 8;
@@ -372,16 +369,51 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
                             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfr[pl][ni]), __builtin_bit_cast(bf16x8, af[mi]), acc[mi][ni], 0, 0, 0);
                     }
         }
-
-        if (more) {
-            if (new_chunk || NBUF == 1) {
-                __syncthreads();              // every wave is done with the old X tile (and the single weight buffer)
-                if (new_chunk) store_x();
+    };
+    if constexpr (PF2) {
+        // Launches with few workgroups (one wave per SIMD, nothing else to hide a load behind): the weight block of
+        // stage s + 2 is requested before stage s is computed, in two register sets that alternate.
+        auto body = [&](int stage, u32x4 (&rn)[A_ITERS], u32x4 (&ri)[A_ITERS]) __attribute__((always_inline)) {
+            int ntap = tap + 1, nchunk = chunk;
+            if (ntap == p.ntaps) { ntap = 0; ++nchunk; }
+            const bool more = stage + 1 < nstages;
+            const bool new_chunk = more && nchunk != chunk;
+            if (stage + 2 < nstages) load_a_to(ri, stage + 2);
+            if (new_chunk) load_x(nchunk);
+            mma(stage);
+            if (more) {
+                if (new_chunk) {
+                    __syncthreads();              // every wave is done with the old X tile
+                    store_x();
+                }
+                store_a_from(rn, (stage + 1) & 1);
+                __syncthreads();
             }
-            store_a(NBUF == 2 ? ((stage + 1) & 1) : 0);
-            __syncthreads();
+            tap = ntap; chunk = nchunk;
+        };
+        for (int stage = 0; stage < nstages; stage += 2) {
+            body(stage, ra, rb);
+            if (stage + 1 < nstages) body(stage + 1, rb, ra);
         }
-        tap = ntap; chunk = nchunk;
+    } else {
+        for (int stage = 0; stage < nstages; ++stage) {
+            int ntap = tap + 1, nchunk = chunk;
+            if (ntap == p.ntaps) { ntap = 0; ++nchunk; }
+            const bool more = stage + 1 < nstages;
+            const bool new_chunk = more && nchunk != chunk;
+            if (more) load_a(stage + 1);
+            if (new_chunk) load_x(nchunk);
+            mma(stage);
+            if (more) {
+                if (new_chunk || NBUF == 1) {
+                    __syncthreads();              // every wave is done with the old X tile (and the single weight buffer)
+                    if (new_chunk) store_x();
+                }
+                store_a(NBUF == 2 ? ((stage + 1) & 1) : 0);
+                __syncthreads();
+            }
+            tap = ntap; chunk = nchunk;
+        }
     }
 
     if (MODE == MODE_RES && LATE_RES) load_res();
