@@ -79,19 +79,4 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, v);
 }
 
-// four consecutive elements starting at element index e of the buffer
-__device__ __forceinline__ float4 hres_load4(__amdgpu_buffer_rsrc_t rs, unsigned e)
-{
-    const u32x2 r = __builtin_amdgcn_raw_buffer_load_b64(rs, e * 2u, 0, 0);
-    const f16x4 hv = __builtin_bit_cast(f16x4, r);
-    return make_float4((float)hv[0], (float)hv[1], (float)hv[2], (float)hv[3]);
-}
-__device__ __forceinline__ void hres_store4(__amdgpu_buffer_rsrc_t rs, unsigned e, float v0, float v1, float v2, float v3)
-{
-    const f16x4 hv = {(_Float16)v0, (_Float16)v1, (_Float16)v2, (_Float16)v3};     // round to nearest even
-    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, hv), rs, e * 2u, 0, 0);
-}
-// the values a later kernel will read back for (v0..v3): what survives the rounding of the store
-__device__ __forceinline__ float hres_round(float v) { return (float)(_Float16)v; }
-
 }  // namespace demon

@@ -166,7 +166,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     constexpr int NTH = 64 * WM * WN;           // threads per workgroup
     constexpr int LDK = KC + 8;                 // padded LDS row (bf16 elements): 16-byte multiple, bank-spread
     // rows of the activation tile: the dilated conv reaches MAXSPAN rows past its NT columns, the 1x1 conv
-    // none and the transposed conv one; a smaller tile lets two workgroups share a CU also with split operands
+    // none and the transposed conv one; a smaller tile lets more workgroups share a CU
     constexpr int XR_MAX = NT + (MODE == MODE_ACT ? MAXSPAN : 8);
     constexpr int WTM = MT / WM, WTN = NT / WN; // tile of one wave
     constexpr int TM = WTM / 32, TN = WTN / 32;

@@ -3,7 +3,7 @@
 // in one kernel, so that the activated branch tensor never goes to HBM.
 //
 // The dilated conv runs as in kernels_bf16.hip (implicit GEMM, rows = output channels, columns = time,
-// weight blocks double-buffered), except that the kernel reads the half-precision residual stream itself and
+// one weight block in LDS, the next waiting in registers), except that the kernel reads the half-precision residual stream itself and
 // applies Snake while staging (cheaper in HBM traffic than a separate bf16 operand at these rates),
 // and that every wave owns ALL C rows of its 32*TN columns.  A lane of a 32x32 MFMA accumulator tile
 // holds column j and rows 8g + 4h + {0..3}; the B operand of the next MFMA wants, for the same column
