@@ -1,5 +1,6 @@
 """Host logic and the C ABI without a GPU: exported symbols, receptive field, window grid, argument errors."""
 import ctypes
+import itertools
 import os
 import re
 
@@ -133,6 +134,56 @@ def test_host_conversion_to_half_rounds_to_nearest_even():
             assert (g & 0x7c00) == 0x7c00 and (g & 0x3ff) != 0
         else:
             assert g == r, (v, hex(g), hex(r))
+
+
+def test_packed_weight_layouts():
+    """The layouts the kernels' comments promise: blocks [row tile][chunk][tap] of MT x KC 16-bit values; with the row
+    permutation, slot mi * 32 + j of every 64-slot block holds GEMM row 2 j + mi (a lane's two slots are consecutive
+    channels); transposed convs in polyphase order; half weights are the bf16-rounded values written as half; the fused
+    units' 1x1 weights with rows (slot (mo, j) = channel j C/32 + mo) and K axis (accumulator row order) permuted."""
+    lib = pa.load_library()
+    pack = lib._ZN5demon9pack_bf16EPKfiiiiibbPt
+    pack.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 5 + [ctypes.c_bool, ctypes.c_bool, ctypes.c_void_p]
+    pack.restype = None
+    bf = lambda a: (di.round_to_bf16(np.asarray(a, dtype=np.float32)).view(np.uint32) >> 16).astype(np.uint16)
+    rng = np.random.default_rng(3)
+    # Conv1d [cout, cin, k], variant 0 (MT 128, KC 64)
+    cout, cin, k = 256, 128, 3
+    w = rng.standard_normal((cout, cin, k)).astype(np.float32)
+    for permute in (False, True):
+        dst = np.zeros(cout * cin * k, dtype=np.uint16)
+        pack(w.ctypes.data, cin, cout, k, 0, 0, False, permute, dst.ctypes.data)
+        blocks = dst.reshape(cout // 128, cin // 64, k, 128, 64)
+        for mt, c, t, slot in itertools.product(range(2), range(2), range(k), (0, 1, 31, 32, 33, 63, 64, 97, 127)):
+            row = mt * 128 + ((slot // 64) * 64 + (slot % 32) * 2 + (slot % 64) // 32 if permute else slot)
+            assert np.array_equal(blocks[mt, c, t, slot], bf(w[row, c * 64:(c + 1) * 64, t])), (permute, mt, c, t, slot)
+    # the same values as half: exact for these magnitudes
+    dsth = np.zeros(cout * cin * k, dtype=np.uint16)
+    pack(w.ctypes.data, cin, cout, k, 0, 0, True, True, dsth.ctypes.data)
+    assert np.array_equal(dsth.view(np.float16).astype(np.float32), (dst.astype(np.uint32) << 16).view(np.float32))
+    # ConvTranspose1d [cin, cout, 2s]: GEMM row mu = phi * cout + o, tap j uses W[i, o, phi + j s]
+    s_, cin, cout = 2, 64, 64
+    wt = rng.standard_normal((cin, cout, 2 * s_)).astype(np.float32)
+    dst = np.zeros(s_ * cout * 2 * cin, dtype=np.uint16)
+    pack(wt.ctypes.data, cin, cout, 2, s_, 0, False, False, dst.ctypes.data)
+    blocks = dst.reshape(1, 1, 2, 128, 64)
+    for j, mu in itertools.product(range(2), (0, 5, 63, 64, 100, 127)):
+        phi, o = divmod(mu, cout)
+        assert np.array_equal(blocks[0, 0, j, mu], bf(wt[:, o, phi + j * s_]))
+    # fused units: W1 [C][C]
+    packw1 = lib._ZN5demon13pack_w1_fusedEPKfiPt
+    packw1.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]; packw1.restype = None
+    for C in (64, 128):
+        w1 = rng.standard_normal((C, C)).astype(np.float32)
+        dst = np.zeros(C * C, dtype=np.uint16)
+        packw1(w1.ctypes.data, C, dst.ctypes.data)
+        got = dst.reshape(C, C)
+        tm = C // 32
+        for slot, kp in itertools.product((0, 1, 31, 32, C - 1), (0, 7, 8, 15, 16, 33, C - 1)):
+            o = (slot % 32) * tm + slot // 32
+            kk, h, e = kp // 16, (kp // 8) % 2, kp % 8
+            ch = 32 * (kk // 2) + 8 * (2 * (kk % 2) + e // 4) + 4 * h + e % 4
+            assert got[slot, kp] == bf(w1[o, ch]), (C, slot, kp)
 
 
 def test_half_conversions_keep_the_fp32_rounding():
