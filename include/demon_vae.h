@@ -38,7 +38,7 @@
  *   DEMON_VAE_NO_FUSED=1            every residual unit as two kernels (no fused units)
  *   DEMON_VAE_ONE_STREAM=1          no internal second stream
  *   DEMON_VAE_SMALL_TILE_WGS=n      launches of at most n 128 x 128 tiles use 64 x 64 tiles
- *                                   (default 256, 0 = never; bit-identical results)
+ *                                   (default 192, 0 = never; bit-identical results)
  */
 #ifndef DEMON_VAE_H
 #define DEMON_VAE_H

@@ -507,7 +507,7 @@ static hipError_t launch_variant(const MfmaParams& p, int mode, int in_fmt, int 
 // the results are bit-identical to the large tile's.  DEMON_VAE_SMALL_TILE_WGS overrides the threshold (0: never).
 static const long long g_small_tile_wgs = [] {
     const char* e = getenv("DEMON_VAE_SMALL_TILE_WGS");
-    return e ? atoll(e) : 256ll;
+    return e ? atoll(e) : 192ll;
 }();
 
 hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
