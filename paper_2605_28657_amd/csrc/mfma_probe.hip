@@ -8,6 +8,8 @@
 //     mode 1: operands re-read from LDS for every MFMA group (the fragment reads of a 64 x 64 wave tile)
 //     mode 2: the whole stage loop of a 128 x 128 x 64 tile: weight block global -> registers -> LDS, one
 //             barrier per stage, fragment reads, MFMAs
+//     mode 3: as mode 0 with the 16 x 16 x 32 MFMA shape (same FLOP count per wave)
+//     mode 4: as mode 2 with the 16 x 16 x 32 MFMA shape (a 64 x 64 wave tile as 4 x 4 tiles)
 //     random 0: constant operands (little switching activity); 1: pseudo-random bf16 values of magnitude ~1
 //
 // Prints the rate of the first launch and the rate sustained over <seconds> of back-to-back launches; read the
@@ -19,6 +21,7 @@
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 #define CK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { fprintf(stderr, "HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); return 1; } } while (0)
@@ -35,7 +38,7 @@ __device__ __forceinline__ uint16_t hash_bf16(unsigned x)
     return (uint16_t)((x & 0x807fu) | (0x3f00u + ((x >> 20) & 0x0080u)));
 }
 
-template <int MODE, int RANDOM>
+template <int MODE, int RANDOM, bool S16 = false>
 __global__ __launch_bounds__(NTH) void probe_kernel(const uint16_t* w, float* out, int nstages, unsigned wbytes)
 {
     __shared__ __attribute__((aligned(16))) uint16_t As[2][MT * LDK];
@@ -63,6 +66,23 @@ __global__ __launch_bounds__(NTH) void probe_kernel(const uint16_t* w, float* ou
         const int off = (stage % 7) * 9;                     // tap offsets of a dilation-9 convolution
         const uint16_t* abase = &As[stage & 1][(wm * WTM + j) * LDK + h * 8];
         const int xoff = (wn * WTN + j + off) * LDK + h * 8;
+        if constexpr (S16) {
+            const int l16 = lane & 15, g4 = lane >> 4;
+            f32x4* acc4 = reinterpret_cast<f32x4*>(&acc[0][0]);        // 16 tiles of 16 x 16
+#pragma unroll
+            for (int ks = 0; ks < KC / 32; ++ks) {
+                bf16x8 a4[4], b4[4];
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi) a4[mi] = *reinterpret_cast<const bf16x8*>(&As[stage & 1][(wm * WTM + mi * 16 + l16) * LDK + ks * 32 + g4 * 8]);
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni) b4[ni] = *reinterpret_cast<const bf16x8*>(&Xs[(wn * WTN + ni * 16 + l16 + off) * LDK + ks * 32 + g4 * 8]);
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < 4; ++ni)
+                        acc4[mi * 4 + ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a4[mi], b4[ni], acc4[mi * 4 + ni], 0, 0, 0);
+            }
+        } else
 #pragma unroll
         for (int ks = 0; ks < KC / 16; ++ks) {
             if (MODE >= 1) {
@@ -91,6 +111,36 @@ __global__ __launch_bounds__(NTH) void probe_kernel(const uint16_t* w, float* ou
     out[blockIdx.x * NTH + tid] = s;
 }
 
+// mode 3: 16 x 16 x 32 MFMAs on register operands; per stage the same 16 x 32768 FLOP per wave as modes 0-2
+template <int RANDOM>
+__global__ __launch_bounds__(NTH) void probe16_kernel(float* out, int nstages)
+{
+    const int tid = threadIdx.x;
+    f32x4 acc[16];
+    for (int a = 0; a < 16; ++a) for (int r = 0; r < 4; ++r) acc[a][r] = 0.f;
+    bf16x8 af[4], bfr[4];
+    for (int i = 0; i < 4; ++i) {
+        uint16_t va[8], vb[8];
+        for (int e = 0; e < 8; ++e) {
+            va[e] = RANDOM ? hash_bf16((tid * 8 + e) * 2654435761u + i * 977u + blockIdx.x) : (uint16_t)0x3c00;
+            vb[e] = RANDOM ? hash_bf16((tid * 8 + e) * 40503u + i * 131u + 7u * blockIdx.x + 12345u) : (uint16_t)0x3c00;
+        }
+        __builtin_memcpy(&af[i], va, 16); __builtin_memcpy(&bfr[i], vb, 16);
+    }
+    for (int stage = 0; stage < nstages; ++stage) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)               // 2 x 16 MFMAs of 16 x 16 x 32 = 16 MFMAs of 32 x 32 x 16 in FLOP
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni)
+                    acc[mi * 4 + ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[mi], bfr[ni], acc[mi * 4 + ni], 0, 0, 0);
+    }
+    float s = 0;
+    for (int a = 0; a < 16; ++a) for (int r = 0; r < 4; ++r) s += acc[a][r];
+    out[blockIdx.x * NTH + tid] = s;
+}
+
 template <int MODE, int RANDOM>
 static int run(const uint16_t* w, float* out, unsigned wbytes, double seconds)
 {
@@ -98,16 +148,20 @@ static int run(const uint16_t* w, float* out, unsigned wbytes, double seconds)
     const double flop = (double)nwg * nstages * MT * NT * KC * 2.0;
     hipEvent_t e0, e1;
     CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
-    hipLaunchKernelGGL((probe_kernel<MODE, RANDOM>), dim3(nwg), dim3(NTH), 0, 0, w, out, nstages, wbytes);   // code load
+    auto launch = [&]() {
+        if (MODE == 3) hipLaunchKernelGGL((probe16_kernel<RANDOM>), dim3(nwg), dim3(NTH), 0, 0, out, nstages);
+        else if (MODE == 4) hipLaunchKernelGGL((probe_kernel<2, RANDOM, true>), dim3(nwg), dim3(NTH), 0, 0, w, out, nstages, wbytes);
+        else hipLaunchKernelGGL((probe_kernel<(MODE >= 3 ? 0 : MODE), RANDOM>), dim3(nwg), dim3(NTH), 0, 0, w, out, nstages, wbytes);
+    };
+    launch();   // code load
     CK(hipDeviceSynchronize());
     CK(hipEventRecord(e0));
-    hipLaunchKernelGGL((probe_kernel<MODE, RANDOM>), dim3(nwg), dim3(NTH), 0, 0, w, out, nstages, wbytes);
+    launch();
     CK(hipEventRecord(e1)); CK(hipDeviceSynchronize());
     float first_ms; CK(hipEventElapsedTime(&first_ms, e0, e1));
     const int reps = (int)(seconds * 1e3 / first_ms) + 1;
     CK(hipEventRecord(e0));
-    for (int r = 0; r < reps; ++r)
-        hipLaunchKernelGGL((probe_kernel<MODE, RANDOM>), dim3(nwg), dim3(NTH), 0, 0, w, out, nstages, wbytes);
+    for (int r = 0; r < reps; ++r) launch();
     CK(hipEventRecord(e1)); CK(hipDeviceSynchronize());
     float total_ms; CK(hipEventElapsedTime(&total_ms, e0, e1));
     printf("mode %d random %d: first launch %.0f TFLOP/s; %d launches in %.0f ms: sustained %.0f TFLOP/s\n",
@@ -121,8 +175,8 @@ int main(int argc, char** argv)
     const int mode = argc > 1 ? atoi(argv[1]) : 0;
     const double seconds = argc > 2 ? atof(argv[2]) : 3.0;
     const int random = argc > 3 ? atoi(argv[3]) : 1;
-    if (mode < 0 || mode > 2 || seconds <= 0 || seconds > 30) {
-        fprintf(stderr, "usage: mfma_probe <mode 0|1|2> <seconds (0, 30]> <random 0|1>\n");
+    if (mode < 0 || mode > 4 || seconds <= 0 || seconds > 30) {
+        fprintf(stderr, "usage: mfma_probe <mode 0|1|2|3|4> <seconds (0, 30]> <random 0|1>\n");
         return 2;
     }
     const unsigned wbytes = (unsigned)N_TILES * STAGES_PER_TILE * MT * KC * 2;
@@ -137,8 +191,8 @@ int main(int argc, char** argv)
     CK(hipMemcpy(w, hw, wbytes, hipMemcpyHostToDevice));
     free(hw);
     int rc;
-    if (random) rc = mode == 0 ? run<0, 1>(w, out, wbytes, seconds) : mode == 1 ? run<1, 1>(w, out, wbytes, seconds) : run<2, 1>(w, out, wbytes, seconds);
-    else rc = mode == 0 ? run<0, 0>(w, out, wbytes, seconds) : mode == 1 ? run<1, 0>(w, out, wbytes, seconds) : run<2, 0>(w, out, wbytes, seconds);
+    if (random) rc = mode == 0 ? run<0, 1>(w, out, wbytes, seconds) : mode == 1 ? run<1, 1>(w, out, wbytes, seconds) : mode == 2 ? run<2, 1>(w, out, wbytes, seconds) : mode == 3 ? run<3, 1>(w, out, wbytes, seconds) : run<4, 1>(w, out, wbytes, seconds);
+    else rc = mode == 0 ? run<0, 0>(w, out, wbytes, seconds) : mode == 1 ? run<1, 0>(w, out, wbytes, seconds) : mode == 2 ? run<2, 0>(w, out, wbytes, seconds) : mode == 3 ? run<3, 0>(w, out, wbytes, seconds) : run<4, 0>(w, out, wbytes, seconds);
     CK(hipFree(w)); CK(hipFree(out));
     return rc;
 }
