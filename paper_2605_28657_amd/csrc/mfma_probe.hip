@@ -10,6 +10,7 @@
 //             barrier per stage, fragment reads, MFMAs
 //     mode 3: as mode 0 with the 16 x 16 x 32 MFMA shape (same FLOP count per wave)
 //     mode 4: as mode 2 with the 16 x 16 x 32 MFMA shape (a 64 x 64 wave tile as 4 x 4 tiles)
+//     mode 5: as mode 2 with one weight buffer in LDS and two barriers per stage (46 KB: three workgroups per CU)
 //     random 0: constant operands (little switching activity); 1: pseudo-random bf16 values of magnitude ~1
 //
 // Prints the rate of the first launch and the rate sustained over <seconds> of back-to-back launches; read the
@@ -38,13 +39,13 @@ __device__ __forceinline__ uint16_t hash_bf16(unsigned x)
     return (uint16_t)((x & 0x807fu) | (0x3f00u + ((x >> 20) & 0x0080u)));
 }
 
-template <int MODE, int RANDOM, bool S16 = false>
+template <int MODE, int RANDOM, bool S16 = false, int NB = 2>
 __global__ __launch_bounds__(NTH) void probe_kernel(const uint16_t* w, float* out, int nstages, unsigned wbytes)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][MT * LDK];
+    __shared__ __attribute__((aligned(16))) uint16_t As[NB][MT * LDK];
     __shared__ __attribute__((aligned(16))) uint16_t Xs[XR * LDK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WN, wn = wave % WN, j = lane & 31, h = lane >> 5;
-    for (int i = tid; i < 2 * MT * LDK; i += NTH)
+    for (int i = tid; i < NB * MT * LDK; i += NTH)
         (&As[0][0])[i] = RANDOM ? hash_bf16(i * 2654435761u + blockIdx.x) : (uint16_t)0x3c00;
     for (int i = tid; i < XR * LDK; i += NTH)
         Xs[i] = RANDOM ? hash_bf16(i * 40503u + 7u * blockIdx.x + 12345u) : (uint16_t)0x3c00;
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(NTH) void probe_kernel(const uint16_t* w, float* ou
             for (int it = 0; it < A_ITERS; ++it) ra[it] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, tid * 16u, base + it * (NTH * 16u), 0);
         }
         const int off = (stage % 7) * 9;                     // tap offsets of a dilation-9 convolution
-        const uint16_t* abase = &As[stage & 1][(wm * WTM + j) * LDK + h * 8];
+        const uint16_t* abase = &As[stage & (NB - 1)][(wm * WTM + j) * LDK + h * 8];
         const int xoff = (wn * WTN + j + off) * LDK + h * 8;
         if constexpr (S16) {
             const int l16 = lane & 15, g4 = lane >> 4;
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(NTH) void probe_kernel(const uint16_t* w, float* ou
             for (int ks = 0; ks < KC / 32; ++ks) {
                 bf16x8 a4[4], b4[4];
 #pragma unroll
-                for (int mi = 0; mi < 4; ++mi) a4[mi] = *reinterpret_cast<const bf16x8*>(&As[stage & 1][(wm * WTM + mi * 16 + l16) * LDK + ks * 32 + g4 * 8]);
+                for (int mi = 0; mi < 4; ++mi) a4[mi] = *reinterpret_cast<const bf16x8*>(&As[stage & (NB - 1)][(wm * WTM + mi * 16 + l16) * LDK + ks * 32 + g4 * 8]);
 #pragma unroll
                 for (int ni = 0; ni < 4; ++ni) b4[ni] = *reinterpret_cast<const bf16x8*>(&Xs[(wn * WTN + ni * 16 + l16 + off) * LDK + ks * 32 + g4 * 8]);
 #pragma unroll
@@ -98,10 +99,11 @@ __global__ __launch_bounds__(NTH) void probe_kernel(const uint16_t* w, float* ou
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
         }
         if (MODE == 2) {
+            if (NB == 1) __syncthreads();                     // every wave is done with the single weight buffer
 #pragma unroll
             for (int it = 0; it < A_ITERS; ++it) {
                 const int q = tid + it * NTH;
-                *reinterpret_cast<u32x4*>(&As[(stage + 1) & 1][(q / SEGS) * LDK + (q % SEGS) * 8]) = ra[it];
+                *reinterpret_cast<u32x4*>(&As[(stage + 1) & (NB - 1)][(q / SEGS) * LDK + (q % SEGS) * 8]) = ra[it];
             }
             __syncthreads();
         }
@@ -151,6 +153,7 @@ static int run(const uint16_t* w, float* out, unsigned wbytes, double seconds)
     auto launch = [&]() {
         if (MODE == 3) hipLaunchKernelGGL((probe16_kernel<RANDOM>), dim3(nwg), dim3(NTH), 0, 0, out, nstages);
         else if (MODE == 4) hipLaunchKernelGGL((probe_kernel<2, RANDOM, true>), dim3(nwg), dim3(NTH), 0, 0, w, out, nstages, wbytes);
+        else if (MODE == 5) hipLaunchKernelGGL((probe_kernel<2, RANDOM, false, 1>), dim3(nwg), dim3(NTH), 0, 0, w, out, nstages, wbytes);
         else hipLaunchKernelGGL((probe_kernel<(MODE >= 3 ? 0 : MODE), RANDOM>), dim3(nwg), dim3(NTH), 0, 0, w, out, nstages, wbytes);
     };
     launch();   // code load
@@ -175,8 +178,8 @@ int main(int argc, char** argv)
     const int mode = argc > 1 ? atoi(argv[1]) : 0;
     const double seconds = argc > 2 ? atof(argv[2]) : 3.0;
     const int random = argc > 3 ? atoi(argv[3]) : 1;
-    if (mode < 0 || mode > 4 || seconds <= 0 || seconds > 30) {
-        fprintf(stderr, "usage: mfma_probe <mode 0|1|2|3|4> <seconds (0, 30]> <random 0|1>\n");
+    if (mode < 0 || mode > 5 || seconds <= 0 || seconds > 30) {
+        fprintf(stderr, "usage: mfma_probe <mode 0|1|2|3|4|5> <seconds (0, 30]> <random 0|1>\n");
         return 2;
     }
     const unsigned wbytes = (unsigned)N_TILES * STAGES_PER_TILE * MT * KC * 2;
@@ -191,8 +194,8 @@ int main(int argc, char** argv)
     CK(hipMemcpy(w, hw, wbytes, hipMemcpyHostToDevice));
     free(hw);
     int rc;
-    if (random) rc = mode == 0 ? run<0, 1>(w, out, wbytes, seconds) : mode == 1 ? run<1, 1>(w, out, wbytes, seconds) : mode == 2 ? run<2, 1>(w, out, wbytes, seconds) : mode == 3 ? run<3, 1>(w, out, wbytes, seconds) : run<4, 1>(w, out, wbytes, seconds);
-    else rc = mode == 0 ? run<0, 0>(w, out, wbytes, seconds) : mode == 1 ? run<1, 0>(w, out, wbytes, seconds) : mode == 2 ? run<2, 0>(w, out, wbytes, seconds) : mode == 3 ? run<3, 0>(w, out, wbytes, seconds) : run<4, 0>(w, out, wbytes, seconds);
+    if (random) rc = mode == 0 ? run<0, 1>(w, out, wbytes, seconds) : mode == 1 ? run<1, 1>(w, out, wbytes, seconds) : mode == 2 ? run<2, 1>(w, out, wbytes, seconds) : mode == 3 ? run<3, 1>(w, out, wbytes, seconds) : mode == 4 ? run<4, 1>(w, out, wbytes, seconds) : run<5, 1>(w, out, wbytes, seconds);
+    else rc = mode == 0 ? run<0, 0>(w, out, wbytes, seconds) : mode == 1 ? run<1, 0>(w, out, wbytes, seconds) : mode == 2 ? run<2, 0>(w, out, wbytes, seconds) : mode == 3 ? run<3, 0>(w, out, wbytes, seconds) : mode == 4 ? run<4, 0>(w, out, wbytes, seconds) : run<5, 0>(w, out, wbytes, seconds);
     CK(hipFree(w)); CK(hipFree(out));
     return rc;
 }
