@@ -11,6 +11,8 @@
 //     mode 3: as mode 0 with the 16 x 16 x 32 MFMA shape (same FLOP count per wave)
 //     mode 4: as mode 2 with the 16 x 16 x 32 MFMA shape (a 64 x 64 wave tile as 4 x 4 tiles)
 //     mode 5: as mode 2 with one weight buffer in LDS and two barriers per stage (46 KB: three workgroups per CU)
+//     mode 6: weight fragments straight from global memory into registers (fragment-major weights, two register sets),
+//             activation fragments from LDS; no barrier in the stage loop
 //     random 0: constant operands (little switching activity); 1: pseudo-random bf16 values of magnitude ~1
 //
 // Prints the rate of the first launch and the rate sustained over <seconds> of back-to-back launches; read the
@@ -113,6 +115,57 @@ __global__ __launch_bounds__(NTH) void probe_kernel(const uint16_t* w, float* ou
     out[blockIdx.x * NTH + tid] = s;
 }
 
+// mode 6
+template <int RANDOM>
+__global__ __launch_bounds__(NTH) void probe_direct_kernel(const uint16_t* w, float* out, int nstages, unsigned wbytes)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[XR * LDK];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WN, wn = wave % WN, j = lane & 31, h = lane >> 5;
+    for (int i = tid; i < XR * LDK; i += NTH)
+        Xs[i] = RANDOM ? hash_bf16(i * 40503u + 7u * blockIdx.x + 12345u) : (uint16_t)0x3c00;
+    __syncthreads();
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(w), 0, (int)wbytes, 0x00020000);
+    f32x16 acc[TM][TN];
+    for (int a = 0; a < TM; ++a) for (int b = 0; b < TN; ++b) for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    const unsigned tile0 = (blockIdx.x % N_TILES) * STAGES_PER_TILE * (A_CH * 16u);
+    // a stage's 16 KB block holds 16 fragments of 1 KB: (wm, mi, ks); lane l reads its 16 bytes of each
+    const unsigned voff = (unsigned)(wm * TM * (KC / 16)) * 1024u + lane * 16u;
+    u32x4 fa[KC / 16][TM], fb[KC / 16][TM];
+    auto load_frags = [&](u32x4 (&f)[KC / 16][TM], int stage) __attribute__((always_inline)) {
+        const unsigned base = tile0 + (unsigned)(stage % STAGES_PER_TILE) * (A_CH * 16u);
+#pragma unroll
+        for (int ks = 0; ks < KC / 16; ++ks)
+#pragma unroll
+            for (int mi = 0; mi < TM; ++mi)
+                f[ks][mi] = __builtin_amdgcn_raw_buffer_load_b128(rs_w, voff, base + (unsigned)(mi * (KC / 16) + ks) * 1024u, 0);
+    };
+    auto compute = [&](const u32x4 (&f)[KC / 16][TM], int stage) __attribute__((always_inline)) {
+        const int off = (stage % 7) * 9;
+        const int xoff = (wn * WTN + j + off) * LDK + h * 8;
+#pragma unroll
+        for (int ks = 0; ks < KC / 16; ++ks) {
+            bf16x8 bfr[TN];
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) bfr[ni] = *reinterpret_cast<const bf16x8*>(&Xs[xoff + ni * 32 * LDK + ks * 16]);
+#pragma unroll
+            for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < TN; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f[ks][mi]), bfr[ni], acc[mi][ni], 0, 0, 0);
+        }
+    };
+    load_frags(fa, 0);
+    for (int stage = 0; stage < nstages; stage += 2) {
+        load_frags(fb, stage + 1);
+        compute(fa, stage);
+        load_frags(fa, stage + 2);
+        compute(fb, stage + 1);
+    }
+    float s = 0;
+    for (int a = 0; a < TM; ++a) for (int b = 0; b < TN; ++b) for (int r = 0; r < 16; ++r) s += acc[a][b][r];
+    out[blockIdx.x * NTH + tid] = s;
+}
+
 // mode 3: 16 x 16 x 32 MFMAs on register operands; per stage the same 16 x 32768 FLOP per wave as modes 0-2
 template <int RANDOM>
 __global__ __launch_bounds__(NTH) void probe16_kernel(float* out, int nstages)
@@ -153,6 +206,7 @@ static int run(const uint16_t* w, float* out, unsigned wbytes, double seconds)
     auto launch = [&]() {
         if (MODE == 3) hipLaunchKernelGGL((probe16_kernel<RANDOM>), dim3(nwg), dim3(NTH), 0, 0, out, nstages);
         else if (MODE == 4) hipLaunchKernelGGL((probe_kernel<2, RANDOM, true>), dim3(nwg), dim3(NTH), 0, 0, w, out, nstages, wbytes);
+        else if (MODE == 6) hipLaunchKernelGGL((probe_direct_kernel<RANDOM>), dim3(nwg), dim3(NTH), 0, 0, w, out, nstages, wbytes);
         else if (MODE == 5) hipLaunchKernelGGL((probe_kernel<2, RANDOM, false, 1>), dim3(nwg), dim3(NTH), 0, 0, w, out, nstages, wbytes);
         else hipLaunchKernelGGL((probe_kernel<(MODE >= 3 ? 0 : MODE), RANDOM>), dim3(nwg), dim3(NTH), 0, 0, w, out, nstages, wbytes);
     };
@@ -178,8 +232,8 @@ int main(int argc, char** argv)
     const int mode = argc > 1 ? atoi(argv[1]) : 0;
     const double seconds = argc > 2 ? atof(argv[2]) : 3.0;
     const int random = argc > 3 ? atoi(argv[3]) : 1;
-    if (mode < 0 || mode > 5 || seconds <= 0 || seconds > 30) {
-        fprintf(stderr, "usage: mfma_probe <mode 0|1|2|3|4|5> <seconds (0, 30]> <random 0|1>\n");
+    if (mode < 0 || mode > 6 || seconds <= 0 || seconds > 30) {
+        fprintf(stderr, "usage: mfma_probe <mode 0|1|2|3|4|5|6> <seconds (0, 30]> <random 0|1>\n");
         return 2;
     }
     const unsigned wbytes = (unsigned)N_TILES * STAGES_PER_TILE * MT * KC * 2;
@@ -194,8 +248,8 @@ int main(int argc, char** argv)
     CK(hipMemcpy(w, hw, wbytes, hipMemcpyHostToDevice));
     free(hw);
     int rc;
-    if (random) rc = mode == 0 ? run<0, 1>(w, out, wbytes, seconds) : mode == 1 ? run<1, 1>(w, out, wbytes, seconds) : mode == 2 ? run<2, 1>(w, out, wbytes, seconds) : mode == 3 ? run<3, 1>(w, out, wbytes, seconds) : mode == 4 ? run<4, 1>(w, out, wbytes, seconds) : run<5, 1>(w, out, wbytes, seconds);
-    else rc = mode == 0 ? run<0, 0>(w, out, wbytes, seconds) : mode == 1 ? run<1, 0>(w, out, wbytes, seconds) : mode == 2 ? run<2, 0>(w, out, wbytes, seconds) : mode == 3 ? run<3, 0>(w, out, wbytes, seconds) : mode == 4 ? run<4, 0>(w, out, wbytes, seconds) : run<5, 0>(w, out, wbytes, seconds);
+    if (random) rc = mode == 0 ? run<0, 1>(w, out, wbytes, seconds) : mode == 1 ? run<1, 1>(w, out, wbytes, seconds) : mode == 2 ? run<2, 1>(w, out, wbytes, seconds) : mode == 3 ? run<3, 1>(w, out, wbytes, seconds) : mode == 4 ? run<4, 1>(w, out, wbytes, seconds) : mode == 5 ? run<5, 1>(w, out, wbytes, seconds) : run<6, 1>(w, out, wbytes, seconds);
+    else rc = mode == 0 ? run<0, 0>(w, out, wbytes, seconds) : mode == 1 ? run<1, 0>(w, out, wbytes, seconds) : mode == 2 ? run<2, 0>(w, out, wbytes, seconds) : mode == 3 ? run<3, 0>(w, out, wbytes, seconds) : mode == 4 ? run<4, 0>(w, out, wbytes, seconds) : mode == 5 ? run<5, 0>(w, out, wbytes, seconds) : run<6, 0>(w, out, wbytes, seconds);
     CK(hipFree(w)); CK(hipFree(out));
     return rc;
 }
