@@ -218,6 +218,26 @@ demon_status demon_vae_decode_windowed_gated(demon_vae* vae, const void* d_laten
                                              const int* d_skip, float* d_out, void* stream);
 
 /*
+ * For callers that cannot allocate device memory or may not let a library hold a workspace of its own choosing --
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc: demon_vae_decode_windowed with
+ * everything the call needs besides its inputs and outputs (window table, activation buffers, window waveforms) in
+ * a static device array of DEMON_VAE_STATIC_SCRATCH_BYTES that is part of the library's image.  Each GPU the library
+ * runs on holds its own copy until the process ends.  The call allocates nothing, copies nothing from the host (a
+ * kernel writes the window table) and runs on the given stream only; it can be captured without a preceding call.
+ * Same arguments, layouts, results (bit for bit) and INVALID_ARG cases as demon_vae_decode_windowed; max_frames,
+ * max_clips and max_extended_frames of the handle do not apply.  WORKSPACE: more than 4096 windows, or extended
+ * windows whose buffers exceed the array (the message states the bytes needed; for the x1920 benchmark stack about
+ * 1.2 MB per extended latent frame, i.e. about 100 frames: one 3 s playback window with its halos).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU -- from different streams,
+ * threads or handles -- race.  The array keeps the previous call's contents; nothing in it needs clearing (whatever
+ * a call reads of it and has not written itself only reaches results that are dropped).
+ */
+#define DEMON_VAE_STATIC_SCRATCH_BYTES ((size_t)128 << 20)
+demon_status demon_vae_decode_windowed_static(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
+                                              int frame_begin, int frame_end, int window, int halo,
+                                              float* d_out, void* stream);
+
+/*
  * Equal-power crossfade of a chunk boundary of the playback stream (the paper crossfades each
  * decoded chunk into the output stream and names a 50 ms equal-power fade, 2400 samples at 48 kHz):
  *   d_out[c][i] = cos(t_i) * d_prev_tail[c][i] + sin(t_i) * d_next_head[c][i],  t_i = (pi/2)(i + 1/2)/n_samples

@@ -1,6 +1,7 @@
 """MI355X-native windowed VAE decode (paper section 3.6): ctypes binding over libdemon_vae.so."""
 from .binding import (DemonVAE, DemonError, load_library, demon_vae_create, demon_vae_destroy,  # noqa: F401
                       demon_vae_decode, demon_vae_decode_windowed, demon_vae_decode_windowed_pcm16, demon_vae_decode_windowed_gated,
+                      demon_vae_decode_windowed_static,
                       demon_vae_receptive_field,
                       demon_vae_rf_from_config, demon_vae_forward_support, demon_vae_plan_windows,
                       demon_vae_weight_count, demon_vae_debug_tap, demon_vae_last_error,

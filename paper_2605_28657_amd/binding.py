@@ -66,6 +66,7 @@ def load_library() -> ctypes.CDLL:
     lib.demon_vae_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     lib.demon_vae_decode_windowed.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 6 + [ctypes.c_void_p, ctypes.c_void_p]
     lib.demon_vae_decode_windowed_pcm16.argtypes = lib.demon_vae_decode_windowed.argtypes
+    lib.demon_vae_decode_windowed_static.argtypes = lib.demon_vae_decode_windowed.argtypes
     lib.demon_vae_decode_windowed_gated.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 6 + [ctypes.c_void_p] * 3
     lib.demon_vae_latent_similarity.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_int,
                                                 ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -170,6 +171,12 @@ def demon_vae_decode_windowed(handle: int, d_latent: int, n_clips: int, n_frames
                               frame_end: int, window: int, halo: int, d_out: int, stream: int = 0):
     _check(load_library().demon_vae_decode_windowed(handle, d_latent, n_clips, n_frames, frame_begin, frame_end,
                                                     window, halo, d_out, stream))
+
+
+def demon_vae_decode_windowed_static(handle: int, d_latent: int, n_clips: int, n_frames: int, frame_begin: int,
+                                     frame_end: int, window: int, halo: int, d_out: int, stream: int = 0):
+    _check(load_library().demon_vae_decode_windowed_static(handle, d_latent, n_clips, n_frames, frame_begin, frame_end,
+                                                           window, halo, d_out, stream))
 
 
 def demon_vae_decode_windowed_pcm16(handle: int, d_latent: int, n_clips: int, n_frames: int, frame_begin: int,
@@ -305,6 +312,16 @@ class DemonVAE:
             frame_end = t
         demon_vae_decode_windowed(self.handle, latent.data_ptr(), n_clips, t, frame_begin, frame_end, window, halo,
                                   out.data_ptr(), stream)
+        return out
+
+    def decode_windowed_static(self, latent, window: int, halo: int = -1, frame_begin: int = 0,
+                               frame_end: Optional[int] = None, out=None):
+        """The windowed decode in the library's static scratch array (allocates nothing); `out` should be given."""
+        latent, out, n_clips, t, stream = self._prep(latent, out)
+        if frame_end is None:
+            frame_end = t
+        demon_vae_decode_windowed_static(self.handle, latent.data_ptr(), n_clips, t, frame_begin, frame_end, window, halo,
+                                         out.data_ptr(), stream)
         return out
 
     def decode_windowed_gated(self, latent, skip, out, window: int, halo: int = -1, frame_begin: int = 0,

@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <memory>
+#include <mutex>
 #include <new>
 
 #include "internal.h"
@@ -66,6 +67,39 @@ struct Plan {
     unsigned long long last_use = 0;
 };
 
+// The device memory a decode call works in besides its inputs and outputs: the handle's own (allocated at create) or,
+// for demon_vae_decode_windowed_static, pieces of the static scratch array below.
+struct Workspace {
+    void* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    float* head_out = nullptr;
+    Slot* slot_gated = nullptr;
+    size_t act_elems = 0;              // elements one activation buffer holds (= offset of the lo plane of a split operand)
+};
+
+// Scratch of demon_vae_decode_windowed_static, the entry point for callers that cannot allocate: window table, activation
+// buffers and window waveforms of one call.  Every GPU the library runs on holds its own copy until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress: kernels get the address looked up there.
+constexpr size_t kStaticScratchBytes = DEMON_VAE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};      // per device: address of its copy of `scratch`
+std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of the static scratch array (looked up once per device).
+hipError_t static_scratch(int device, unsigned char** out)
+{
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[device] = static_cast<unsigned char*>(ptr);
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
 }  // namespace
 
 struct demon_vae {
@@ -73,10 +107,10 @@ struct demon_vae {
     demon_dtype dtype = DEMON_F32;
     int max_frames = 0, max_clips = 0;
     long long cap_frames = 0;
-    size_t act_elems = 0;              // elements one activation buffer holds
     long long per_frame = 0;           // largest rate x width of a layer: elements of one latent frame at its widest
     int rf_left = 0, rf_right = 0;
     int device = 0;
+    bool has_split_operands = false;   // bf16 path: some layer carries its operand as hi + lo planes
 
     void* d_params = nullptr;          // one allocation: all packed weights, biases, Snake parameters
     std::vector<Block> blocks;
@@ -88,10 +122,11 @@ struct demon_vae {
     // fp32 path: residual stream ping/pong + Snake scratch, all fp32.
     // bf16 path: buf[0], buf[1] residual stream ping/pong (half), buf[2] bf16 activated branch tensor,
     // buf[3], buf[4] bf16 activated operand of the next layer (each bf16 buffer: hi plane + lo plane).
-    void* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
-    float* head_out = nullptr;                     // planar window waveforms [out_channels, cap_frames*S]
+    // head_out: planar window waveforms [out_channels, cap_frames*S]; slot_gated: per-call copy of a window table with
+    // the skipped clips emptied (gated decode)
+    Workspace ws;
+    unsigned char* scratch = nullptr;              // this device's copy of the static scratch array
     Slot* d_slot_arena = nullptr;
-    Slot* d_slot_gated = nullptr;                  // per-call copy of a window table with the skipped clips emptied (gated decode)
     hipStream_t stream2 = nullptr;                 // second lane of the bf16 layer sequence (default priority, non-blocking)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     Slot* h_slot_stage = nullptr;                  // pinned staging of the window tables, one region per cached plan
@@ -259,21 +294,24 @@ demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, i
 
 #define HIP_TRY(expr, what) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_fail(e_, what); } while (0)
 
-demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_frames, int fb, int fe,
-                        int window, int halo, const int* d_skip, float* d_out, int16_t* d_pcm, hipStream_t stream)
+// two window groups on two streams unless a mode wants one ordered launch sequence (per-launch timing, debug tap)
+bool wants_two_groups(const demon_vae* v)
 {
-    Plan* plan = nullptr;
+    return v->dtype == DEMON_BF16 && v->stream2 && v->timing < 2 && !(v->tap_layer >= 0 && v->tap_dst);
+}
+
+// The launch sequence of one decode call over the windows of `plan`, in the memory of `ws`.
+demon_status run_decode(demon_vae* v, const Workspace& ws, const Plan* plan, const void* d_latent, int n_frames,
+                        const int* d_skip, float* d_out, int16_t* d_pcm, hipStream_t stream)
+{
     const bool bf = v->dtype == DEMON_BF16;
-    // two window groups on two streams unless a mode wants one ordered launch sequence (per-launch timing, debug tap)
-    const bool dual = bf && v->stream2 && v->timing < 2 && !(v->tap_layer >= 0 && v->tap_dst);
-    demon_status rc = get_plan(v, n_clips, n_frames, fb, fe, window, halo, dual, stream, &plan);
-    if (rc != DEMON_OK) return rc;
+    const bool dual = wants_two_groups(v);
     const Slot* slots = plan->d_slots;
     const int ns = plan->n_slots, ml = plan->max_len;
     if (d_skip) {
         // gated decode: every kernel reads a copy of the table in which the skipped clips' windows are empty
-        HIP_TRY(launch_gate_slots(plan->d_slots, v->d_slot_gated, ns, d_skip, stream), "decode gate");
-        slots = v->d_slot_gated;
+        HIP_TRY(launch_gate_slots(plan->d_slots, ws.slot_gated, ns, d_skip, stream), "decode gate");
+        slots = ws.slot_gated;
     }
 
     // the convolution launches address a group of windows (gs, gn) on a stream gst: all windows on the caller's
@@ -298,11 +336,11 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
     // level 2 adds a mark after every convolution launch.
     HIP_TRY(mark(1), "event");
 
-    void* cur = v->buf[0];
-    void* other = v->buf[1];
+    void* cur = ws.buf[0];
+    void* other = ws.buf[1];
     int r = 1, layer_id = 0;
     const size_t n_blocks = v->blocks.size();
-    const long long lo_off = (long long)v->act_elems;        // lo plane of a split bf16 tensor
+    const long long lo_off = (long long)ws.act_elems;        // lo plane of a split bf16 tensor
     auto tap = [&](const void* x, int c) -> hipError_t {
         const int id = layer_id++;
         if (id != v->tap_layer || !v->tap_dst) return hipSuccess;
@@ -330,10 +368,10 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
         auto run_conv = [&](const ConvLayer& L, const void* x, void* y, const void* res) -> hipError_t {
             ConvArgs a = conv_args(L, x, y, res);
             if (L.in_alpha) {
-                hipError_t e = launch_snake_f32((const float*)x, (float*)v->buf[2], L.in_alpha, L.in_inv_beta, L.cin,
+                hipError_t e = launch_snake_f32((const float*)x, (float*)ws.buf[2], L.in_alpha, L.in_inv_beta, L.cin,
                                                 (size_t)plan->total_frames * r * L.cin, stream);
                 if (e != hipSuccess) return e;
-                a.x = v->buf[2];
+                a.x = ws.buf[2];
                 a.in_alpha = a.in_inv_beta = nullptr;
             }
             return launch_conv_f32(a, stream);
@@ -359,9 +397,9 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
         // ---- bf16 path.  h (half) ping-pongs between buf[0] and buf[1]; the activated bf16 operand `a` of the
         // next layer that wants one ping-pongs between buf[3] and buf[4]; buf[2] holds the activated branch tensor
         // between the dilated and the 1x1 conv of a two-kernel unit.  Each producer writes `a` with its consumer's Snake.
-        uint16_t* acur = (uint16_t*)v->buf[3];
-        uint16_t* aoth = (uint16_t*)v->buf[4];
-        uint16_t* mid = (uint16_t*)v->buf[2];
+        uint16_t* acur = (uint16_t*)ws.buf[3];
+        uint16_t* aoth = (uint16_t*)ws.buf[4];
+        uint16_t* mid = (uint16_t*)ws.buf[2];
         // the layer that consumes the output of block bi's unit ui (ui = -1: of its transposed conv);
         // nullptr when that layer reads the residual stream itself (narrow fused unit, head)
         auto consumer = [&](size_t bi, int ui) -> const ConvLayer* {
@@ -372,13 +410,13 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
         for (int gi = 0; gi < plan->n_groups; ++gi) {
             select_group(gi, stream);
             const ConvLayer& U0 = v->blocks[0].up;
-            HIP_TRY(launch_gather(d_latent, nullptr, v->st.c0, n_frames, true, gs, gn, ml, stream, (uint16_t*)v->buf[3] + goff(),
+            HIP_TRY(launch_gather(d_latent, nullptr, v->st.c0, n_frames, true, gs, gn, ml, stream, (uint16_t*)ws.buf[3] + goff(),
                                   U0.in_fmt, lo_off, U0.in_alpha, U0.in_inv_beta), "gather");
         }
         HIP_TRY(mark(1), "event");
         auto layers = [&]() -> demon_status {
-        cur = (uint16_t*)v->buf[0] + goff(); other = (uint16_t*)v->buf[1] + goff();      // half: 2 bytes
-        acur = (uint16_t*)v->buf[3] + goff(); aoth = (uint16_t*)v->buf[4] + goff(); mid = (uint16_t*)v->buf[2] + goff();
+        cur = (uint16_t*)ws.buf[0] + goff(); other = (uint16_t*)ws.buf[1] + goff();      // half: 2 bytes
+        acur = (uint16_t*)ws.buf[3] + goff(); aoth = (uint16_t*)ws.buf[4] + goff(); mid = (uint16_t*)ws.buf[2] + goff();
         r = 1; layer_id = 0;
         for (size_t bi = 0; bi < n_blocks; ++bi) {
             const Block& B = v->blocks[bi];
@@ -468,7 +506,7 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
     for (int gi = 0; gi < plan->n_groups; ++gi) {
         select_group(gi, stream);
         const void* x = final_base + goff() * hbytes;
-        float* y = v->head_out + plan->g_frame0[gi] * r;
+        float* y = ws.head_out + plan->g_frame0[gi] * r;
         if (v->head_wfrag) {
             HIP_TRY(launch_head_mfma(x, y, v->head_wfrag, v->head_bias, v->head_alpha, v->head_inv_beta, v->head_cin,
                                      v->st.out_channels, v->st.head_kernel, r, total_rows, gs, gn, ml, plan->max_int, stream), "head");
@@ -480,7 +518,7 @@ demon_status run_decode(demon_vae* v, const void* d_latent, int n_clips, int n_f
     HIP_TRY(mark(1), "event");
     for (int gi = 0; gi < plan->n_groups; ++gi) {
         select_group(gi, stream);
-        const float* y = v->head_out + plan->g_frame0[gi] * r;
+        const float* y = ws.head_out + plan->g_frame0[gi] * r;
         if (d_pcm)
             HIP_TRY(launch_stitch_pcm16(y, d_pcm, v->st.out_channels, r, n_frames, total_rows, gs, gn, plan->max_int, stream), "stitch");
         else
@@ -529,7 +567,12 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
     if (cfg->max_extended_frames < 0) return fail(DEMON_ERR_INVALID_ARG, "max_extended_frames must be >= 0");
     v->cap_frames = cfg->max_extended_frames > 0 ? cfg->max_extended_frames : 3ll * cfg->max_frames * cfg->max_clips;
     stack_receptive_field(st, &v->rf_left, &v->rf_right);
-    (void)hipGetDevice(&v->device);
+    if (hipGetDevice(&v->device) != hipSuccess) return fail(DEMON_ERR_HIP, "hipGetDevice failed");
+    {
+        // the static scratch array of demon_vae_decode_windowed_static: its address on this device
+        const hipError_t se = static_scratch(v->device, &v->scratch);
+        if (se != hipSuccess) return hip_fail(se, "hipGetSymbolAddress(static scratch)");
+    }
 
     // ---- pack parameters (offsets first, device pointers after the upload)
     Arena ar;
@@ -550,6 +593,7 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
             ConvLayer& L = B.up;
             L.cin = cin; L.cout = c; L.ntaps = 2; L.stride = s;
             L.in_fmt = (bf && c >= kSplitWidth) ? g_wide_fmt : (int)OP_BF16;
+            if (L.in_fmt == OP_BF16X2) v->has_split_operands = true;
             if (bf) {
                 L.variant = choose_variant_bf16(cin, s * c);
                 if (L.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for a %d -> %d stride-%d upsampling", cin, c, s);
@@ -568,6 +612,7 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
             P.cin = c; P.cout = c; P.ntaps = 1; P.dil = 1;
             const bool wide_ops = bf && c >= kSplitWidth;
             P.in_fmt = wide_ops ? g_wide_fmt : (int)OP_BF16;
+            if (P.in_fmt == OP_BF16X2) v->has_split_operands = true;
             D.in_fmt = (wide_ops && g_wide_fmt == OP_F16) ? (int)OP_F16 : (int)OP_BF16;
             if (bf) {
                 D.variant = choose_variant_bf16(c, c);
@@ -648,15 +693,15 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
 
     // ---- device memory
     const size_t act_elems = (size_t)v->cap_frames * (size_t)per_frame;
-    v->act_elems = act_elems;
+    v->ws.act_elems = act_elems;
     v->per_frame = per_frame;
     const size_t head_bytes = (size_t)v->cap_frames * (size_t)rate * oc * sizeof(float);
     auto cleanup = [&]() {
         if (v->d_params) (void)hipFree(v->d_params);
-        for (void* b : v->buf) if (b) (void)hipFree(b);
-        if (v->head_out) (void)hipFree(v->head_out);
+        for (void* b : v->ws.buf) if (b) (void)hipFree(b);
+        if (v->ws.head_out) (void)hipFree(v->ws.head_out);
         if (v->d_slot_arena) (void)hipFree(v->d_slot_arena);
-        if (v->d_slot_gated) (void)hipFree(v->d_slot_gated);
+        if (v->ws.slot_gated) (void)hipFree(v->ws.slot_gated);
         if (v->h_slot_stage) (void)hipHostFree(v->h_slot_stage);
         for (hipEvent_t ev : v->plan_copied) if (ev) (void)hipEventDestroy(ev);
         if (v->ev_fork) (void)hipEventDestroy(v->ev_fork);
@@ -665,10 +710,10 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
     };
     hipError_t e = hipMalloc(&v->d_params, ar.bytes.size());
     // fp32 path: 4 bytes per element; bf16 path: half residual stream (2 bytes), bf16 operand buffers with hi and lo planes (4)
-    for (int i = 0; e == hipSuccess && i < (bf ? 5 : 3); ++i) e = hipMalloc(&v->buf[i], act_elems * ((bf && i < 2) ? 2 : 4));
-    if (e == hipSuccess) e = hipMalloc((void**)&v->head_out, head_bytes);
+    for (int i = 0; e == hipSuccess && i < (bf ? 5 : 3); ++i) e = hipMalloc(&v->ws.buf[i], act_elems * ((bf && i < 2) ? 2 : 4));
+    if (e == hipSuccess) e = hipMalloc((void**)&v->ws.head_out, head_bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&v->d_slot_arena, sizeof(Slot) * kMaxSlots * kPlanCache);
-    if (e == hipSuccess) e = hipMalloc((void**)&v->d_slot_gated, sizeof(Slot) * kMaxSlots);
+    if (e == hipSuccess) e = hipMalloc((void**)&v->ws.slot_gated, sizeof(Slot) * kMaxSlots);
     if (e == hipSuccess) e = hipHostMalloc((void**)&v->h_slot_stage, sizeof(Slot) * kMaxSlots * kPlanCache, hipHostMallocDefault);
     for (int i = 0; e == hipSuccess && i < kPlanCache; ++i) e = hipEventCreateWithFlags(&v->plan_copied[i], hipEventDisableTiming);
     if (e == hipSuccess && bf && g_dual_stream) {
@@ -700,10 +745,10 @@ void demon_vae_destroy(demon_vae* v)
 {
     if (!v) return;
     (void)hipFree(v->d_params);
-    for (void* b : v->buf) if (b) (void)hipFree(b);
-    (void)hipFree(v->head_out);
+    for (void* b : v->ws.buf) if (b) (void)hipFree(b);
+    (void)hipFree(v->ws.head_out);
     (void)hipFree(v->d_slot_arena);
-    (void)hipFree(v->d_slot_gated);
+    (void)hipFree(v->ws.slot_gated);
     (void)hipHostFree(v->h_slot_stage);
     for (hipEvent_t e : v->plan_copied) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : v->events) (void)hipEventDestroy(e);
@@ -736,7 +781,10 @@ static demon_status decode_checked(demon_vae* v, const void* d_latent, int n_cli
     if (n_frames > v->max_frames) return fail(DEMON_ERR_WORKSPACE, "n_frames %d exceeds max_frames %d", n_frames, v->max_frames);
     if (n_clips > v->max_clips) return fail(DEMON_ERR_WORKSPACE, "n_clips %d exceeds max_clips %d", n_clips, v->max_clips);
     if (halo == -1) halo = std::max(v->rf_left, v->rf_right);
-    return run_decode(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, d_skip, d_out, d_pcm, (hipStream_t)stream);
+    Plan* plan = nullptr;
+    const demon_status rc = get_plan(v, n_clips, n_frames, frame_begin, frame_end, window, halo, wants_two_groups(v), (hipStream_t)stream, &plan);
+    if (rc != DEMON_OK) return rc;
+    return run_decode(v, v->ws, plan, d_latent, n_frames, d_skip, d_out, d_pcm, (hipStream_t)stream);
 }
 
 demon_status demon_vae_decode_windowed(demon_vae* v, const void* d_latent, int n_clips, int n_frames,
@@ -761,6 +809,70 @@ demon_status demon_vae_decode_windowed_pcm16(demon_vae* v, const void* d_latent,
 {
     if (!d_pcm) { clear_error(); return fail(DEMON_ERR_INVALID_ARG, "NULL argument"); }
     return decode_checked(v, d_latent, n_clips, n_frames, frame_begin, frame_end, window, halo, nullptr, nullptr, d_pcm, stream);
+}
+
+demon_status demon_vae_decode_windowed_static(demon_vae* v, const void* d_latent, int n_clips, int n_frames,
+                                              int frame_begin, int frame_end, int window, int halo,
+                                              float* d_out, void* stream_)
+{
+    clear_error();
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!v || !d_latent || !d_out) return fail(DEMON_ERR_INVALID_ARG, "NULL argument");
+    if (n_clips < 1) return fail(DEMON_ERR_INVALID_ARG, "n_clips must be >= 1");
+    if (n_frames < 1) return fail(DEMON_ERR_INVALID_ARG, "n_frames must be >= 1");
+    if (frame_begin < 0) return fail(DEMON_ERR_INVALID_ARG, "frame_begin must be >= 0");
+    if (frame_end > n_frames) return fail(DEMON_ERR_INVALID_ARG, "frame_end %d exceeds n_frames %d", frame_end, n_frames);
+    if (frame_begin >= frame_end) return fail(DEMON_ERR_INVALID_ARG, "empty frame range [%d, %d)", frame_begin, frame_end);
+    if (window < 1) return fail(DEMON_ERR_INVALID_ARG, "window must be >= 1");
+    if (halo < -1) return fail(DEMON_ERR_INVALID_ARG, "halo must be >= -1");
+    if (halo == -1) halo = std::max(v->rf_left, v->rf_right);
+    if (!v->scratch) return fail(DEMON_ERR_HIP, "the static scratch array was not found on this device");
+
+    // the window grid, counted on the host without building it (the table itself is written by a kernel)
+    const long long per_clip = ((long long)frame_end - frame_begin + window - 1) / window;
+    if (per_clip * n_clips > kMaxSlots)
+        return fail(DEMON_ERR_WORKSPACE, "%lld windows exceed the limit of %d", per_clip * n_clips, kMaxSlots);
+    long long clip_frames = 0;
+    int max_len = 0, max_int = 0;
+    for (long long b = frame_begin; b < frame_end; b += window) {
+        const long long e = std::min<long long>(b + window, frame_end);
+        const int len = (int)(std::min<long long>(n_frames, e + halo) - std::max<long long>(0, b - halo));
+        clip_frames += len;
+        max_len = std::max(max_len, len);
+        max_int = std::max(max_int, (int)(e - b));
+    }
+    const long long total = clip_frames * n_clips;
+
+    // carve the call's memory out of the static array: window table, activation buffers, window waveforms
+    const bool bf = v->dtype == DEMON_BF16;
+    const size_t act_elems = (size_t)total * (size_t)v->per_frame;
+    const size_t planes = (bf && v->has_split_operands) ? 2 : 1;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t at = off; off = (at + bytes + 255) & ~(size_t)255; return at; };
+    const size_t at_slots = take(sizeof(Slot) * (size_t)(per_clip * n_clips));
+    size_t at_buf[5] = {0, 0, 0, 0, 0};
+    for (int i = 0; i < (bf ? 5 : 3); ++i) at_buf[i] = take(act_elems * (bf ? (i < 2 ? 2 : 2 * planes) : 4));
+    const size_t at_head = take((size_t)total * (size_t)v->st.total_stride() * v->st.out_channels * sizeof(float));
+    if (off > kStaticScratchBytes)
+        return fail(DEMON_ERR_WORKSPACE, "the call needs %zu bytes of scratch for %lld extended frames, the static array holds %zu",
+                    off, total, kStaticScratchBytes);
+    Workspace ws;
+    for (int i = 0; i < (bf ? 5 : 3); ++i) ws.buf[i] = v->scratch + at_buf[i];
+    ws.head_out = reinterpret_cast<float*>(v->scratch + at_head);
+    ws.act_elems = act_elems;
+
+    Plan plan;
+    plan.valid = true;
+    plan.n_clips = n_clips; plan.n_frames = n_frames; plan.frame_begin = frame_begin; plan.frame_end = frame_end;
+    plan.window = window; plan.halo = halo;
+    plan.n_slots = (int)(per_clip * n_clips); plan.max_len = max_len; plan.max_int = max_int;
+    plan.total_frames = total;
+    plan.n_groups = 1;
+    plan.g_first[0] = 0; plan.g_count[0] = plan.n_slots; plan.g_frame0[0] = 0; plan.g_frames[0] = total;
+    plan.d_slots = reinterpret_cast<Slot*>(v->scratch + at_slots);
+    HIP_TRY(launch_plan_slots(plan.d_slots, n_clips, (int)per_clip, (int)clip_frames, n_frames, frame_begin, frame_end, window, halo, stream),
+            "window table");
+    return run_decode(v, ws, &plan, d_latent, n_frames, nullptr, d_out, nullptr, stream);
 }
 
 demon_status demon_vae_decode(demon_vae* v, const void* d_latent, int n_clips, int n_frames, float* d_out, void* stream)

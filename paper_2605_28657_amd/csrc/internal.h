@@ -153,6 +153,10 @@ hipError_t launch_stitch(const float* y, float* out, int oc, int S, int n_frames
 // crop + stitch + 16-bit render: planar slot waveform -> d_pcm [n_clips, n_frames*S, oc] interleaved int16
 hipError_t launch_stitch_pcm16(const float* y, int16_t* pcm, int oc, int S, int n_frames, long long total_rows,
                                const Slot* slots, int n_slots, int max_int, hipStream_t stream);
+// window table written on the device (no host copy): the same grid as the host builds for the plan cache, as one
+// group; per_clip windows and clip_frames extended frames per clip
+hipError_t launch_plan_slots(Slot* dst, int n_clips, int per_clip, int clip_frames, int n_frames, int frame_begin,
+                             int frame_end, int window, int halo, hipStream_t stream);
 // decode gate: dst = src with the windows of clips whose skip flag is set emptied
 hipError_t launch_gate_slots(const Slot* src, Slot* dst, int n, const int* skip, hipStream_t stream);
 // latent similarity filter: per clip mse = mean((a-b)^2) over n elements and the gate mse < threshold

@@ -517,6 +517,45 @@ hipError_t launch_gate_slots(const Slot* src, Slot* dst, int n, const int* skip,
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------- window table on the device
+// The window grid of section 3.6 written by a kernel: window k of a clip covers frames [begin + k window, ...), is
+// extended by the halo and clamped to the clip; its workspace rows follow those of the windows before it.  One thread
+// per window; the prefix sum over the earlier windows of the clip is a short loop (at most 4096 windows per call).
+__global__ __launch_bounds__(256) void plan_slots_kernel(Slot* __restrict__ dst, int n, int per_clip, int clip_frames,
+                                                         int n_frames, int fb, int fe, int window, int halo)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int clip = i / per_clip, k = i - clip * per_clip;
+    auto extent = [&](int kk, int* lo, int* hi, int* b, int* e) {
+        *b = fb + kk * window;
+        *e = min(*b + window, fe);
+        *lo = max(0, *b - halo);
+        *hi = min(n_frames, *e + halo);
+    };
+    int row = clip * clip_frames;
+    for (int kk = 0; kk < k; ++kk) {
+        int lo, hi, b, e;
+        extent(kk, &lo, &hi, &b, &e);
+        row += hi - lo;
+    }
+    int lo, hi, b, e;
+    extent(k, &lo, &hi, &b, &e);
+    Slot s;
+    s.row0 = row; s.len = hi - lo; s.clip = clip; s.lo = lo; s.crop = b - lo; s.n_int = e - b; s.begin = b; s.pad = 0;
+    dst[i] = s;
+}
+
+hipError_t launch_plan_slots(Slot* dst, int n_clips, int per_clip, int clip_frames, int n_frames, int frame_begin,
+                             int frame_end, int window, int halo, hipStream_t stream)
+{
+    const long long n = (long long)n_clips * per_clip;
+    if (n < 1 || n > 65536) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(plan_slots_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, dst, (int)n, per_clip, clip_frames,
+                       n_frames, frame_begin, frame_end, window, halo);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------- latent similarity filter
 // One workgroup per clip: squared differences accumulate in double in a fixed order (thread-strided partial sums, then a
 // tree over the workgroup), so the result does not depend on scheduling.  mse and the gate go out as fp32 / int.

@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "demon_vae.h")).read()
     names = set(re.findall(r"\b(demon_vae_[a-z0-9_]+)\s*\(", header))
     assert {"demon_vae_create", "demon_vae_destroy", "demon_vae_decode", "demon_vae_decode_windowed", "demon_vae_decode_windowed_pcm16",
-            "demon_vae_decode_windowed_gated", "demon_vae_latent_similarity", "demon_vae_crossfade",
+            "demon_vae_decode_windowed_gated", "demon_vae_decode_windowed_static", "demon_vae_latent_similarity", "demon_vae_crossfade",
             "demon_vae_receptive_field", "demon_vae_rf_from_config", "demon_vae_plan_windows",
             "demon_vae_weight_count", "demon_vae_last_error"} <= names
     lib = pa.load_library()
@@ -103,6 +103,7 @@ def test_null_handle_calls_return_invalid_arg():
     assert lib.demon_vae_decode_windowed(None, None, 1, 1, 0, 1, 1, 0, None, None) == pa.DEMON_ERR_INVALID_ARG
     assert lib.demon_vae_decode_windowed_pcm16(None, None, 1, 1, 0, 1, 1, 0, None, None) == pa.DEMON_ERR_INVALID_ARG
     assert lib.demon_vae_decode_windowed_gated(None, None, 1, 1, 0, 1, 1, 0, None, None, None) == pa.DEMON_ERR_INVALID_ARG
+    assert lib.demon_vae_decode_windowed_static(None, None, 1, 1, 0, 1, 1, 0, None, None) == pa.DEMON_ERR_INVALID_ARG
     l = ctypes.c_int()
     assert lib.demon_vae_receptive_field(None, ctypes.byref(l), ctypes.byref(l)) == pa.DEMON_ERR_INVALID_ARG
     lib.demon_vae_destroy(None)      # ignored
