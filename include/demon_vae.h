@@ -24,21 +24,18 @@
  * internal stream that it forks from and joins back into the given stream
  * within the call, so the call is ordered on the given stream like any other
  * work and can be captured into a graph.
- * A window grid (clips, frames, range, window, halo) seen for the first time
- * has its table uploaded by a small copy on the same stream; the 8 most
- * recent grids are kept.  Under stream capture only cached grids are
- * accepted (issue the call once before capturing).
+ * A window grid (clips, frames, range, window, halo) seen for the first time has its table written by a small
+ * kernel on the same stream; the 16 most recent grids are kept.  A call recorded into a HIP graph pins its grid's
+ * entry for the life of the handle (the graph holds the table's address), so at most 16 different grids can be
+ * recorded per handle; a further one returns DEMON_ERR_WORKSPACE.
  *
- * Environment switches, read once when the library is loaded (A/B timing and
- * tests of the alternative kernels; on the benchmark stacks the results stay within
- * the same tolerances):
- *   DEMON_VAE_WIDE_OPERANDS=bf16x2  bf16 path: levels of 512 channels and more carry the inputs of
- *                                   their transposed and 1x1 convolutions as hi + lo bf16 pairs
- *                                   instead of IEEE half operands
- *   DEMON_VAE_NO_FUSED=1            every residual unit as two kernels (no fused units)
- *   DEMON_VAE_ONE_STREAM=1          no internal second stream
- *   DEMON_VAE_SMALL_TILE_WGS=n      launches of at most n 128 x 128 tiles use 64 x 64 tiles
- *                                   (default 192, 0 = never; bit-identical results)
+ * Options (demon_vae_config fields wide_operands, flags, small_tile_wgs; on the benchmark stacks the results stay
+ * within the same tolerances).  A field left at 0 takes the default, which the environment can change for a whole
+ * process (read once when the library is loaded):
+ *   DEMON_VAE_WIDE_OPERANDS=bf16x2  default of wide_operands becomes 2
+ *   DEMON_VAE_NO_FUSED=1            as if DEMON_VAE_FLAG_NO_FUSED were set in every config
+ *   DEMON_VAE_ONE_STREAM=1          as if DEMON_VAE_FLAG_ONE_STREAM were set in every config
+ *   DEMON_VAE_SMALL_TILE_WGS=n      default of small_tile_wgs becomes n (0 = never)
  */
 #ifndef DEMON_VAE_H
 #define DEMON_VAE_H
@@ -48,6 +45,13 @@
 
 #ifdef __cplusplus
 extern "C" {
+#endif
+
+/* The library is built with hidden visibility; only the entry points declared here are exported. */
+#if defined(__GNUC__)
+#define DEMON_API __attribute__((visibility("default")))
+#else
+#define DEMON_API
 #endif
 
 typedef struct demon_vae demon_vae; /* opaque; owned by the library */
@@ -62,10 +66,15 @@ typedef enum {
 
 typedef enum {
     DEMON_F32 = 0, /* fp32 storage and arithmetic (reference-precision path)            */
-    DEMON_BF16 = 1 /* bf16 weights and latent, 16-bit MFMA operands (bf16; IEEE half on levels
-                      of 512 channels and more), fp32 accumulation and epilogues, residual
-                      stream stored as IEEE half: values beyond the half range overflow      */
+    DEMON_BF16 = 1 /* bf16 weights and latent, 16-bit MFMA operands (bf16; on levels of 512 channels
+                      and more IEEE half or, with wide_operands = 2, hi + lo bf16 pairs), fp32
+                      accumulation and epilogues, residual stream stored as IEEE half.  Conversions to
+                      half saturate at +-65504 instead of overflowing to infinity                      */
 } demon_dtype;
+
+/* demon_vae_config.flags */
+#define DEMON_VAE_FLAG_NO_FUSED   1   /* every residual unit as two kernels (no fused units)          */
+#define DEMON_VAE_FLAG_ONE_STREAM 2   /* no internal second stream: all launches on the given stream  */
 
 /* Layer stack and workspace limits.  Arrays are read during the call only. */
 typedef struct {
@@ -83,6 +92,13 @@ typedef struct {
     int max_clips;        /* most clips a decode call may pass */
     long long max_extended_frames; /* most latent frames, summed over all extended windows (window + halos)
                                       of one call, the workspace must hold; 0 = 3 * max_frames * max_clips */
+    /* Options of the bf16 path; 0 = default in each. */
+    int wide_operands;    /* levels of 512 channels and more: 1 = IEEE half operands on the f16 MFMA (the default),
+                             2 = hi + lo bf16 pairs on the bf16 MFMA (two MFMAs per k-step in the transposed and 1x1
+                             convolutions) for stacks whose wide-level activations may leave the half range */
+    int flags;            /* DEMON_VAE_FLAG_* */
+    int small_tile_wgs;   /* launches of at most this many 128 x 128 tiles use 64 x 64 tiles instead (bit-identical
+                             results, more workgroups for a single playback window); default 192, negative = never */
 } demon_vae_config;
 
 /* One window of the grid: interior latent frames [begin, end) of clip `clip`, decoded from the
@@ -100,7 +116,7 @@ typedef struct {
  * then head.alpha[C], head.beta[C], head.weight[out_channels, C, head_kernel], head.bias[out_channels]
  * -- in that order, each tensor C-contiguous.  Host only.  Returns 0 for an invalid description.
  */
-size_t demon_vae_weight_count(const demon_vae_config* cfg);
+DEMON_API size_t demon_vae_weight_count(const demon_vae_config* cfg);
 
 /*
  * Receptive field of the layer stack in latent frames (host only, no GPU needed): output frame f
@@ -110,13 +126,13 @@ size_t demon_vae_weight_count(const demon_vae_config* cfg);
  * samples [a, b] to inputs [ceil((a + p - k + 1)/s), floor((b + p)/s)].  This is the analytic
  * counterpart of the measured convergence distance of section 3.6.
  */
-demon_status demon_vae_rf_from_config(const demon_vae_config* cfg, int* halo_left, int* halo_right);
+DEMON_API demon_status demon_vae_rf_from_config(const demon_vae_config* cfg, int* halo_left, int* halo_right);
 
 /*
  * Output samples [*lo, *hi] that latent frames [frame_a, frame_b] can influence, ignoring clip
  * edges (the forward cone; host only).
  */
-demon_status demon_vae_forward_support(const demon_vae_config* cfg, int frame_a, int frame_b,
+DEMON_API demon_status demon_vae_forward_support(const demon_vae_config* cfg, int frame_a, int frame_b,
                                        long long* lo, long long* hi);
 
 /*
@@ -127,7 +143,7 @@ demon_status demon_vae_forward_support(const demon_vae_config* cfg, int frame_a,
  * INVALID_ARG: n_clips < 1, n_frames < 1, frame_begin < 0, frame_end > n_frames,
  * frame_begin >= frame_end, window < 1, halo < 0, n_windows NULL.
  */
-demon_status demon_vae_plan_windows(int n_clips, int n_frames, int frame_begin, int frame_end,
+DEMON_API demon_status demon_vae_plan_windows(int n_clips, int n_frames, int frame_begin, int frame_end,
                                     int window, int halo, demon_window* out, int capacity,
                                     int* n_windows);
 
@@ -141,15 +157,15 @@ demon_status demon_vae_plan_windows(int n_clips, int n_frames, int frame_begin, 
  * not a multiple of 16, a width not a multiple of 32, or a dilated kernel spanning more than 64 samples.  HIP: no device / allocation
  * failure.
  */
-demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_weights, size_t n_floats,
+DEMON_API demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_weights, size_t n_floats,
                               demon_vae** out);
 
 /* Frees device memory and the handle.  NULL is ignored.  The caller must have synchronised the
  * streams it used with this handle. */
-void demon_vae_destroy(demon_vae* vae);
+DEMON_API void demon_vae_destroy(demon_vae* vae);
 
 /* Receptive field of this decoder (same as demon_vae_rf_from_config). Host only. */
-demon_status demon_vae_receptive_field(const demon_vae* vae, int* halo_left, int* halo_right);
+DEMON_API demon_status demon_vae_receptive_field(const demon_vae* vae, int* halo_left, int* halo_right);
 
 /*
  * Full decode (section 3.6, the un-windowed baseline): every clip is one window covering
@@ -159,7 +175,7 @@ demon_status demon_vae_receptive_field(const demon_vae* vae, int* halo_left, int
  *   d_out    : device, fp32, [n_clips, out_channels, n_frames * S] planar, S = prod(strides).
  *   stream   : hipStream_t (NULL = default stream).
  */
-demon_status demon_vae_decode(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
+DEMON_API demon_status demon_vae_decode(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
                               float* d_out, void* stream);
 
 /*
@@ -172,9 +188,12 @@ demon_status demon_vae_decode(demon_vae* vae, const void* d_latent, int n_clips,
  * Layouts as for demon_vae_decode (d_latent and d_out are whole-clip buffers).
  * INVALID_ARG: null pointers, n_clips < 1, n_frames < 1, frame_begin < 0, frame_end > n_frames,
  * frame_begin >= frame_end, window < 1, halo < -1.  WORKSPACE: n_frames > max_frames,
- * n_clips > max_clips, more than 4096 windows, or extended windows that exceed the workspace.
+ * n_clips > max_clips, more than 4096 windows, extended windows that exceed the workspace, or (under
+ * stream capture) a new grid when all cached grids are held by graphs.  UNSUPPORTED (bf16 path): one
+ * extended window whose widest activation plane exceeds 4 026 531 840 bytes (32-bit offsets within a
+ * window; about 300 s of audio in ONE window of the x1920 stack -- decode it in several windows).
  */
-demon_status demon_vae_decode_windowed(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
+DEMON_API demon_status demon_vae_decode_windowed(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
                                        int frame_begin, int frame_end, int window, int halo,
                                        float* d_out, void* stream);
 
@@ -186,7 +205,7 @@ demon_status demon_vae_decode_windowed(demon_vae* vae, const void* d_latent, int
  *           [frame_begin*S, frame_end*S) of every clip are written.
  * All other arguments, limits and errors as for demon_vae_decode_windowed.
  */
-demon_status demon_vae_decode_windowed_pcm16(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
+DEMON_API demon_status demon_vae_decode_windowed_pcm16(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
                                              int frame_begin, int frame_end, int window, int halo,
                                              int16_t* d_pcm, void* stream);
 
@@ -202,7 +221,7 @@ demon_status demon_vae_decode_windowed_pcm16(demon_vae* vae, const void* d_laten
  * No handle and no workspace are needed.  INVALID_ARG: null pointers, n_clips outside [1, 65535],
  * elems_per_clip < 1, unknown dtype, threshold negative or NaN.
  */
-demon_status demon_vae_latent_similarity(const void* d_curr, const void* d_prev, int n_clips, long long elems_per_clip,
+DEMON_API demon_status demon_vae_latent_similarity(const void* d_curr, const void* d_prev, int n_clips, long long elems_per_clip,
                                          demon_dtype dtype, float threshold, float* d_mse, int* d_unchanged, void* stream);
 
 /*
@@ -213,7 +232,7 @@ demon_status demon_vae_latent_similarity(const void* d_curr, const void* d_prev,
  * d_out is left as it is; the other clips are decoded exactly as by demon_vae_decode_windowed.
  * All other arguments, limits and errors as there; INVALID_ARG also for a NULL d_skip.
  */
-demon_status demon_vae_decode_windowed_gated(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
+DEMON_API demon_status demon_vae_decode_windowed_gated(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
                                              int frame_begin, int frame_end, int window, int halo,
                                              const int* d_skip, float* d_out, void* stream);
 
@@ -233,20 +252,20 @@ demon_status demon_vae_decode_windowed_gated(demon_vae* vae, const void* d_laten
  * a call reads of it and has not written itself only reaches results that are dropped).
  */
 #define DEMON_VAE_STATIC_SCRATCH_BYTES ((size_t)128 << 20)
-demon_status demon_vae_decode_windowed_static(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
+DEMON_API demon_status demon_vae_decode_windowed_static(demon_vae* vae, const void* d_latent, int n_clips, int n_frames,
                                               int frame_begin, int frame_end, int window, int halo,
                                               float* d_out, void* stream);
 
 /*
- * Equal-power crossfade of a chunk boundary of the playback stream (the paper crossfades each
- * decoded chunk into the output stream and names a 50 ms equal-power fade, 2400 samples at 48 kHz):
+ * Equal-power crossfade of a chunk boundary of the playback stream (Fig. 1 and section 3.1: each decoded
+ * chunk is crossfaded into the output stream; section 4.8.2 names a 50 ms equal-power fade, 2400 samples at 48 kHz):
  *   d_out[c][i] = cos(t_i) * d_prev_tail[c][i] + sin(t_i) * d_next_head[c][i],  t_i = (pi/2)(i + 1/2)/n_samples
  * for planes c < n_planes, samples i < n_samples; plane c of a buffer starts c * stride floats after
  * its pointer, so the segments may lie inside larger planar waveforms.  All device, fp32.  d_out may
  * alias either input exactly (same pointer and stride).  INVALID_ARG: null pointers, n_planes outside
  * [1, 65535], n_samples < 1, a negative stride, or output planes that overlap.
  */
-demon_status demon_vae_crossfade(const float* d_prev_tail, long long prev_stride, const float* d_next_head, long long next_stride,
+DEMON_API demon_status demon_vae_crossfade(const float* d_prev_tail, long long prev_stride, const float* d_next_head, long long next_stride,
                                  float* d_out, long long out_stride, int n_planes, int n_samples, void* stream);
 
 /*
@@ -255,14 +274,14 @@ demon_status demon_vae_crossfade(const float* d_prev_tail, long long prev_stride
  * extended windows to d_dst as fp32, row-major [extended samples at that level, channels].
  * At most `capacity` floats are written.  d_dst is device memory owned by the caller.
  */
-demon_status demon_vae_debug_tap(demon_vae* vae, int layer, float* d_dst, size_t capacity);
+DEMON_API demon_status demon_vae_debug_tap(demon_vae* vae, int layer, float* d_dst, size_t capacity);
 
 /*
  * Benchmark instrumentation.  level 0 = off (default); 1 = HIP events on the decode stream at the
  * boundaries gather | convolutions | head | stitch; 2 = an event after every kernel launch.  The
  * events are created here, not in the decode calls.
  */
-demon_status demon_vae_set_timing(demon_vae* vae, int level);
+DEMON_API demon_status demon_vae_set_timing(demon_vae* vae, int level);
 
 /*
  * Elapsed milliseconds between consecutive events, averaged over the decode calls made since the last
@@ -272,10 +291,24 @@ demon_status demon_vae_set_timing(demon_vae* vae, int level);
  * residual unit the dilated and the 1x1 conv, then head, stitch).  Writes at most `capacity` values
  * to `ms` (host memory) and the number available to *n.
  */
-demon_status demon_vae_get_timing(demon_vae* vae, float* ms, int capacity, int* n);
+DEMON_API demon_status demon_vae_get_timing(demon_vae* vae, float* ms, int capacity, int* n);
+
+/*
+ * Test aids (host only, no GPU): the packed weight layouts the kernels read and the host's fp32 -> half conversion,
+ * exported so that the CPU tests can check them against the layouts the kernel comments state.
+ *   pack_bf16     : `w` in the PyTorch layout (conv [cout, cin, k]; transposed conv [cin, cout, 2 stride], stride > 0)
+ *                   -> blocks [row tile][channel chunk][tap] of the tile variant (0: 128 x 64, 1: 64 x 64, 2: 32 x 16,
+ *                   3: 256 x 32), as bf16 or (as_half) the same values as IEEE half; permute_rows: row order of the
+ *                   generic kernel's accumulator tiles.  dst holds cout * cin * k (times stride) 16-bit values.
+ *   pack_w1_fused : 1x1 weights [c][c] of a fused unit (c = 64, 128), rows and K axis permuted.
+ */
+DEMON_API void demon_vae_test_pack_bf16(const float* w, int cin, int cout, int ntaps, int stride, int variant,
+                                        int as_half, int permute_rows, uint16_t* dst);
+DEMON_API void demon_vae_test_pack_w1_fused(const float* w, int c, uint16_t* dst);
+DEMON_API uint16_t demon_vae_test_f32_to_f16(float v);
 
 /* Message of the last error returned on this thread (empty string if none). Never NULL. */
-const char* demon_vae_last_error(void);
+DEMON_API const char* demon_vae_last_error(void);
 
 #ifdef __cplusplus
 }

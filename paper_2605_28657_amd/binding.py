@@ -33,7 +33,10 @@ class _Config(ctypes.Structure):
                 ("n_res", ctypes.c_int), ("dilations", ctypes.POINTER(ctypes.c_int)),
                 ("res_kernel", ctypes.c_int), ("head_kernel", ctypes.c_int), ("out_channels", ctypes.c_int),
                 ("dtype", ctypes.c_int), ("max_frames", ctypes.c_int), ("max_clips", ctypes.c_int),
-                ("max_extended_frames", ctypes.c_longlong)]
+                ("max_extended_frames", ctypes.c_longlong),
+                ("wide_operands", ctypes.c_int), ("flags", ctypes.c_int), ("small_tile_wgs", ctypes.c_int)]
+
+DEMON_VAE_FLAG_NO_FUSED, DEMON_VAE_FLAG_ONE_STREAM = 1, 2
 
 
 class _Window(ctypes.Structure):
@@ -92,7 +95,8 @@ def _check(status: int):
 
 def _make_config(latent_channels: int, strides: Sequence[int], widths: Sequence[int], dilations: Sequence[int],
                  res_kernel: int, head_kernel: int, out_channels: int, dtype: int = DEMON_F32,
-                 max_frames: int = 1, max_clips: int = 1, max_extended_frames: int = 0):
+                 max_frames: int = 1, max_clips: int = 1, max_extended_frames: int = 0,
+                 wide_operands: int = 0, flags: int = 0, small_tile_wgs: int = 0):
     """Returns (config struct, keep-alive tuple of the int arrays it points to)."""
     s = (ctypes.c_int * max(len(strides), 1))(*strides)
     w = (ctypes.c_int * max(len(widths), 1))(*widths)
@@ -100,15 +104,16 @@ def _make_config(latent_channels: int, strides: Sequence[int], widths: Sequence[
     if len(strides) != len(widths):
         raise ValueError("strides and widths differ in length")
     cfg = _Config(latent_channels, len(strides), s, w, len(dilations), d, res_kernel, head_kernel, out_channels,
-                  dtype, max_frames, max_clips, max_extended_frames)
+                  dtype, max_frames, max_clips, max_extended_frames, wide_operands, flags, small_tile_wgs)
     return cfg, (s, w, d)
 
 
 def config_from_spec(spec, dtype: int = DEMON_F32, max_frames: int = 1, max_clips: int = 1,
-                     max_extended_frames: int = 0):
+                     max_extended_frames: int = 0, wide_operands: int = 0, flags: int = 0, small_tile_wgs: int = 0):
     """Config from any object with latent_channels/strides/widths/dilations/res_kernel/head_kernel/out_channels."""
     return _make_config(spec.latent_channels, spec.strides, spec.widths, spec.dilations, spec.res_kernel,
-                        spec.head_kernel, spec.out_channels, dtype, max_frames, max_clips, max_extended_frames)
+                        spec.head_kernel, spec.out_channels, dtype, max_frames, max_clips, max_extended_frames,
+                        wide_operands, flags, small_tile_wgs)
 
 
 def demon_vae_weight_count(spec) -> int:
@@ -141,9 +146,9 @@ def demon_vae_plan_windows(n_clips: int, n_frames: int, frame_begin: int, frame_
 
 
 def demon_vae_create(spec, weights: np.ndarray, dtype: int, max_frames: int, max_clips: int = 1,
-                     max_extended_frames: int = 0) -> int:
+                     max_extended_frames: int = 0, wide_operands: int = 0, flags: int = 0, small_tile_wgs: int = 0) -> int:
     """Returns the opaque handle (an integer address).  `weights`: flat fp32 host array, canonical order."""
-    cfg, _keep = config_from_spec(spec, dtype, max_frames, max_clips, max_extended_frames)
+    cfg, _keep = config_from_spec(spec, dtype, max_frames, max_clips, max_extended_frames, wide_operands, flags, small_tile_wgs)
     w = np.ascontiguousarray(weights, dtype=np.float32)
     handle = ctypes.c_void_p()
     _check(load_library().demon_vae_create(ctypes.byref(cfg), w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
@@ -259,7 +264,7 @@ class DemonVAE:
     """Convenience wrapper: owns a handle, marshals torch tensors.  No arithmetic happens here."""
 
     def __init__(self, spec, weights: np.ndarray, dtype: str = "bf16", max_frames: int = 1500, max_clips: int = 1,
-                 max_extended_frames: int = 0):
+                 max_extended_frames: int = 0, wide_operands: int = 0, flags: int = 0, small_tile_wgs: int = 0):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("DemonVAE needs a HIP device; there is no CPU fallback")
@@ -269,7 +274,8 @@ class DemonVAE:
         self.S = 1
         for s in spec.strides:
             self.S *= s
-        self.handle = demon_vae_create(spec, weights, self.dtype, max_frames, max_clips, max_extended_frames)
+        self.handle = demon_vae_create(spec, weights, self.dtype, max_frames, max_clips, max_extended_frames,
+                                       wide_operands, flags, small_tile_wgs)
 
     def close(self):
         if getattr(self, "handle", None):

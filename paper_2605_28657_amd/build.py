@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdemon_vae.so")
 PROBE = os.path.join(HERE, "mfma_probe")        # stand-alone measurement aid (sustained MFMA rate), see csrc/mfma_probe.hip
 SOURCES = ["host_plan.cpp", "api.hip", "kernels_io.hip", "kernels_f32.hip", "kernels_bf16.hip", "kernels_bf16_fused.hip", "kernels_bf16_wide.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-fvisibility=hidden", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          # MFMA accumulators in ordinary VGPRs: the epilogues work on them with VALU instructions
          "-mllvm", "-amdgpu-mfma-vgpr-form"]

@@ -16,24 +16,27 @@ using namespace demon;
 namespace {
 
 constexpr int kMaxSlots = 4096;
-constexpr int kPlanCache = 8;
+constexpr int kPlanCache = 16;
 constexpr int kTimingRing = 32;        // decode calls whose events are kept for demon_vae_get_timing
 // bf16 path: blocks at least this wide carry their MFMA operands with more mantissa bits than bf16.  There the
 // branch gain (weight std x sqrt(fan-in)) is about one, so operand rounding passes into the output at full
 // strength.  Default: IEEE half operands on the f16 MFMA for every convolution of such a block (same rate as bf16;
-// the operands have the range of the half residual stream they are computed from).  DEMON_VAE_WIDE_OPERANDS=bf16x2
-// in the environment selects hi + lo bf16 pairs instead, for the inputs of the block's transposed conv and of its
-// 1x1 convs (two MFMAs per k-step there; the dilated convs then take plain bf16).
+// the operands have the range of the half residual stream they are computed from).  The alternative (config field
+// wide_operands) carries hi + lo bf16 pairs instead, for the inputs of the block's transposed conv and of its 1x1
+// convs (two MFMAs per k-step there; the dilated convs then take plain bf16).
 constexpr int kSplitWidth = 512;
-const int g_wide_fmt = [] {
+// Defaults of the config fields wide_operands / flags / small_tile_wgs where they are left at 0, from the environment
+// (read once when the library is loaded; for A/B timing of a whole program without touching its configs).
+const int g_env_wide_fmt = [] {
     const char* e = getenv("DEMON_VAE_WIDE_OPERANDS");
     return (e && strcmp(e, "bf16x2") == 0) ? (int)OP_BF16X2 : (int)OP_F16;
 }();
-// DEMON_VAE_NO_FUSED=1 in the environment keeps every residual unit on the two-kernel path (A/B timing and
-// parity tests of the unfused kernels at 64 and 128 channels).
-const bool g_allow_fused = getenv("DEMON_VAE_NO_FUSED") == nullptr;
-// DEMON_VAE_ONE_STREAM=1 keeps the layer sequence of the bf16 path on the caller's stream only (A/B timing).
-const bool g_dual_stream = getenv("DEMON_VAE_ONE_STREAM") == nullptr;
+const bool g_env_no_fused = getenv("DEMON_VAE_NO_FUSED") != nullptr;
+const bool g_env_one_stream = getenv("DEMON_VAE_ONE_STREAM") != nullptr;
+const long long g_env_small_tile_wgs = [] {
+    const char* e = getenv("DEMON_VAE_SMALL_TILE_WGS");
+    return e ? atoll(e) : 192ll;
+}();
 
 struct ConvLayer {
     int cin = 0, cout = 0, ntaps = 0, dil = 1, stride = 0, variant = -1;
@@ -65,6 +68,9 @@ struct Plan {
     long long g_frame0[2] = {0, 0}, g_frames[2] = {0, 0};
     Slot* d_slots = nullptr;
     unsigned long long last_use = 0;
+    // A call on this grid was recorded into a HIP graph: the graph holds the address of this entry's table (and the
+    // grid's launch shapes), so the entry is never evicted while the handle lives.
+    bool pinned = false;
 };
 
 // The device memory a decode call works in besides its inputs and outputs: the handle's own (allocated at create) or,
@@ -111,6 +117,7 @@ struct demon_vae {
     int rf_left = 0, rf_right = 0;
     int device = 0;
     bool has_split_operands = false;   // bf16 path: some layer carries its operand as hi + lo planes
+    long long small_tile_wgs = 192;    // bf16 path: launches of at most this many 128 x 128 tiles use 64 x 64 tiles
 
     void* d_params = nullptr;          // one allocation: all packed weights, biases, Snake parameters
     std::vector<Block> blocks;
@@ -129,8 +136,6 @@ struct demon_vae {
     Slot* d_slot_arena = nullptr;
     hipStream_t stream2 = nullptr;                 // second lane of the bf16 layer sequence (default priority, non-blocking)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-    Slot* h_slot_stage = nullptr;                  // pinned staging of the window tables, one region per cached plan
-    hipEvent_t plan_copied[kPlanCache] = {};       // recorded after a table's upload: its staging region is free again
     Plan plans[kPlanCache];
     unsigned long long use_counter = 0;
 
@@ -200,99 +205,102 @@ demon_status hip_fail(hipError_t e, const char* what)
     return fail(DEMON_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-void build_slots(int n_clips, int n_frames, int fb, int fe, int window, int halo, std::vector<Slot>* out,
-                 long long* total, int* max_len, int* max_int)
+// The window grid of one clip, walked on the host: windows, extended frames, longest window and interior.
+struct GridCount { long long per_clip = 0, clip_frames = 0; int max_len = 0, max_int = 0; };
+
+GridCount count_grid(int n_frames, int fb, int fe, int window, int halo)
 {
-    long long row = 0;
-    int ml = 0, mi = 0;
-    for (int c = 0; c < n_clips; ++c)
-        for (long long b = fb; b < fe; b += window) {
-            const long long e = std::min<long long>(b + window, fe);
-            Slot s;
-            s.clip = c;
-            s.lo = (int)std::max<long long>(0, b - halo);
-            const int hi = (int)std::min<long long>(n_frames, e + halo);
-            s.len = hi - s.lo;
-            s.crop = (int)b - s.lo;
-            s.n_int = (int)(e - b);
-            s.begin = (int)b;
-            s.row0 = (int)row;
-            s.pad = 0;
-            row += s.len;
-            ml = std::max(ml, s.len);
-            mi = std::max(mi, s.n_int);
-            out->push_back(s);
-        }
-    *total = row; *max_len = ml; *max_int = mi;
+    GridCount g;
+    for (long long b = fb; b < fe; b += window) {
+        const long long e = std::min<long long>(b + window, fe);
+        const int len = (int)(std::min<long long>(n_frames, e + halo) - std::max<long long>(0, b - halo));
+        g.clip_frames += len;
+        g.max_len = std::max(g.max_len, len);
+        g.max_int = std::max(g.max_int, (int)(e - b));
+        ++g.per_clip;
+    }
+    return g;
 }
 
-// Looks the window grid up in the plan cache; on a miss builds the table, writes it to the pinned staging region of the
-// least recently used entry and uploads it with a copy on the decode stream, so the call stays asynchronous: kernels of
-// earlier calls that still read the replaced table precede the copy on that stream.
+#define HIP_TRY(expr, what) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_fail(e_, what); } while (0)
+
+// bf16 path: a window's activation plane is addressed with 32-bit byte offsets through a buffer descriptor
+demon_status check_plane(const demon_vae* v, int max_len)
+{
+    if (v->dtype != DEMON_BF16) return DEMON_OK;
+    const long long bytes = (long long)max_len * v->per_frame * 2;
+    if (bytes > 0xf0000000ll)
+        return fail(DEMON_ERR_UNSUPPORTED, "a window of %d frames has an activation plane of %lld bytes; the kernels address one window "
+                    "with 32-bit offsets (limit %lld bytes): decode it in several windows", max_len, bytes, 0xf0000000ll);
+    return DEMON_OK;
+}
+
+// Looks the window grid up in the plan cache; on a miss the table of the least recently used entry that no graph holds is
+// rewritten by a small kernel on the decode stream, so the call stays asynchronous (kernels of earlier calls that still
+// read the replaced table precede that kernel on the stream) and can itself be recorded into a graph.
 demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, int window, int halo, bool two_groups,
                       hipStream_t stream, Plan** out)
 {
     ++v->use_counter;
-    Plan* victim = &v->plans[0];
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    HIP_TRY(hipStreamIsCapturing(stream, &cap), "hipStreamIsCapturing");
+    const bool capturing = cap != hipStreamCaptureStatusNone;
+    Plan* victim = nullptr;
     for (Plan& p : v->plans) {
         if (p.valid && p.n_clips == n_clips && p.n_frames == n_frames && p.frame_begin == fb && p.frame_end == fe &&
             p.window == window && p.halo == halo && (p.n_groups == 2) == (two_groups && p.n_slots >= 2)) {
             p.last_use = v->use_counter;
+            if (capturing) p.pinned = true;
             *out = &p;
             return DEMON_OK;
         }
-        if (!p.valid) { if (victim->valid) victim = &p; }
-        else if (victim->valid && p.last_use < victim->last_use) victim = &p;
+        if (p.pinned) continue;
+        if (!victim || (victim->valid && (!p.valid || p.last_use < victim->last_use))) victim = &p;
     }
-    const long long per_clip = ((long long)fe - fb + window - 1) / window;
-    if (per_clip * n_clips > kMaxSlots)
-        return fail(DEMON_ERR_WORKSPACE, "%lld windows exceed the limit of %d", per_clip * n_clips, kMaxSlots);
-    std::vector<Slot> slots;
-    long long total; int max_len, max_int;
-    build_slots(n_clips, n_frames, fb, fe, window, halo, &slots, &total, &max_len, &max_int);
+    if (!victim)
+        return fail(DEMON_ERR_WORKSPACE, "all %d cached window grids are held by recorded graphs; a further grid needs another handle", kPlanCache);
+    const GridCount gc = count_grid(n_frames, fb, fe, window, halo);
+    const long long n_slots = gc.per_clip * n_clips;
+    if (n_slots > kMaxSlots)
+        return fail(DEMON_ERR_WORKSPACE, "%lld windows exceed the limit of %d", n_slots, kMaxSlots);
+    const long long total = gc.clip_frames * n_clips;
     if (total > v->cap_frames)
         return fail(DEMON_ERR_WORKSPACE, "extended windows need %lld frames, the workspace holds %lld", total, v->cap_frames);
-    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-    hipError_t e = hipStreamIsCapturing(stream, &cap);
-    if (e != hipSuccess) return hip_fail(e, "hipStreamIsCapturing");
-    if (cap != hipStreamCaptureStatusNone)
-        return fail(DEMON_ERR_INVALID_ARG, "this window grid is not cached: issue the call once outside the stream capture first");
-    // two groups of about equal size (in frames) for the bf16 path, whose layer sequence can run on two streams
-    int n_groups = 1, split = (int)slots.size();
-    if (two_groups && slots.size() >= 2) {
-        long long best = -1;
-        for (size_t i = 1; i < slots.size(); ++i) {
-            const long long a = slots[i].row0, d = a > total - a ? a - (total - a) : (total - a) - a;
-            if (best < 0 || d < best) { best = d; split = (int)i; }
-        }
+    const demon_status prc = check_plane(v, gc.max_len);
+    if (prc != DEMON_OK) return prc;
+    // two groups of about equal size (in frames) for the bf16 path, whose layer sequence can run on two streams: the
+    // second group starts at the window whose first row is nearest to half of the rows
+    int n_groups = 1, split = (int)n_slots;
+    long long frame0_b = 0;
+    if (two_groups && n_slots >= 2) {
+        long long best = -1, row = 0, i = 0;
+        for (int c = 0; c < n_clips; ++c)
+            for (long long b = fb; b < fe; b += window, ++i) {
+                const long long e = std::min<long long>(b + window, fe);
+                const long long d = row > total - row ? row - (total - row) : (total - row) - row;
+                if (i >= 1 && (best < 0 || d < best)) { best = d; split = (int)i; frame0_b = row; }
+                row += std::min<long long>(n_frames, e + halo) - std::max<long long>(0, b - halo);
+            }
         n_groups = 2;
     }
-    const long long frame0_b = n_groups == 2 ? slots[split].row0 : 0;
-    for (size_t i = (size_t)split; i < slots.size(); ++i) slots[i].row0 -= (int)frame0_b;
     const int idx = (int)(victim - v->plans);
-    // the staging region may still be the source of this entry's previous upload
-    e = hipEventSynchronize(v->plan_copied[idx]);
-    if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize(window table)");
-    victim->valid = false;
-    Slot* h = v->h_slot_stage + (size_t)idx * kMaxSlots;
     Slot* d = v->d_slot_arena + (size_t)idx * kMaxSlots;
-    memcpy(h, slots.data(), sizeof(Slot) * slots.size());
-    e = hipMemcpyAsync(d, h, sizeof(Slot) * slots.size(), hipMemcpyHostToDevice, stream);
-    if (e == hipSuccess) e = hipEventRecord(v->plan_copied[idx], stream);
-    if (e != hipSuccess) return hip_fail(e, "uploading the window table");
+    victim->valid = false;
+    HIP_TRY(launch_plan_slots(d, n_clips, (int)gc.per_clip, (int)gc.clip_frames, n_frames, fb, fe, window, halo, split, (int)frame0_b, stream),
+            "window table");
     victim->valid = true;
+    victim->pinned = capturing;
     victim->n_clips = n_clips; victim->n_frames = n_frames; victim->frame_begin = fb; victim->frame_end = fe;
     victim->window = window; victim->halo = halo;
-    victim->n_slots = (int)slots.size(); victim->max_len = max_len; victim->max_int = max_int;
+    victim->n_slots = (int)n_slots; victim->max_len = gc.max_len; victim->max_int = gc.max_int;
     victim->total_frames = total; victim->d_slots = d; victim->last_use = v->use_counter;
     victim->n_groups = n_groups;
     victim->g_first[0] = 0; victim->g_count[0] = split; victim->g_frame0[0] = 0; victim->g_frames[0] = n_groups == 2 ? frame0_b : total;
-    victim->g_first[1] = split; victim->g_count[1] = (int)slots.size() - split; victim->g_frame0[1] = frame0_b; victim->g_frames[1] = total - frame0_b;
+    victim->g_first[1] = split; victim->g_count[1] = (int)n_slots - split; victim->g_frame0[1] = frame0_b; victim->g_frames[1] = total - frame0_b;
     *out = victim;
     return DEMON_OK;
 }
 
-#define HIP_TRY(expr, what) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_fail(e_, what); } while (0)
 
 // two window groups on two streams unless a mode wants one ordered launch sequence (per-launch timing, debug tap)
 bool wants_two_groups(const demon_vae* v)
@@ -358,6 +366,7 @@ demon_status run_decode(demon_vae* v, const Workspace& ws, const Plan* plan, con
         a.cin = L.cin; a.cout = L.cout; a.ntaps = L.ntaps; a.dil = L.dil; a.stride = L.stride;
         a.in_fmt = L.in_fmt;
         a.in_lo_off = a.out_lo_off = lo_off;
+        a.small_tile_wgs = v->small_tile_wgs;
         return a;
     };
 
@@ -487,17 +496,21 @@ demon_status run_decode(demon_vae* v, const Workspace& ws, const Plan* plan, con
             HIP_TRY(hipEventRecord(v->ev_fork, stream), "event");
             HIP_TRY(hipStreamWaitEvent(v->stream2, v->ev_fork, 0), "hipStreamWaitEvent");
         }
-        for (int gi = 0; gi < plan->n_groups; ++gi) {
+        demon_status lrc = DEMON_OK;
+        for (int gi = 0; gi < plan->n_groups && lrc == DEMON_OK; ++gi) {
             select_group(gi, two && gi == 1 ? v->stream2 : stream);
-            const demon_status lrc = layers();
-            if (lrc != DEMON_OK) return lrc;
+            lrc = layers();
         }
         if (two) {
-            HIP_TRY(hipEventRecord(v->ev_join, v->stream2), "event");
-            HIP_TRY(hipStreamWaitEvent(stream, v->ev_join, 0), "hipStreamWaitEvent");
+            // also after a failed launch: the second stream joins the caller's again (an open capture stays well-formed)
+            const hipError_t e1 = hipEventRecord(v->ev_join, v->stream2);
+            const hipError_t e2 = e1 == hipSuccess ? hipStreamWaitEvent(stream, v->ev_join, 0) : e1;
+            if (lrc != DEMON_OK) return lrc;
+            HIP_TRY(e2, "joining the second stream");
             marks_on = true;
             HIP_TRY(mark(1), "event");                       // after the last convolution
         }
+        if (lrc != DEMON_OK) return lrc;
     }
     // head and stitch, group by group on the caller's stream; the window waveforms are planar [channel][all rows]
     const long long total_rows = plan->total_frames * r;
@@ -547,6 +560,12 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
     const size_t need = stack_weight_count(st);
     if (n_floats != need) return fail(DEMON_ERR_INVALID_ARG, "got %zu weights, the layer stack needs %zu", n_floats, need);
     const bool bf = cfg->dtype == DEMON_BF16;
+    if (cfg->wide_operands < 0 || cfg->wide_operands > 2) return fail(DEMON_ERR_INVALID_ARG, "wide_operands must be 0, 1 or 2");
+    if (cfg->flags & ~(DEMON_VAE_FLAG_NO_FUSED | DEMON_VAE_FLAG_ONE_STREAM)) return fail(DEMON_ERR_INVALID_ARG, "unknown flag bits 0x%x", (unsigned)cfg->flags);
+    // 0 in a field = the default, which the environment may have changed (see the header)
+    const int g_wide_fmt = cfg->wide_operands == 1 ? (int)OP_F16 : cfg->wide_operands == 2 ? (int)OP_BF16X2 : g_env_wide_fmt;
+    const bool g_allow_fused = !((cfg->flags & DEMON_VAE_FLAG_NO_FUSED) || g_env_no_fused);
+    const bool g_dual_stream = !((cfg->flags & DEMON_VAE_FLAG_ONE_STREAM) || g_env_one_stream);
     if (bf) {
         if (st.c0 % 16) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: latent_channels %d is not a multiple of 16", st.c0);
         for (int c : st.widths)
@@ -567,6 +586,7 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
     if (cfg->max_extended_frames < 0) return fail(DEMON_ERR_INVALID_ARG, "max_extended_frames must be >= 0");
     v->cap_frames = cfg->max_extended_frames > 0 ? cfg->max_extended_frames : 3ll * cfg->max_frames * cfg->max_clips;
     stack_receptive_field(st, &v->rf_left, &v->rf_right);
+    v->small_tile_wgs = cfg->small_tile_wgs > 0 ? cfg->small_tile_wgs : cfg->small_tile_wgs < 0 ? 0 : g_env_small_tile_wgs;
     if (hipGetDevice(&v->device) != hipSuccess) return fail(DEMON_ERR_HIP, "hipGetDevice failed");
     {
         // the static scratch array of demon_vae_decode_windowed_static: its address on this device
@@ -702,8 +722,6 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
         if (v->ws.head_out) (void)hipFree(v->ws.head_out);
         if (v->d_slot_arena) (void)hipFree(v->d_slot_arena);
         if (v->ws.slot_gated) (void)hipFree(v->ws.slot_gated);
-        if (v->h_slot_stage) (void)hipHostFree(v->h_slot_stage);
-        for (hipEvent_t ev : v->plan_copied) if (ev) (void)hipEventDestroy(ev);
         if (v->ev_fork) (void)hipEventDestroy(v->ev_fork);
         if (v->ev_join) (void)hipEventDestroy(v->ev_join);
         if (v->stream2) (void)hipStreamDestroy(v->stream2);
@@ -714,8 +732,6 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
     if (e == hipSuccess) e = hipMalloc((void**)&v->ws.head_out, head_bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&v->d_slot_arena, sizeof(Slot) * kMaxSlots * kPlanCache);
     if (e == hipSuccess) e = hipMalloc((void**)&v->ws.slot_gated, sizeof(Slot) * kMaxSlots);
-    if (e == hipSuccess) e = hipHostMalloc((void**)&v->h_slot_stage, sizeof(Slot) * kMaxSlots * kPlanCache, hipHostMallocDefault);
-    for (int i = 0; e == hipSuccess && i < kPlanCache; ++i) e = hipEventCreateWithFlags(&v->plan_copied[i], hipEventDisableTiming);
     if (e == hipSuccess && bf && g_dual_stream) {
         e = hipStreamCreateWithFlags(&v->stream2, hipStreamNonBlocking);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&v->ev_fork, hipEventDisableTiming);
@@ -749,8 +765,6 @@ void demon_vae_destroy(demon_vae* v)
     (void)hipFree(v->ws.head_out);
     (void)hipFree(v->d_slot_arena);
     (void)hipFree(v->ws.slot_gated);
-    (void)hipHostFree(v->h_slot_stage);
-    for (hipEvent_t e : v->plan_copied) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : v->events) (void)hipEventDestroy(e);
     if (v->ev_fork) (void)hipEventDestroy(v->ev_fork);
     if (v->ev_join) (void)hipEventDestroy(v->ev_join);
@@ -829,19 +843,14 @@ demon_status demon_vae_decode_windowed_static(demon_vae* v, const void* d_latent
     if (!v->scratch) return fail(DEMON_ERR_HIP, "the static scratch array was not found on this device");
 
     // the window grid, counted on the host without building it (the table itself is written by a kernel)
-    const long long per_clip = ((long long)frame_end - frame_begin + window - 1) / window;
+    const GridCount gc = count_grid(n_frames, frame_begin, frame_end, window, halo);
+    const long long per_clip = gc.per_clip, clip_frames = gc.clip_frames;
+    const int max_len = gc.max_len, max_int = gc.max_int;
     if (per_clip * n_clips > kMaxSlots)
         return fail(DEMON_ERR_WORKSPACE, "%lld windows exceed the limit of %d", per_clip * n_clips, kMaxSlots);
-    long long clip_frames = 0;
-    int max_len = 0, max_int = 0;
-    for (long long b = frame_begin; b < frame_end; b += window) {
-        const long long e = std::min<long long>(b + window, frame_end);
-        const int len = (int)(std::min<long long>(n_frames, e + halo) - std::max<long long>(0, b - halo));
-        clip_frames += len;
-        max_len = std::max(max_len, len);
-        max_int = std::max(max_int, (int)(e - b));
-    }
     const long long total = clip_frames * n_clips;
+    const demon_status prc = check_plane(v, max_len);
+    if (prc != DEMON_OK) return prc;
 
     // carve the call's memory out of the static array: window table, activation buffers, window waveforms
     const bool bf = v->dtype == DEMON_BF16;
@@ -870,7 +879,8 @@ demon_status demon_vae_decode_windowed_static(demon_vae* v, const void* d_latent
     plan.n_groups = 1;
     plan.g_first[0] = 0; plan.g_count[0] = plan.n_slots; plan.g_frame0[0] = 0; plan.g_frames[0] = total;
     plan.d_slots = reinterpret_cast<Slot*>(v->scratch + at_slots);
-    HIP_TRY(launch_plan_slots(plan.d_slots, n_clips, (int)per_clip, (int)clip_frames, n_frames, frame_begin, frame_end, window, halo, stream),
+    HIP_TRY(launch_plan_slots(plan.d_slots, n_clips, (int)per_clip, (int)clip_frames, n_frames, frame_begin, frame_end, window, halo,
+                              plan.n_slots, 0, stream),
             "window table");
     return run_decode(v, ws, &plan, d_latent, n_frames, nullptr, d_out, nullptr, stream);
 }
@@ -949,6 +959,16 @@ demon_status demon_vae_get_timing(demon_vae* v, float* ms, int capacity, int* n)
     v->timed_calls = 0;
     return DEMON_OK;
 }
+
+void demon_vae_test_pack_bf16(const float* w, int cin, int cout, int ntaps, int stride, int variant, int as_half,
+                              int permute_rows, uint16_t* dst)
+{
+    pack_bf16(w, cin, cout, ntaps, stride, variant, as_half != 0, permute_rows != 0, dst);
+}
+
+void demon_vae_test_pack_w1_fused(const float* w, int c, uint16_t* dst) { pack_w1_fused(w, c, dst); }
+
+uint16_t demon_vae_test_f32_to_f16(float v) { return f32_to_f16_rne(v); }
 
 demon_status demon_vae_debug_tap(demon_vae* v, int layer, float* d_dst, size_t capacity)
 {

@@ -71,6 +71,16 @@ __device__ __forceinline__ float keep_f32(float v)
     return v;
 }
 
+// Conversions to half saturate instead of overflowing: with the FP16_OVFL bit of the wave's MODE register set, a
+// result beyond the half range is clamped to +-65504 (true infinities stay).  The residual stream and the operands of
+// the wide levels are IEEE half; a trained decoder whose activations leave that range then clips instead of turning
+// into infinities and, through Snake's sine, NaNs.  Called once at the start of every kernel that converts to half.
+__device__ __forceinline__ void fp16_saturate_on()
+{
+    // hwreg(HW_REG_MODE = 1, offset 23, size 1): simm16 = ((size - 1) << 11) | (offset << 6) | id
+    __builtin_amdgcn_s_setreg((0 << 11) | (23 << 6) | 1, 1);
+}
+
 // two fp32 values -> one dword of two halves (lo in bits 0..15), round to nearest even
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)

@@ -75,6 +75,7 @@ struct ConvArgs {
     // bf16 path only: format of the MFMA operand read (x) and of the one emitted (ya), see kernels_bf16.hip
     int in_fmt = OP_BF16, out_fmt = OP_BF16;
     long long in_lo_off = 0, out_lo_off = 0;     // OP_BF16X2: element offset of the lo plane
+    long long small_tile_wgs = 192;              // bf16 path: a launch of at most this many 128 x 128 tiles uses 64 x 64 tiles (0: never)
 };
 
 hipError_t launch_conv_f32(const ConvArgs& a, hipStream_t stream);   // in_alpha must be nullptr (see launch_snake_f32)
@@ -153,10 +154,10 @@ hipError_t launch_stitch(const float* y, float* out, int oc, int S, int n_frames
 // crop + stitch + 16-bit render: planar slot waveform -> d_pcm [n_clips, n_frames*S, oc] interleaved int16
 hipError_t launch_stitch_pcm16(const float* y, int16_t* pcm, int oc, int S, int n_frames, long long total_rows,
                                const Slot* slots, int n_slots, int max_int, hipStream_t stream);
-// window table written on the device (no host copy): the same grid as the host builds for the plan cache, as one
-// group; per_clip windows and clip_frames extended frames per clip
+// window table written on the device (no host copy); per_clip windows and clip_frames extended frames per clip.
+// Windows from index `split` on form the second group: their rows count from `split_row0` (n_clips * per_clip, 0: one group).
 hipError_t launch_plan_slots(Slot* dst, int n_clips, int per_clip, int clip_frames, int n_frames, int frame_begin,
-                             int frame_end, int window, int halo, hipStream_t stream);
+                             int frame_end, int window, int halo, int split, int split_row0, hipStream_t stream);
 // decode gate: dst = src with the windows of clips whose skip flag is set emptied
 hipError_t launch_gate_slots(const Slot* src, Slot* dst, int n, const int* skip, hipStream_t stream);
 // latent similarity filter: per clip mse = mean((a-b)^2) over n elements and the gate mse < threshold

@@ -163,6 +163,7 @@ void pack_bf16(const float* w, int cin, int cout, int ntaps, int stride, int var
 template <int MT, int NT, int KC, int WM, int WN, int MODE, int IN, int EMIT>
 __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
 {
+    fp16_saturate_on();
     constexpr int NTH = 64 * WM * WN;           // threads per workgroup
     constexpr int LDK = KC + 8;                 // padded LDS row (bf16 elements): 16-byte multiple, bank-spread
     // rows of the activation tile: the dilated conv reaches MAXSPAN rows past its NT columns, the 1x1 conv
@@ -482,7 +483,8 @@ template <int MT, int NT, int KC, int WM, int WN>
 static hipError_t launch_variant(const MfmaParams& p, int mode, int in_fmt, int emit, dim3 grid, hipStream_t stream)
 {
     // input format x emitted format: the pairs the layer sequence can ask for.  A layer with hi + lo input never emits
-    // half and one with half input never emits hi + lo (a stack uses one of the two for its wide levels).
+    // half and one with half input never emits hi + lo (a stack uses one of the two for its wide levels); a transposed
+    // conv with plain bf16 input emits either when no residual unit sits between it and a wide block.
 #define DEMON_LAUNCH(MODE_, IN_, EM_) \
     hipLaunchKernelGGL((conv_mfma_kernel<MT, NT, KC, WM, WN, MODE_, IN_, EM_>), grid, dim3(64 * WM * WN), 0, stream, p)
 #define DEMON_CASE(MODE_, IN_, EM_) if (in_fmt == IN_ && emit == EM_) { DEMON_LAUNCH(MODE_, IN_, EM_); return hipGetLastError(); }
@@ -493,7 +495,7 @@ static hipError_t launch_variant(const MfmaParams& p, int mode, int in_fmt, int 
         DEMON_CASE(MODE_RES, OP_BF16X2, 0) DEMON_CASE(MODE_RES, OP_BF16X2, 1) DEMON_CASE(MODE_RES, OP_BF16X2, 2)
         DEMON_CASE(MODE_RES, OP_F16, 0) DEMON_CASE(MODE_RES, OP_F16, 1) DEMON_CASE(MODE_RES, OP_F16, 3)
     } else {
-        DEMON_CASE(MODE_UP, OP_BF16, 0) DEMON_CASE(MODE_UP, OP_BF16, 1)
+        DEMON_CASE(MODE_UP, OP_BF16, 0) DEMON_CASE(MODE_UP, OP_BF16, 1) DEMON_CASE(MODE_UP, OP_BF16, 2) DEMON_CASE(MODE_UP, OP_BF16, 3)
         DEMON_CASE(MODE_UP, OP_BF16X2, 1) DEMON_CASE(MODE_UP, OP_BF16X2, 2)
         DEMON_CASE(MODE_UP, OP_F16, 1) DEMON_CASE(MODE_UP, OP_F16, 3)
     }
@@ -504,12 +506,7 @@ static hipError_t launch_variant(const MfmaParams& p, int mode, int in_fmt, int 
 
 // Launches of the 128 x 128 tile that would leave most CUs without a workgroup (one playback window at the wide, low-rate
 // levels) use a 64 x 64 tile on the same packed weights instead: four times the workgroups, and the same K order, so
-// the results are bit-identical to the large tile's.  DEMON_VAE_SMALL_TILE_WGS overrides the threshold (0: never).
-static const long long g_small_tile_wgs = [] {
-    const char* e = getenv("DEMON_VAE_SMALL_TILE_WGS");
-    return e ? atoll(e) : 192ll;
-}();
-
+// the results are bit-identical to the large tile's.  ConvArgs::small_tile_wgs is the threshold (0: never).
 hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
 {
     if (variant < 0 || variant > 2) return hipErrorInvalidValue;
@@ -554,7 +551,7 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     //  * else column tiles fastest (blockIdx.x): workgroups in flight share one row tile of the weights: mtiles X + W.
     p.pack_ratio = 1;
     bool small_tile = false;
-    if (variant == 0 && ((ncols + v.NT - 1) / v.NT) * (M / v.MT) * a.n_slots <= g_small_tile_wgs) {
+    if (variant == 0 && ((ncols + v.NT - 1) / v.NT) * (M / v.MT) * a.n_slots <= a.small_tile_wgs) {
         small_tile = true;
         v.MT = 64; v.NT = 64; p.pack_ratio = 2;
     }

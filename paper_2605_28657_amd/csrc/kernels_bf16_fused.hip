@@ -58,6 +58,7 @@ void pack_w1_fused(const float* w /*[C][C]*/, int C, uint16_t* dst)
 template <int CH, int TN, bool EMIT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void res_unit_fused_kernel(FusedParams p)
 {
+    fp16_saturate_on();
     constexpr int KC = 64;
     constexpr int LDK = KC + 8;
     constexpr int NT = 4 * 32 * TN;               // four waves side by side in time

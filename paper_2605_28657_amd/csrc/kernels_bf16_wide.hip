@@ -47,6 +47,7 @@ struct WideParams {
 template <bool EMIT>
 __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
 {
+    fp16_saturate_on();
     constexpr int CH = W_CH, KC = W_KC, LDK = W_LDK, NT = W_NT, TM = W_TM;
     constexpr int A_ITERS = W_A_ITERS, X_ITERS = W_X_ITERS, SEGS = W_SEGS, RPP = W_RPP;
     constexpr int AS_BYTES = 2 * CH * LDK * 2, XS_BYTES = W_XR_MAX * LDK * 2;
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
     const int tid = threadIdx.x;
     const int lane = tid & 63, wn = tid >> 6;
     const int j = lane & 31, h = lane >> 5;
-    const int seg = tid % SEGS, xr0 = tid / SEGS;
+    const int seg = tid % SEGS;
 
     const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(p.xa + rowbase * CH, (unsigned)nrows * CH * 2u);
     const __amdgpu_buffer_rsrc_t rs_y = make_rsrc(p.y + rowbase * CH, (unsigned)out_hi * CH * (unsigned)sizeof(hres_t));
@@ -85,8 +86,13 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
     const __amdgpu_buffer_rsrc_t rs_w7 = make_rsrc(p.w7, (unsigned)nstages * (W_A_CH * 16u));
     const __amdgpu_buffer_rsrc_t rs_w1 = make_rsrc(p.w1, (unsigned)W_NCHUNKS * (W_A_CH * 16u));
 
-    const unsigned a_voff = tid * 16u;
-    const unsigned x_voff = ((unsigned)((n0 + minoff + xr0) * CH) + seg * 8u) * 2u;      // may wrap "negative": out of range
+    // Staging pattern.  An LDS row is 80 bytes (20 banks), so the 8 lanes that one cycle of a 16-byte LDS write serves
+    // must not hold two neighbouring rows (rows r and r + 1 overlap in 4 banks): lanes 0..3 of each group of 8 take the
+    // four pieces of row r, lanes 4..7 those of row r + 4, which starts 16 banks further.  A pass of 256 threads covers
+    // 64 rows; srow is the thread's row within a pass.
+    const int srow = 8 * (tid >> 5) + ((tid >> 3) & 3) + 4 * ((tid >> 2) & 1);
+    const unsigned a_voff = (unsigned)(srow * SEGS + seg) * 16u;
+    const unsigned x_voff = ((unsigned)((n0 + minoff + srow) * CH) + seg * 8u) * 2u;     // may wrap "negative": out of range
     constexpr unsigned x_row_step = RPP * CH * 2u;
 
     u32x4 ra[A_ITERS], rb[A_ITERS];     // rb: second set, only for the blocks of the 1x1 weights (requested two ahead)
@@ -98,10 +104,8 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
     };
     auto store_set = [&](const u32x4 (&r)[A_ITERS], int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int it = 0; it < A_ITERS; ++it) {
-            const int q = tid + it * 256;
-            *reinterpret_cast<u32x4*>(&As[buf * CH * LDK + (q / SEGS) * LDK + (q % SEGS) * 8]) = r[it];
-        }
+        for (int it = 0; it < A_ITERS; ++it)
+            *reinterpret_cast<u32x4*>(&As[buf * CH * LDK + (srow + it * RPP) * LDK + seg * 8]) = r[it];
     };
     auto load_a = [&](__amdgpu_buffer_rsrc_t rs, int block) __attribute__((always_inline)) { load_set(ra, rs, block); };
     auto store_a = [&](int buf) __attribute__((always_inline)) { store_set(ra, buf); };
@@ -117,7 +121,7 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
 #pragma unroll
         for (int it = 0; it < X_ITERS; ++it) {
             if (it * RPP >= XR) break;                        // uniform
-            const int xr = xr0 + it * RPP;
+            const int xr = srow + it * RPP;
             if (xr >= W_XR_MAX) continue;
             *reinterpret_cast<u32x4*>(&Xs[xr * LDK + seg * 8]) = rx[it];
         }

@@ -33,6 +33,7 @@ __global__ __launch_bounds__(256) void gather_act_kernel(const T* __restrict__ l
                                                          const float* __restrict__ inv_beta, int c0, int n_frames,
                                                          const Slot* __restrict__ slots)
 {
+    fp16_saturate_on();
     const Slot s = slots[blockIdx.y];
     const int e = blockIdx.x * 256 + threadIdx.x;
     if (e >= s.len * c0) return;
@@ -271,6 +272,7 @@ void head_mfma_kernel(const _Float16* __restrict__ x, float* __restrict__ y,
                                                         int oc, int k, int r, long long total_rows,
                                                         const Slot* __restrict__ slots)
 {
+    fp16_saturate_on();
     constexpr int LDX = CIN + 8;                           // padded LDS row (halfs)
     constexpr int XR_MAX = HM_NT + HEAD_MAXK - 1;
     constexpr int SEGS = CIN / 8, RPP = 256 / SEGS;
@@ -519,10 +521,11 @@ hipError_t launch_gate_slots(const Slot* src, Slot* dst, int n, const int* skip,
 
 // ---------------------------------------------------------------------------------- window table on the device
 // The window grid of section 3.6 written by a kernel: window k of a clip covers frames [begin + k window, ...), is
-// extended by the halo and clamped to the clip; its workspace rows follow those of the windows before it.  One thread
-// per window; the prefix sum over the earlier windows of the clip is a short loop (at most 4096 windows per call).
+// extended by the halo and clamped to the clip; its workspace rows follow those of the windows before it (the windows
+// from `split` on form a second group whose rows count from the group's first).  One thread per window; the prefix
+// sum over the earlier windows of the clip is a short loop (at most 4096 windows per call).
 __global__ __launch_bounds__(256) void plan_slots_kernel(Slot* __restrict__ dst, int n, int per_clip, int clip_frames,
-                                                         int n_frames, int fb, int fe, int window, int halo)
+                                                         int n_frames, int fb, int fe, int window, int halo, int split, int split_row0)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
@@ -542,17 +545,17 @@ __global__ __launch_bounds__(256) void plan_slots_kernel(Slot* __restrict__ dst,
     int lo, hi, b, e;
     extent(k, &lo, &hi, &b, &e);
     Slot s;
-    s.row0 = row; s.len = hi - lo; s.clip = clip; s.lo = lo; s.crop = b - lo; s.n_int = e - b; s.begin = b; s.pad = 0;
+    s.row0 = i >= split ? row - split_row0 : row; s.len = hi - lo; s.clip = clip; s.lo = lo; s.crop = b - lo; s.n_int = e - b; s.begin = b; s.pad = 0;
     dst[i] = s;
 }
 
 hipError_t launch_plan_slots(Slot* dst, int n_clips, int per_clip, int clip_frames, int n_frames, int frame_begin,
-                             int frame_end, int window, int halo, hipStream_t stream)
+                             int frame_end, int window, int halo, int split, int split_row0, hipStream_t stream)
 {
     const long long n = (long long)n_clips * per_clip;
     if (n < 1 || n > 65536) return hipErrorInvalidValue;
     hipLaunchKernelGGL(plan_slots_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, dst, (int)n, per_clip, clip_frames,
-                       n_frames, frame_begin, frame_end, window, halo);
+                       n_frames, frame_begin, frame_end, window, halo, split, split_row0);
     return hipGetLastError();
 }
 

@@ -10,7 +10,7 @@ import torch
 import demon_inputs as di
 import oracle
 from gpu_util import TOL_WINDOWED_VS_FULL, assert_close, to_device
-from paper_2605_28657_amd import DemonVAE
+from paper_2605_28657_amd import DemonVAE, DEMON_VAE_FLAG_NO_FUSED, DEMON_VAE_FLAG_ONE_STREAM
 
 pytestmark = pytest.mark.gpu
 
@@ -55,6 +55,32 @@ def test_single_clip_windowed_full_and_oracle_samples(name, starts):
     assert g.shape == (2, wl.n_frames * S) and np.all(np.isfinite(g)) and np.abs(g).max() <= 1.0
     check_blocks(g, oracle_blocks(weights, lat[0], starts), name)
     vae.close()
+
+
+def test_10s_clip_whole_against_the_oracle_with_every_kernel_variant():
+    """configs[1] element by element over the whole clip (the f64 oracle decodes 10 s in seconds), for the default
+    kernels and for each alternative the config selects: hi + lo bf16 operands on the wide levels, unfused residual
+    units, one stream, no small tiles.  Each variant also reproduces its own full decode bit for bit."""
+    wl = di.WORKLOADS["full_10s_bf16"]
+    weights, lat = di.workload_inputs(wl)
+    ref = oracle.decode(SPEC, weights, lat[0])
+    zt = to_device(lat, "bf16")
+    n_windows = -(-wl.n_frames // wl.window)
+    base = None
+    for name, kw in [("default", {}), ("bf16x2", dict(wide_operands=2)), ("unfused", dict(flags=DEMON_VAE_FLAG_NO_FUSED)),
+                     ("one stream", dict(flags=DEMON_VAE_FLAG_ONE_STREAM)), ("large tiles only", dict(small_tile_wgs=-1))]:
+        vae = DemonVAE(SPEC, weights, dtype="bf16", max_frames=wl.n_frames, max_extended_frames=n_windows * (wl.window + 2 * H), **kw)
+        win = vae.decode_windowed(zt, window=wl.window, halo=-1)
+        full = vae.decode(zt)
+        assert torch.equal(win, full), name
+        g = win[0].cpu().numpy()
+        ma, rl = assert_close(g, ref, "bf16", name)
+        print(f"10 s clip, {name}: max-abs {ma:.3e} rel-L2 {rl:.3e} over {g.size} samples")
+        if name == "default":
+            base = win.clone()
+        elif name in ("one stream", "large tiles only"):
+            assert torch.equal(win, base), name              # same kernels and K order: the same bits
+        vae.close()
 
 
 def test_four_clips_in_one_call():

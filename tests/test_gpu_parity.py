@@ -145,7 +145,9 @@ def test_every_layer_against_oracle_primitives(dtype, spec):
         got = dst.cpu().numpy().reshape(ref.shape)
         ma, rl = errors(got, ref)
         tol = 1e-5 if dtype == "f32" else 1e-2
-        assert rl <= tol, f"layer {i}: rel-L2 {rl:.3e}, max-abs {ma:.3e}"
+        # max-abs against the layer's own magnitude: the output bar (2e-2 at |y| <= 1) scaled to the activation's range
+        tol_abs = (1e-4 if dtype == "f32" else 2e-2) * max(1.0, float(np.abs(ref).max()))
+        assert rl <= tol and ma <= tol_abs, f"layer {i}: rel-L2 {rl:.3e} (tol {tol}), max-abs {ma:.3e} (tol {tol_abs:.3e})"
     vae.tap(-1)
     vae.close()
 
@@ -588,16 +590,91 @@ def test_sliding_playback_window_cycles_the_plan_cache():
         e = min(T, begin + 7)
         assert torch.equal(buf[:, :, begin * S:e * S], full[:, :, begin * S:e * S])
         buf.copy_(full)
-    # a grid that is not cached cannot be captured into a graph; the error names the remedy
-    g = torch.cuda.CUDAGraph()
-    s = torch.cuda.Stream()
-    with torch.cuda.stream(s):
-        g.capture_begin()
-        try:
-            with pytest.raises(pa.DemonError) as ei:
-                vae.decode_windowed(zt, window=5, halo=-1, frame_begin=11, frame_end=16, out=buf)
-        finally:
-            g.capture_end()
-    assert ei.value.status == pa.DEMON_ERR_INVALID_ARG and "capture" in ei.value.message
     torch.cuda.synchronize()
     vae.close()
+
+
+def test_a_recorded_grid_survives_any_number_of_other_grids():
+    """A call recorded into a graph holds the address of its grid's window table.  The entry is pinned: eager calls
+    on more other grids than the cache holds do not evict it, and replays keep decoding the recorded window.  A grid
+    seen for the first time while recording is fine too (its table is written by a kernel inside the graph).  When all
+    entries are pinned a further recorded grid is refused with WORKSPACE."""
+    spec = STACK_V1
+    T, S = 64, spec.total_stride
+    vae, w, z = make(spec, "bf16", T, max_extended_frames=2 * T)
+    zt = to_device(z, "bf16")
+    full = vae.decode(zt)
+    out_graph = torch.zeros_like(full)
+    buf = torch.zeros_like(full)
+    rec = dict(window=5, halo=-1, frame_begin=11, frame_end=21)          # two windows, never seen before the capture
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        vae.decode_windowed(zt, out=out_graph, **rec)
+    for rep in range(3):
+        for begin in range(0, T - 3, 3):                                  # 21 other grids, 16 cache entries
+            vae.decode_windowed(zt, window=3, halo=-1, frame_begin=begin, frame_end=begin + 3, out=buf)
+        out_graph.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_graph[:, :, 11 * S:21 * S], full[:, :, 11 * S:21 * S]), rep
+        assert float(out_graph[:, :, :11 * S].abs().max()) == 0.0 and float(out_graph[:, :, 21 * S:].abs().max()) == 0.0
+        assert torch.equal(buf[:, :, :(T - 4) // 3 * 3 * S], full[:, :, :(T - 4) // 3 * 3 * S])
+    # fill the cache with recorded grids: the 16th distinct recorded grid still fits (one entry is taken above), the next does not
+    graphs = []
+    for i in range(16):
+        gi = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            gi.capture_begin()
+            try:
+                if i < 15:
+                    vae.decode_windowed(zt, window=2, halo=-1, frame_begin=2 * i, frame_end=2 * i + 2, out=buf)
+                else:
+                    with pytest.raises(pa.DemonError) as ei:
+                        vae.decode_windowed(zt, window=2, halo=-1, frame_begin=2 * i, frame_end=2 * i + 2, out=buf)
+            finally:
+                gi.capture_end()
+        torch.cuda.current_stream().wait_stream(s)
+        graphs.append(gi)
+    assert ei.value.status == pa.DEMON_ERR_WORKSPACE and "graph" in ei.value.message
+    # eager calls on cached (pinned) grids still work; a new eager grid has no entry left either
+    vae.decode_windowed(zt, out=out_graph, **rec)
+    with pytest.raises(pa.DemonError) as ei:
+        vae.decode_windowed(zt, window=4, halo=-1, frame_begin=40, frame_end=44, out=buf)
+    assert ei.value.status == pa.DEMON_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    vae.close()
+
+
+@pytest.mark.parametrize("spec", [STACK_V1, STACK_SPLIT, STACK_WIDE])
+def test_values_beyond_the_half_range_saturate(spec):
+    """Weights large enough to push the residual stream (IEEE half in memory) and the half operands of the wide levels
+    far beyond 65504: conversions to half clamp instead of producing infinities, which Snake's sine would turn into
+    NaNs.  There is no parity to check out there (the oracle does not clip); the output must be finite and in tanh's range."""
+    w = di.make_weights(spec, seed=0, bf16=True)
+    for name, t in di.split_weights(spec, w).items():
+        if name.endswith(".weight") and not name.startswith("head."):
+            t *= np.float32(2.0 ** 17)                       # exact in bf16; Snake parameters and biases stay as they are
+    z = np.stack([di.make_latent(spec.latent_channels, 20, 1, bf16=True)])
+    vae = pa.DemonVAE(spec, w, dtype="bf16", max_frames=20)
+    y = vae.decode_windowed(to_device(z, "bf16"), window=8, halo=-1)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(y).all())
+    assert float(y.abs().max()) <= 1.0 and float(y.abs().max()) > 0.0
+    vae.close()
+
+
+def test_transposed_conv_feeding_wide_operands_without_residual_units():
+    """No residual units and widths rising across 512 channels: a transposed conv with plain bf16 input emits the wide
+    operand format of the next block itself."""
+    spec = di.DecoderSpec(32, (2, 2, 2), (256, 512, 64), ())
+    for wide in (1, 2):
+        vae, w, z = make(spec, "bf16", 40, wide_operands=wide)
+        ref = oracle.decode(spec, w, z)
+        zt = to_device(z, "bf16")
+        full = vae.decode(zt).cpu().numpy()
+        win = vae.decode_windowed(zt, window=9, halo=-1).cpu().numpy()
+        assert_close(full, ref, "bf16", f"wide_operands={wide}")
+        assert np.array_equal(win, full)
+        vae.close()

@@ -114,7 +114,7 @@ def test_host_conversion_to_half_rounds_to_nearest_even():
     bit patterns, on every tie between neighbouring halves and its two neighbours, around the subnormal range and at
     the overflow threshold."""
     lib = pa.load_library()
-    f = lib._ZN5demon14f32_to_f16_rneEf
+    f = lib.demon_vae_test_f32_to_f16
     f.argtypes = [ctypes.c_float]; f.restype = ctypes.c_uint16
     rng = np.random.default_rng(0)
     bits = [rng.integers(0, 2 ** 32, 50000, dtype=np.uint64).astype(np.uint32),
@@ -143,8 +143,8 @@ def test_packed_weight_layouts():
     channels); transposed convs in polyphase order; half weights are the bf16-rounded values written as half; the fused
     units' 1x1 weights with rows (slot (mo, j) = channel j C/32 + mo) and K axis (accumulator row order) permuted."""
     lib = pa.load_library()
-    pack = lib._ZN5demon9pack_bf16EPKfiiiiibbPt
-    pack.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 5 + [ctypes.c_bool, ctypes.c_bool, ctypes.c_void_p]
+    pack = lib.demon_vae_test_pack_bf16
+    pack.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 7 + [ctypes.c_void_p]
     pack.restype = None
     bf = lambda a: (di.round_to_bf16(np.asarray(a, dtype=np.float32)).view(np.uint32) >> 16).astype(np.uint16)
     rng = np.random.default_rng(3)
@@ -172,7 +172,7 @@ def test_packed_weight_layouts():
         phi, o = divmod(mu, cout)
         assert np.array_equal(blocks[0, 0, j, mu], bf(wt[:, o, phi + j * s_]))
     # fused units: W1 [C][C]
-    packw1 = lib._ZN5demon13pack_w1_fusedEPKfiPt
+    packw1 = lib.demon_vae_test_pack_w1_fused
     packw1.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]; packw1.restype = None
     for C in (64, 128):
         w1 = rng.standard_normal((C, C)).astype(np.float32)
