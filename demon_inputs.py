@@ -152,6 +152,82 @@ def make_latent(channels: int, frames: int, seed: int, bf16: bool = False) -> np
     return round_to_bf16(z) if bf16 else z
 
 
+# ---------------------------------------------------------------- encoder (the decoder's mirror)
+
+def encoder_weight_layout(spec: DecoderSpec) -> List[Tuple[str, Tuple[int, ...]]]:
+    """Names and shapes of the encoder's parameter tensors in processing order: stem conv from the waveform, then per
+    block from the audio rate down (decoder block index l = nb-1 .. 0) its residual units and the strided conv to the
+    next width (the last one to 2 x latent_channels: mean and log-variance)."""
+    nb = len(spec.strides)
+    c = spec.widths[-1]
+    out: List[Tuple[str, Tuple[int, ...]]] = [("stem.weight", (c, spec.out_channels, spec.head_kernel)), ("stem.bias", (c,))]
+    for l in range(nb - 1, -1, -1):
+        c, s = spec.widths[l], spec.strides[l]
+        cn = spec.widths[l - 1] if l > 0 else 2 * spec.latent_channels
+        for j in range(len(spec.dilations)):
+            p = f"e{l}.r{j}"
+            out += [(f"{p}.a1.alpha", (c,)), (f"{p}.a1.beta", (c,)),
+                    (f"{p}.c1.weight", (c, c, spec.res_kernel)), (f"{p}.c1.bias", (c,)),
+                    (f"{p}.a2.alpha", (c,)), (f"{p}.a2.beta", (c,)),
+                    (f"{p}.c2.weight", (c, c, 1)), (f"{p}.c2.bias", (c,))]
+        out += [(f"e{l}.down.alpha", (c,)), (f"e{l}.down.beta", (c,)),
+                (f"e{l}.down.weight", (cn, c, 2 * s)), (f"e{l}.down.bias", (cn,))]
+    return out
+
+
+def split_encoder_weights(spec: DecoderSpec, flat: np.ndarray) -> dict:
+    """Views of the flat encoder array, by tensor name (no copies, no arithmetic)."""
+    out = {}
+    pos = 0
+    for name, shape in encoder_weight_layout(spec):
+        n = int(np.prod(shape))
+        out[name] = flat[pos:pos + n].reshape(shape)
+        pos += n
+    if pos != flat.size:
+        raise ValueError(f"flat encoder weight array has {flat.size} values, layout needs {pos}")
+    return out
+
+
+def make_encoder_weights(spec: DecoderSpec, seed: int = 100, std: float = 0.02, bf16: bool = False,
+                         snake: str = "lognormal", zero_bias: bool = False, positive: bool = False) -> np.ndarray:
+    """Flat fp32 encoder parameters, drawn like the decoder's (make_weights): conv weights and biases N(0, std), Snake
+    parameters exp(N(0, std)) or U[0.5, 2]; `positive`: |w| scaled to 1/fan-in, for exact support measurements."""
+    rng = np.random.default_rng(seed)
+    parts = []
+    for name, shape in encoder_weight_layout(spec):
+        n = int(np.prod(shape))
+        if name.endswith(".alpha") or name.endswith(".beta"):
+            if snake == "lognormal":
+                v = np.exp(rng.standard_normal(n, dtype=np.float32) * np.float32(std))
+            elif snake == "uniform":
+                v = rng.uniform(0.5, 2.0, n).astype(np.float32)
+            else:
+                raise ValueError(snake)
+        elif name.endswith(".bias"):
+            v = rng.standard_normal(n, dtype=np.float32) * np.float32(std)
+            if zero_bias:
+                v[:] = 0
+        else:
+            v = rng.standard_normal(n, dtype=np.float32) * np.float32(std)
+            if positive:
+                v = (np.abs(v) / np.float32(std) + np.float32(0.5)) / np.float32(shape[1] * shape[2])
+        parts.append(v.astype(np.float32))
+    flat = np.concatenate(parts)
+    return round_to_bf16(flat) if bf16 else flat
+
+
+def make_waveform(channels: int, samples: int, seed: int, bf16: bool = False) -> np.ndarray:
+    """Waveform [channels, samples], N(0, 0.25) clipped to [-1, 1], fp32: the stand-in for audio at the encoder's input."""
+    rng = np.random.default_rng(seed)
+    x = np.clip(rng.standard_normal((channels, samples), dtype=np.float32) * np.float32(0.25), -1.0, 1.0).astype(np.float32)
+    return round_to_bf16(x) if bf16 else x
+
+
+def make_noise(channels: int, frames: int, seed: int) -> np.ndarray:
+    """The N(0, 1) draw of the encoder's sampling step, [channels, frames] fp32: an input of the method, not its arithmetic."""
+    return np.random.default_rng(seed).standard_normal((channels, frames), dtype=np.float32)
+
+
 @dataclass(frozen=True)
 class Workload:
     """One of the benchmark configurations: decoder, latent shape, window grid, seeds."""

@@ -97,6 +97,22 @@ def convT1d(x, W, b, stride, padding, dtype=np.float64):
     return y
 
 
+def conv1d_strided(x, W, b, stride, padding, dtype=np.float64):
+    """Strided Conv1d; W [Cout, Cin, K]; output length floor((L + 2 padding - K) / stride) + 1."""
+    sfx, ct = _sfx(dtype)
+    x = np.ascontiguousarray(x, dtype=dtype)
+    W = np.ascontiguousarray(W, dtype=dtype)
+    b = None if b is None else np.ascontiguousarray(b, dtype=dtype)
+    Cin, L = x.shape
+    Cout, Cin2, K = W.shape
+    assert Cin == Cin2 and L + 2 * padding >= K
+    Lout = (L + 2 * padding - K) // stride + 1
+    y = np.empty((Cout, Lout), dtype=dtype)
+    getattr(_lib(), "oracle_conv1d_strided" + sfx)(_ptr(x, ct), Cin, ctypes.c_long(L), _ptr(W, ct), _ptr(b, ct),
+                                                   Cout, K, int(stride), int(padding), _ptr(y, ct))
+    return y
+
+
 def decode(spec, weights, latent, dtype=np.float64):
     """Full decode.  latent [C0, T] or [n_clips, C0, T] -> [.., out_channels, T * S]."""
     latent = np.asarray(latent)
@@ -239,3 +255,103 @@ def crossfade(prev_tail, next_head):
     n = a.shape[1]
     theta = (np.pi / 2) * (np.arange(n) + 0.5) / n
     return np.cos(theta)[None, :] * a + np.sin(theta)[None, :] * b
+
+
+# ---------------------------------------------------------------- encoder (the mirror path)
+
+def encode_moments(spec, enc_weights, wave, dtype=np.float64):
+    """Full encode to the latent's moments.  wave [channels, T * S] or [n_clips, channels, T * S] ->
+    [.., 2 C0, T]: rows 0..C0-1 the mean, rows C0..2C0-1 the log-variance.  The encoder is the decoder's mirror
+    (section 3.7 only names the encode engine): stem conv from the waveform, then per block from the audio rate
+    down the residual units and Snake -> strided conv (kernel 2s, stride s, padding s/2)."""
+    wave = np.asarray(wave)
+    if wave.ndim == 3:
+        return np.stack([encode_moments(spec, enc_weights, x, dtype) for x in wave])
+    sfx, ct = _sfx(dtype)
+    w = np.ascontiguousarray(enc_weights, dtype=dtype)
+    x = np.ascontiguousarray(wave, dtype=dtype)
+    ch, n = x.shape
+    S = spec.total_stride
+    assert ch == spec.out_channels and n % S == 0 and n > 0
+    T = n // S
+    out = np.empty((2 * spec.latent_channels, T), dtype=dtype)
+    IntArr = lambda v: (ctypes.c_int * max(len(v), 1))(*v)
+    rc = getattr(_lib(), "oracle_encode" + sfx)(
+        spec.latent_channels, len(spec.strides), IntArr(spec.strides), IntArr(spec.widths),
+        len(spec.dilations), IntArr(spec.dilations), spec.res_kernel, spec.head_kernel,
+        spec.out_channels, _ptr(w, ct), _ptr(x, ct), ctypes.c_long(T), _ptr(out, ct))
+    if rc != 0:
+        raise ValueError("oracle_encode rejected the encoder description")
+    return out
+
+
+def sample_latent(moments, eps):
+    """The sampling step on the output moments (Table III's note names it, no formula is printed).  Reading taken
+    here, the usual diagonal-Gaussian posterior: z = mean + exp(logvar / 2) * eps, eps ~ N(0, 1) drawn by the caller."""
+    m = np.asarray(moments, dtype=np.float64)
+    c0 = m.shape[-2] // 2
+    mean, logvar = m[..., :c0, :], m[..., c0:, :]
+    return mean + np.exp(0.5 * logvar) * np.asarray(eps, dtype=np.float64)
+
+
+def encode_moments_windowed(spec, enc_weights, wave, window, halo, frame_begin=0, frame_end=None, dtype=np.float64):
+    """Windowed encode of latent frames [frame_begin, frame_end): the three steps of section 3.6 in the other
+    direction -- extend the window's samples by `halo` frames of samples on both sides (clamped to the clip), encode
+    the extended region as if it were a whole clip, trim the halo frames.  Returns [.., 2 C0, frame_end - frame_begin]."""
+    wave = np.asarray(wave)
+    if wave.ndim == 3:
+        return np.stack([encode_moments_windowed(spec, enc_weights, x, window, halo, frame_begin, frame_end, dtype)
+                         for x in wave])
+    S = spec.total_stride
+    T = wave.shape[1] // S
+    if frame_end is None:
+        frame_end = T
+    pieces = []
+    for b, e in window_grid(frame_begin, frame_end, window):
+        lo, hi = max(0, b - halo), min(T, e + halo)
+        m = encode_moments(spec, enc_weights, wave[:, lo * S:hi * S], dtype)
+        pieces.append(m[:, b - lo:e - lo])
+    return np.concatenate(pieces, axis=1)
+
+
+def _encoder_layers(spec):
+    """(kind, kernel, stride_or_dilation, padding) of the encoder's index-moving layers, input to output."""
+    out = [("conv", spec.head_kernel, 1, 0)]
+    for s in reversed(spec.strides):
+        for d in spec.dilations:
+            out.append(("conv", spec.res_kernel, d, 0))
+        out.append(("convS", 2 * s, s, s // 2))
+    return out
+
+
+def encoder_backward_interval(spec, a: int, b: int) -> Tuple[int, int]:
+    """Waveform samples [lo, hi] that latent frames [a, b] depend on (clip edges ignored): a strided conv reads
+    inputs n s - p .. n s - p + K - 1 for output n, an odd conv of dilation d reaches d (K-1)/2 further."""
+    for kind, K, sd, p in reversed(_encoder_layers(spec)):
+        if kind == "conv":
+            r = sd * (K - 1) // 2
+            a, b = a - r, b + r
+        else:
+            a, b = a * sd - p, b * sd - p + K - 1
+    return a, b
+
+
+def encoder_forward_interval(spec, a: int, b: int) -> Tuple[int, int]:
+    """Latent frames [lo, hi] that waveform samples [a, b] can influence (clip edges ignored)."""
+    for kind, K, sd, p in _encoder_layers(spec):
+        if kind == "conv":
+            r = sd * (K - 1) // 2
+            a, b = a - r, b + r
+        else:
+            # output n reads input m when 0 <= m - n s + p <= K - 1
+            a, b = -((-(a + p - K + 1)) // sd), (b + p) // sd
+    return a, b
+
+
+def encoder_receptive_field(spec) -> Tuple[int, int]:
+    """(halo_left, halo_right) of the windowed encode in latent frames: how many frames' worth of samples before and
+    after a frame its moments depend on."""
+    S = spec.total_stride
+    f = 1000
+    lo, hi = encoder_backward_interval(spec, f, f)
+    return -((lo - f * S) // S), (hi - (f * S + S - 1) + S - 1) // S
