@@ -237,6 +237,68 @@ DEMON_API demon_status demon_vae_decode_windowed_gated(demon_vae* vae, const voi
                                              const int* d_skip, float* d_out, void* stream);
 
 /*
+ * ---- The windowed encode (the mirror path; section 3.7 names separate encode and decode engines, Table III times
+ * the encode and notes its sampling step on the output moments).  The paper prints no encoder layers; the encoder
+ * here is the mirror of the decoder the config describes:
+ *   stem:                        Conv1d(head_kernel) from the out_channels-channel waveform to widths[n_blocks-1]
+ *   for l = n_blocks .. 1:       n_res residual units of width widths[l-1] (as in the decoder), then
+ *                                Snake -> Conv1d(kernel 2 s_l, stride s_l, padding s_l/2) to widths[l-2],
+ *                                and for l = 1 to 2 x latent_channels: the moments (mean | log-variance)
+ *   sampling step:               z = mean + exp(logvar / 2) * eps, eps ~ N(0, 1) supplied by the caller
+ * S = prod(strides) samples make one latent frame, exactly.  Windowed: the samples of every window of latent frames
+ * are extended by `halo` frames' worth of samples on both sides (clamped to the clip), the extended windows are
+ * encoded as one batch, each as if it were a whole clip, and the halo frames are trimmed; with a halo of at least the
+ * encoder's receptive field the result equals the full encode.
+ */
+
+/*
+ * Number of fp32 values demon_vae_create_encoder expects: stem.weight[C, out_channels, head_kernel], stem.bias[C]
+ * (C = widths[n_blocks-1]); then for l = n_blocks .. 1, C = widths[l-1]: per residual unit the eight tensors of a
+ * decoder unit; then down.alpha[C], down.beta[C], down.weight[C_out, C, 2 s_l], down.bias[C_out] with
+ * C_out = widths[l-2], and 2 latent_channels for l = 1.  Host only.  Returns 0 for an invalid description.
+ */
+DEMON_API size_t demon_vae_encoder_weight_count(const demon_vae_config* cfg);
+
+/*
+ * Receptive field of the encoder (host only): the moments of latent frame f depend on the waveform samples
+ * [f S - *samples_left, f S + S - 1 + *samples_right], i.e. on *halo_left / *halo_right further frames' worth of
+ * samples (the sample counts rounded up to whole frames).  Interval propagation backwards from the moments: a strided
+ * conv reads inputs n s - s/2 .. n s + 3s/2 - 1 for output n, a k-tap conv of dilation d widens by d (k-1)/2.
+ * samples_left / samples_right may be NULL.
+ */
+DEMON_API demon_status demon_vae_encoder_rf_from_config(const demon_vae_config* cfg, int* halo_left, int* halo_right,
+                                                        long long* samples_left, long long* samples_right);
+
+/*
+ * Builds the encoder on the current HIP device; arguments, limits and errors as for demon_vae_create
+ * (max_frames, max_clips, max_extended_frames size its workspace in latent frames), with the weight order of
+ * demon_vae_encoder_weight_count.  UNSUPPORTED also for wide_operands = 2 and a stem width that is not a multiple
+ * of 8.  The handle is freed with demon_vae_destroy; demon_vae_receptive_field returns the encoder's halo; the decode
+ * entry points reject it (INVALID_ARG), as the encode entry points reject a decoder.
+ */
+DEMON_API demon_status demon_vae_create_encoder(const demon_vae_config* cfg, const float* host_weights, size_t n_floats,
+                                                demon_vae** out);
+
+/*
+ * Windowed encode of latent frames [frame_begin, frame_end) of every clip.
+ *   d_wave    : device, fp32, [n_clips, out_channels, n_frames * S] planar (the decoder's output layout).  Read only.
+ *   d_eps     : device, fp32, [n_clips, latent_channels, n_frames], the N(0, 1) draw of the sampling step; NULL: z = mean.
+ *   d_moments : device, fp32, [n_clips, 2 latent_channels, n_frames] (channels 0 .. C0-1 mean, C0 .. 2 C0-1 log-variance), or NULL.
+ *   d_latent  : device, [n_clips, latent_channels, n_frames], frames fastest; fp32 for DEMON_F32, bf16 for DEMON_BF16
+ *               (the layout demon_vae_decode reads), or NULL.  Not both outputs NULL.
+ * Only frames [frame_begin, frame_end) of the outputs are written.  `halo` in latent frames; -1 = the encoder's
+ * receptive field.  Asynchronous on `stream`, allocates nothing; window grids are cached as for the decode.
+ * Errors as for demon_vae_decode_windowed.
+ */
+DEMON_API demon_status demon_vae_encode_windowed(demon_vae* enc, const float* d_wave, int n_clips, int n_frames,
+                                                 int frame_begin, int frame_end, int window, int halo,
+                                                 const float* d_eps, float* d_moments, void* d_latent, void* stream);
+
+/* Full encode: every clip is one window covering [0, n_frames) with no halo. */
+DEMON_API demon_status demon_vae_encode(demon_vae* enc, const float* d_wave, int n_clips, int n_frames, const float* d_eps,
+                                        float* d_moments, void* d_latent, void* stream);
+
+/*
  * For callers that cannot allocate device memory or may not let a library hold a workspace of its own choosing --
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc: demon_vae_decode_windowed with
  * everything the call needs besides its inputs and outputs (window table, activation buffers, window waveforms) in

@@ -1,5 +1,6 @@
 """MI355X-native windowed VAE decode (paper section 3.6): ctypes binding over libdemon_vae.so."""
-from .binding import (DemonVAE, DemonError, load_library, demon_vae_create, demon_vae_destroy,  # noqa: F401
+from .binding import (DemonVAE, DemonVAEEncoder, DemonError, demon_vae_create_encoder, demon_vae_encode, demon_vae_encode_windowed,
+                      demon_vae_encoder_weight_count, demon_vae_encoder_rf_from_config, load_library, demon_vae_create, demon_vae_destroy,  # noqa: F401
                       demon_vae_decode, demon_vae_decode_windowed, demon_vae_decode_windowed_pcm16, demon_vae_decode_windowed_gated,
                       demon_vae_decode_windowed_static,
                       demon_vae_receptive_field,

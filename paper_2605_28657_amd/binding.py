@@ -71,6 +71,12 @@ def load_library() -> ctypes.CDLL:
     lib.demon_vae_decode_windowed_pcm16.argtypes = lib.demon_vae_decode_windowed.argtypes
     lib.demon_vae_decode_windowed_static.argtypes = lib.demon_vae_decode_windowed.argtypes
     lib.demon_vae_decode_windowed_gated.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 6 + [ctypes.c_void_p] * 3
+    lib.demon_vae_encoder_weight_count.restype = ctypes.c_size_t
+    lib.demon_vae_encoder_weight_count.argtypes = [P(_Config)]
+    lib.demon_vae_encoder_rf_from_config.argtypes = [P(_Config), P(ctypes.c_int), P(ctypes.c_int), P(ctypes.c_longlong), P(ctypes.c_longlong)]
+    lib.demon_vae_create_encoder.argtypes = lib.demon_vae_create.argtypes
+    lib.demon_vae_encode_windowed.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 6 + [ctypes.c_void_p] * 4
+    lib.demon_vae_encode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int] + [ctypes.c_void_p] * 4
     lib.demon_vae_latent_similarity.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_int,
                                                 ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.demon_vae_crossfade.argtypes = [ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p, ctypes.c_longlong,
@@ -154,6 +160,43 @@ def demon_vae_create(spec, weights: np.ndarray, dtype: int, max_frames: int, max
     _check(load_library().demon_vae_create(ctypes.byref(cfg), w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
                                            w.size, ctypes.byref(handle)))
     return handle.value
+
+
+def demon_vae_encoder_weight_count(spec) -> int:
+    cfg, _keep = config_from_spec(spec)
+    return int(load_library().demon_vae_encoder_weight_count(ctypes.byref(cfg)))
+
+
+def demon_vae_encoder_rf_from_config(spec) -> Tuple[int, int, int, int]:
+    """(halo_left, halo_right) in latent frames and (samples_left, samples_right)."""
+    cfg, _keep = config_from_spec(spec)
+    l, r = ctypes.c_int(), ctypes.c_int()
+    sl, sr = ctypes.c_longlong(), ctypes.c_longlong()
+    _check(load_library().demon_vae_encoder_rf_from_config(ctypes.byref(cfg), ctypes.byref(l), ctypes.byref(r),
+                                                           ctypes.byref(sl), ctypes.byref(sr)))
+    return l.value, r.value, sl.value, sr.value
+
+
+def demon_vae_create_encoder(spec, weights: np.ndarray, dtype: int, max_frames: int, max_clips: int = 1,
+                             max_extended_frames: int = 0, wide_operands: int = 0, flags: int = 0, small_tile_wgs: int = 0) -> int:
+    """Returns the opaque handle of an encoder.  `weights`: flat fp32 host array in the encoder's order."""
+    cfg, _keep = config_from_spec(spec, dtype, max_frames, max_clips, max_extended_frames, wide_operands, flags, small_tile_wgs)
+    w = np.ascontiguousarray(weights, dtype=np.float32)
+    handle = ctypes.c_void_p()
+    _check(load_library().demon_vae_create_encoder(ctypes.byref(cfg), w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+                                                   w.size, ctypes.byref(handle)))
+    return handle.value
+
+
+def demon_vae_encode_windowed(handle: int, d_wave: int, n_clips: int, n_frames: int, frame_begin: int, frame_end: int,
+                              window: int, halo: int, d_eps: int, d_moments: int, d_latent: int, stream: int = 0):
+    _check(load_library().demon_vae_encode_windowed(handle, d_wave, n_clips, n_frames, frame_begin, frame_end, window, halo,
+                                                    d_eps, d_moments, d_latent, stream))
+
+
+def demon_vae_encode(handle: int, d_wave: int, n_clips: int, n_frames: int, d_eps: int, d_moments: int, d_latent: int,
+                     stream: int = 0):
+    _check(load_library().demon_vae_encode(handle, d_wave, n_clips, n_frames, d_eps, d_moments, d_latent, stream))
 
 
 def demon_vae_destroy(handle: Optional[int]):
@@ -370,3 +413,76 @@ class DemonVAE:
     def tap(self, layer: int, dst=None):
         demon_vae_debug_tap(self.handle, layer, dst.data_ptr() if dst is not None else 0,
                             dst.numel() if dst is not None else 0)
+
+
+class DemonVAEEncoder:
+    """Convenience wrapper of an encoder handle: marshals torch tensors.  No arithmetic happens here."""
+
+    def __init__(self, spec, weights: np.ndarray, dtype: str = "bf16", max_frames: int = 1500, max_clips: int = 1,
+                 max_extended_frames: int = 0, flags: int = 0, small_tile_wgs: int = 0):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("DemonVAEEncoder needs a HIP device; there is no CPU fallback")
+        self.spec = spec
+        self.dtype = {"bf16": DEMON_BF16, "f32": DEMON_F32}[dtype]
+        self.latent_dtype = torch.bfloat16 if self.dtype == DEMON_BF16 else torch.float32
+        self.S = 1
+        for s in spec.strides:
+            self.S *= s
+        self.handle = demon_vae_create_encoder(spec, weights, self.dtype, max_frames, max_clips, max_extended_frames,
+                                               0, flags, small_tile_wgs)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            import torch
+            torch.cuda.synchronize()
+            demon_vae_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def receptive_field(self) -> Tuple[int, int]:
+        return demon_vae_receptive_field(self.handle)
+
+    def set_timing(self, level: int):
+        demon_vae_set_timing(self.handle, level)
+
+    def get_timing(self) -> List[float]:
+        return demon_vae_get_timing(self.handle)
+
+    def encode_windowed(self, wave, window: int, halo: int = -1, frame_begin: int = 0, frame_end: Optional[int] = None,
+                        eps=None, moments=None, latent=None):
+        """wave: fp32 [n_clips, channels, T * S] (or [channels, T * S]).  Returns (moments, latent); pass the tensors
+        to write into, or get new ones (zero outside the encoded range)."""
+        import torch
+        if wave.dim() == 2:
+            wave = wave[None]
+        assert wave.is_cuda and wave.dtype == torch.float32 and wave.is_contiguous()
+        n_clips, ch, n = wave.shape
+        assert ch == self.spec.out_channels and n % self.S == 0
+        t = n // self.S
+        c0 = self.spec.latent_channels
+        if moments is None:
+            moments = torch.zeros((n_clips, 2 * c0, t), dtype=torch.float32, device=wave.device)
+        if latent is None:
+            latent = torch.zeros((n_clips, c0, t), dtype=self.latent_dtype, device=wave.device)
+        assert moments.is_contiguous() and moments.dtype == torch.float32 and tuple(moments.shape) == (n_clips, 2 * c0, t)
+        assert latent.is_contiguous() and latent.dtype == self.latent_dtype and tuple(latent.shape) == (n_clips, c0, t)
+        if eps is not None:
+            assert eps.is_cuda and eps.dtype == torch.float32 and eps.is_contiguous() and tuple(eps.shape) == (n_clips, c0, t)
+        if frame_end is None:
+            frame_end = t
+        demon_vae_encode_windowed(self.handle, wave.data_ptr(), n_clips, t, frame_begin, frame_end, window, halo,
+                                  eps.data_ptr() if eps is not None else 0, moments.data_ptr(), latent.data_ptr(),
+                                  torch.cuda.current_stream().cuda_stream)
+        return moments, latent
+
+    def encode(self, wave, eps=None):
+        if wave.dim() == 2:
+            wave = wave[None]
+        t = wave.shape[2] // self.S
+        return self.encode_windowed(wave, window=t, halo=0, eps=eps)

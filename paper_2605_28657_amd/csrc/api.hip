@@ -40,6 +40,7 @@ const long long g_env_small_tile_wgs = [] {
 
 struct ConvLayer {
     int cin = 0, cout = 0, ntaps = 0, dil = 1, stride = 0, variant = -1;
+    int down = 0;                      // s > 0: strided Conv1d(kernel 2s, stride s, padding s/2) of the encoder (ntaps = 2s)
     int in_fmt = OP_BF16;              // bf16 path: format of the activation operand (the weights are packed to match)
     bool generic = true;               // bf16 path: runs on launch_conv_bf16 (row order of its accumulator tiles)
     int margin = 0;                    // output rows beyond the interior that later layers read
@@ -52,7 +53,11 @@ struct ConvLayer {
 // fused: one kernel per unit that reads the half residual stream itself (64, 128 channels);
 // wide: one kernel per unit that reads the pre-activated operand (256 channels); else two kernels
 struct ResUnit { ConvLayer dilated, pointwise; bool fused = false, wide = false; const uint16_t* w1_fused = nullptr; };
+// up: the block's resampling layer -- the decoder's transposed conv (before the units) or the encoder's strided conv (after them)
 struct Block { ConvLayer up; std::vector<ResUnit> res; };
+// The layer sequence in processing order: a resampling convolution (conv) or a residual unit (unit), and the layer that
+// takes this step's output as an activated MFMA operand (bf16 path; nullptr: the next layer reads the residual stream).
+struct Step { const ConvLayer* conv = nullptr; const ResUnit* unit = nullptr; const ConvLayer* consumer = nullptr; };
 
 struct Plan {
     bool valid = false;
@@ -120,7 +125,12 @@ struct demon_vae {
     long long small_tile_wgs = 192;    // bf16 path: launches of at most this many 128 x 128 tiles use 64 x 64 tiles
 
     void* d_params = nullptr;          // one allocation: all packed weights, biases, Snake parameters
-    std::vector<Block> blocks;
+    std::vector<Block> blocks;         // in processing order (encoder: from the audio rate down)
+    std::vector<Step> steps;
+    const ConvLayer* first_consumer = nullptr;     // bf16 path: the layer whose operand the gather (stem) writes
+    bool encoder = false;              // the mirror path: waveform -> moments / latent
+    const float* stem_w = nullptr;  const float* stem_bias = nullptr;      // encoder stem, fp32 [k][channels][C]
+    int stem_cout = 0, stem_margin = 0;
     const float* head_w = nullptr;  const float* head_bias = nullptr;
     const uint16_t* head_wfrag = nullptr;   // bf16 path: half-precision MFMA fragments of the head weights (or nullptr)
     const float* head_alpha = nullptr;  const float* head_inv_beta = nullptr;
@@ -191,7 +201,7 @@ size_t pack_conv(Arena& ar, const float* w, ConvLayer& L, bool bf16)
     if (bf16) {
         const size_t n = packed_bf16_count(L.cin, L.cout, L.ntaps, L.stride, L.variant);
         const size_t off = ar.reserve(n * 2);
-        pack_bf16(w, L.cin, L.cout, L.ntaps, L.stride, L.variant, L.in_fmt == OP_F16, L.generic, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
+        pack_bf16(w, L.cin, L.cout, L.ntaps, L.stride, L.variant, L.in_fmt == OP_F16, L.generic, reinterpret_cast<uint16_t*>(ar.bytes.data() + off), L.down);
         return off;
     }
     const size_t n = packed_f32_count(L.cin, L.cout, L.ntaps, L.stride);
@@ -308,17 +318,28 @@ bool wants_two_groups(const demon_vae* v)
     return v->dtype == DEMON_BF16 && v->stream2 && v->timing < 2 && !(v->tap_layer >= 0 && v->tap_dst);
 }
 
-// The launch sequence of one decode call over the windows of `plan`, in the memory of `ws`.
-demon_status run_decode(demon_vae* v, const Workspace& ws, const Plan* plan, const void* d_latent, int n_frames,
-                        const int* d_skip, float* d_out, int16_t* d_pcm, hipStream_t stream)
+// What one call reads and writes besides the handle's own memory.
+struct Io {
+    // decode: latent in, waveform (fp32 planar or interleaved int16) out, optional per-clip skip flags
+    const void* d_latent = nullptr; const int* d_skip = nullptr; float* d_out = nullptr; int16_t* d_pcm = nullptr;
+    // encode: waveform in, moments and / or sampled latent out, optional noise of the sampling step
+    const float* d_wave = nullptr; const float* d_eps = nullptr; float* d_moments = nullptr; void* d_zout = nullptr;
+    int n_frames = 0;
+};
+
+// The launch sequence of one call over the windows of `plan`, in the memory of `ws`: the decoder's
+// gather | layers | head | stitch, or the encoder's stem | layers | sampling step.
+demon_status run_pass(demon_vae* v, const Workspace& ws, const Plan* plan, const Io& io, hipStream_t stream)
 {
     const bool bf = v->dtype == DEMON_BF16;
+    const bool enc = v->encoder;
     const bool dual = wants_two_groups(v);
+    const int n_frames = io.n_frames;
     const Slot* slots = plan->d_slots;
     const int ns = plan->n_slots, ml = plan->max_len;
-    if (d_skip) {
+    if (io.d_skip) {
         // gated decode: every kernel reads a copy of the table in which the skipped clips' windows are empty
-        HIP_TRY(launch_gate_slots(plan->d_slots, ws.slot_gated, ns, d_skip, stream), "decode gate");
+        HIP_TRY(launch_gate_slots(plan->d_slots, ws.slot_gated, ns, io.d_skip, stream), "decode gate");
         slots = ws.slot_gated;
     }
 
@@ -340,14 +361,15 @@ demon_status run_decode(demon_vae* v, const Workspace& ws, const Plan* plan, con
         if (!marks_on || v->timing < level || v->n_marks >= v->marks_per_call) return hipSuccess;
         return hipEventRecord(v->events[ring_base + v->n_marks++], stream);
     };
-    // level 1 marks: start, after gather, after the last convolution, after head, after stitch.
+    // level 1 marks: start, after gather (stem), after the last convolution, after head (sampling step), after stitch.
     // level 2 adds a mark after every convolution launch.
     HIP_TRY(mark(1), "event");
 
+    const int S = v->st.total_stride();
     void* cur = ws.buf[0];
     void* other = ws.buf[1];
-    int r = 1, layer_id = 0;
-    const size_t n_blocks = v->blocks.size();
+    int r = enc ? S : 1, layer_id = 0;
+    const size_t n_steps = v->steps.size();
     const long long lo_off = (long long)ws.act_elems;        // lo plane of a split bf16 tensor
     auto tap = [&](const void* x, int c) -> hipError_t {
         const int id = layer_id++;
@@ -363,16 +385,22 @@ demon_status run_decode(demon_vae* v, const Workspace& ws, const Plan* plan, con
         a.in_alpha = L.in_alpha; a.in_inv_beta = L.in_inv_beta;
         a.out_alpha = L.out_alpha; a.out_inv_beta = L.out_inv_beta;
         a.slots = gs; a.n_slots = gn; a.max_len = ml; a.max_int = plan->max_int; a.margin = L.margin; a.r_in = r;
-        a.cin = L.cin; a.cout = L.cout; a.ntaps = L.ntaps; a.dil = L.dil; a.stride = L.stride;
+        a.cin = L.cin; a.cout = L.cout; a.ntaps = L.ntaps; a.dil = L.dil; a.stride = L.stride; a.down = L.down;
         a.in_fmt = L.in_fmt;
         a.in_lo_off = a.out_lo_off = lo_off;
         a.small_tile_wgs = v->small_tile_wgs;
         return a;
     };
+    // samples per frame after a resampling layer
+    auto resampled = [](int rate, const ConvLayer& L) { return L.down > 0 ? rate / L.down : rate * L.stride; };
 
     if (!bf) {
         // ---- fp32 path: Snake on a layer's input runs as its own kernel into buf[2]
-        HIP_TRY(launch_gather(d_latent, (float*)cur, v->st.c0, n_frames, false, slots, ns, ml, stream), "gather");
+        if (enc)
+            HIP_TRY(launch_stem(io.d_wave, cur, false, nullptr, 0, v->stem_w, v->stem_bias, nullptr, nullptr, v->st.out_channels,
+                                v->stem_cout, v->st.head_kernel, S, n_frames, v->stem_margin, slots, ns, ml, plan->max_int, stream), "stem");
+        else
+            HIP_TRY(launch_gather(io.d_latent, (float*)cur, v->st.c0, n_frames, false, slots, ns, ml, stream), "gather");
         HIP_TRY(mark(1), "event");
         auto run_conv = [&](const ConvLayer& L, const void* x, void* y, const void* res) -> hipError_t {
             ConvArgs a = conv_args(L, x, y, res);
@@ -385,20 +413,21 @@ demon_status run_decode(demon_vae* v, const Workspace& ws, const Plan* plan, con
             }
             return launch_conv_f32(a, stream);
         };
-        for (size_t bi = 0; bi < n_blocks; ++bi) {
-            const Block& B = v->blocks[bi];
-            const bool last_block = bi + 1 == n_blocks;
-            HIP_TRY(run_conv(B.up, cur, other, nullptr), "transposed convolution");
-            HIP_TRY(mark(last_block && B.res.empty() ? 1 : 2), "event");
-            std::swap(cur, other);
-            r *= B.up.stride;
-            HIP_TRY(tap(cur, B.up.cout), "debug tap");
-            for (size_t ui = 0; ui < B.res.size(); ++ui) {
-                const ResUnit& U = B.res[ui];
+        for (size_t si = 0; si < n_steps; ++si) {
+            const Step& T = v->steps[si];
+            const bool last = si + 1 == n_steps;
+            if (T.conv) {
+                HIP_TRY(run_conv(*T.conv, cur, other, nullptr), "resampling convolution");
+                HIP_TRY(mark(last ? 1 : 2), "event");
+                std::swap(cur, other);
+                r = resampled(r, *T.conv);
+                HIP_TRY(tap(cur, T.conv->cout), "debug tap");
+            } else {
+                const ResUnit& U = *T.unit;
                 HIP_TRY(run_conv(U.dilated, cur, other, nullptr), "dilated convolution");
                 HIP_TRY(mark(2), "event");
                 HIP_TRY(run_conv(U.pointwise, other, cur, cur), "pointwise convolution");   // in place on the residual stream
-                HIP_TRY(mark(last_block && ui + 1 == B.res.size() ? 1 : 2), "event");
+                HIP_TRY(mark(last ? 1 : 2), "event");
                 HIP_TRY(tap(cur, U.pointwise.cout), "debug tap");
             }
         }
@@ -409,80 +438,81 @@ demon_status run_decode(demon_vae* v, const Workspace& ws, const Plan* plan, con
         uint16_t* acur = (uint16_t*)ws.buf[3];
         uint16_t* aoth = (uint16_t*)ws.buf[4];
         uint16_t* mid = (uint16_t*)ws.buf[2];
-        // the layer that consumes the output of block bi's unit ui (ui = -1: of its transposed conv);
-        // nullptr when that layer reads the residual stream itself (narrow fused unit, head)
-        auto consumer = [&](size_t bi, int ui) -> const ConvLayer* {
-            const Block& B = v->blocks[bi];
-            if (ui + 1 < (int)B.res.size()) return B.res[ui + 1].fused ? nullptr : &B.res[ui + 1].dilated;
-            return bi + 1 < n_blocks ? &v->blocks[bi + 1].up : nullptr;
-        };
         for (int gi = 0; gi < plan->n_groups; ++gi) {
             select_group(gi, stream);
-            const ConvLayer& U0 = v->blocks[0].up;
-            HIP_TRY(launch_gather(d_latent, nullptr, v->st.c0, n_frames, true, gs, gn, ml, stream, (uint16_t*)ws.buf[3] + goff(),
-                                  U0.in_fmt, lo_off, U0.in_alpha, U0.in_inv_beta), "gather");
+            if (enc) {
+                const ConvLayer* C = v->first_consumer;
+                HIP_TRY(launch_stem(io.d_wave, (uint16_t*)ws.buf[0] + goff(), true, C ? (uint16_t*)ws.buf[3] + goff() : nullptr,
+                                    C ? C->in_fmt : 0, v->stem_w, v->stem_bias, C ? C->in_alpha : nullptr, C ? C->in_inv_beta : nullptr,
+                                    v->st.out_channels, v->stem_cout, v->st.head_kernel, S, n_frames, v->stem_margin, gs, gn, ml,
+                                    plan->max_int, stream), "stem");
+            } else {
+                const ConvLayer& U0 = *v->first_consumer;
+                HIP_TRY(launch_gather(io.d_latent, nullptr, v->st.c0, n_frames, true, gs, gn, ml, stream, (uint16_t*)ws.buf[3] + goff(),
+                                      U0.in_fmt, lo_off, U0.in_alpha, U0.in_inv_beta), "gather");
+            }
         }
         HIP_TRY(mark(1), "event");
         auto layers = [&]() -> demon_status {
         cur = (uint16_t*)ws.buf[0] + goff(); other = (uint16_t*)ws.buf[1] + goff();      // half: 2 bytes
         acur = (uint16_t*)ws.buf[3] + goff(); aoth = (uint16_t*)ws.buf[4] + goff(); mid = (uint16_t*)ws.buf[2] + goff();
-        r = 1; layer_id = 0;
-        for (size_t bi = 0; bi < n_blocks; ++bi) {
-            const Block& B = v->blocks[bi];
-            const bool last_block = bi + 1 == n_blocks;
-            {
-                ConvArgs a = conv_args(B.up, acur, other, nullptr);
-                const ConvLayer* C = consumer(bi, -1);
+        r = enc ? S : 1; layer_id = 0;
+        for (size_t si = 0; si < n_steps; ++si) {
+            const Step& T = v->steps[si];
+            const bool last = si + 1 == n_steps;
+            // the layer that consumes this step's output through an activated operand; nullptr when that layer reads the
+            // residual stream itself (narrow fused unit, head, sampling step)
+            const ConvLayer* C = T.consumer;
+            if (T.conv) {
+                ConvArgs a = conv_args(*T.conv, acur, other, nullptr);
                 if (C) { a.ya = aoth; a.out_alpha = C->in_alpha; a.out_inv_beta = C->in_inv_beta; a.out_fmt = C->in_fmt; }
-                HIP_TRY(launch_conv_bf16(a, B.up.variant, gst), "transposed convolution");
+                HIP_TRY(launch_conv_bf16(a, T.conv->variant, gst), "resampling convolution");
                 if (C) std::swap(acur, aoth);
+                HIP_TRY(mark(last ? 1 : 2), "event");
+                std::swap(cur, other);
+                r = resampled(r, *T.conv);
+                HIP_TRY(tap(cur, T.conv->cout), "debug tap");
+                continue;
             }
-            HIP_TRY(mark(last_block && B.res.empty() ? 1 : 2), "event");
-            std::swap(cur, other);
-            r *= B.up.stride;
-            HIP_TRY(tap(cur, B.up.cout), "debug tap");
-            for (size_t ui = 0; ui < B.res.size(); ++ui) {
-                const ResUnit& U = B.res[ui];
-                const ConvLayer* C = consumer(bi, (int)ui);
-                if (U.fused) {
-                    FusedArgs f;
-                    f.x = cur; f.y = other;
-                    if (C) { f.ya = acur; f.a3 = C->in_alpha; f.ib3 = C->in_inv_beta; }
-                    f.w7 = (const uint16_t*)U.dilated.w; f.w1 = U.w1_fused;
-                    f.b7 = U.dilated.bias; f.b1 = U.pointwise.bias;
-                    f.a1 = U.dilated.in_alpha; f.ib1 = U.dilated.in_inv_beta;
-                    f.a2 = U.dilated.out_alpha; f.ib2 = U.dilated.out_inv_beta;
-                    f.slots = gs; f.n_slots = gn; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
-                    f.r = r; f.c = U.dilated.cin; f.ntaps = U.dilated.ntaps; f.dil = U.dilated.dil;
-                    if (C && C->in_fmt != OP_BF16) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a layer with wide operands");
-                    HIP_TRY(launch_res_unit_fused(f, gst), "fused residual unit");
-                    std::swap(cur, other);
-                    HIP_TRY(mark(2), "event");
-                } else if (U.wide) {
-                    WideArgs f;
-                    f.xa = acur; f.y = cur;
-                    if (C) { f.ya = aoth; f.a3 = C->in_alpha; f.ib3 = C->in_inv_beta; }
-                    f.w7 = (const uint16_t*)U.dilated.w; f.w1 = U.w1_fused;
-                    f.b7 = U.dilated.bias; f.b1 = U.pointwise.bias;
-                    f.a2 = U.dilated.out_alpha; f.ib2 = U.dilated.out_inv_beta;
-                    f.slots = gs; f.n_slots = gn; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
-                    f.r = r; f.c = U.dilated.cin; f.ntaps = U.dilated.ntaps; f.dil = U.dilated.dil;
-                    if (C && C->in_fmt != OP_BF16) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a layer with wide operands");
-                    HIP_TRY(launch_res_unit_wide(f, gst), "fused residual unit (256 channels)");
-                    if (C) std::swap(acur, aoth);
-                    HIP_TRY(mark(2), "event");
-                } else {
-                    ConvArgs d = conv_args(U.dilated, acur, nullptr, nullptr);
-                    d.ya = mid; d.out_fmt = U.pointwise.in_fmt;   // Snake between the convolutions: the layer's own out_alpha
-                    HIP_TRY(launch_conv_bf16(d, U.dilated.variant, gst), "dilated convolution");
-                    HIP_TRY(mark(2), "event");
-                    ConvArgs q = conv_args(U.pointwise, mid, cur, cur);   // in place on the residual stream
-                    if (C) { q.ya = acur; q.out_alpha = C->in_alpha; q.out_inv_beta = C->in_inv_beta; q.out_fmt = C->in_fmt; }
-                    HIP_TRY(launch_conv_bf16(q, U.pointwise.variant, gst), "pointwise convolution");
-                }
-                HIP_TRY(mark(last_block && ui + 1 == B.res.size() ? 1 : 2), "event");
-                HIP_TRY(tap(cur, U.pointwise.cout), "debug tap");
+            const ResUnit& U = *T.unit;
+            if (U.fused) {
+                FusedArgs f;
+                f.x = cur; f.y = other;
+                if (C) { f.ya = acur; f.a3 = C->in_alpha; f.ib3 = C->in_inv_beta; }
+                f.w7 = (const uint16_t*)U.dilated.w; f.w1 = U.w1_fused;
+                f.b7 = U.dilated.bias; f.b1 = U.pointwise.bias;
+                f.a1 = U.dilated.in_alpha; f.ib1 = U.dilated.in_inv_beta;
+                f.a2 = U.dilated.out_alpha; f.ib2 = U.dilated.out_inv_beta;
+                f.slots = gs; f.n_slots = gn; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
+                f.r = r; f.c = U.dilated.cin; f.ntaps = U.dilated.ntaps; f.dil = U.dilated.dil;
+                if (C && C->in_fmt != OP_BF16) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a layer with wide operands");
+                HIP_TRY(launch_res_unit_fused(f, gst), "fused residual unit");
+                std::swap(cur, other);
+                HIP_TRY(mark(2), "event");
+            } else if (U.wide) {
+                WideArgs f;
+                f.xa = acur; f.y = cur;
+                if (C) { f.ya = aoth; f.a3 = C->in_alpha; f.ib3 = C->in_inv_beta; }
+                f.w7 = (const uint16_t*)U.dilated.w; f.w1 = U.w1_fused;
+                f.b7 = U.dilated.bias; f.b1 = U.pointwise.bias;
+                f.a2 = U.dilated.out_alpha; f.ib2 = U.dilated.out_inv_beta;
+                f.slots = gs; f.n_slots = gn; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
+                f.r = r; f.c = U.dilated.cin; f.ntaps = U.dilated.ntaps; f.dil = U.dilated.dil;
+                if (C && C->in_fmt != OP_BF16) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a layer with wide operands");
+                HIP_TRY(launch_res_unit_wide(f, gst), "fused residual unit (256 channels)");
+                if (C) std::swap(acur, aoth);
+                HIP_TRY(mark(2), "event");
+            } else {
+                ConvArgs d = conv_args(U.dilated, acur, nullptr, nullptr);
+                d.ya = mid; d.out_fmt = U.pointwise.in_fmt;   // Snake between the convolutions: the layer's own out_alpha
+                HIP_TRY(launch_conv_bf16(d, U.dilated.variant, gst), "dilated convolution");
+                HIP_TRY(mark(2), "event");
+                ConvArgs q = conv_args(U.pointwise, mid, cur, cur);   // in place on the residual stream
+                if (C) { q.ya = acur; q.out_alpha = C->in_alpha; q.out_inv_beta = C->in_inv_beta; q.out_fmt = C->in_fmt; }
+                HIP_TRY(launch_conv_bf16(q, U.pointwise.variant, gst), "pointwise convolution");
             }
+            HIP_TRY(mark(last ? 1 : 2), "event");
+            HIP_TRY(tap(cur, U.pointwise.cout), "debug tap");
         }
         return DEMON_OK;
         };
@@ -512,10 +542,21 @@ demon_status run_decode(demon_vae* v, const Workspace& ws, const Plan* plan, con
         }
         if (lrc != DEMON_OK) return lrc;
     }
-    // head and stitch, group by group on the caller's stream; the window waveforms are planar [channel][all rows]
-    const long long total_rows = plan->total_frames * r;
     const size_t hbytes = bf ? 2 : sizeof(float);                           // half or fp32 residual stream
     const char* final_base = (const char*)cur - goff() * hbytes;           // the buffer the last layer wrote, without the group offset
+    if (enc) {
+        // sampling step on the moments, trim and scatter into the caller's [clip, channel, frame] arrays
+        for (int gi = 0; gi < plan->n_groups; ++gi) {
+            select_group(gi, stream);
+            HIP_TRY(launch_sample(final_base + goff() * hbytes, bf, io.d_eps, io.d_moments, io.d_zout, bf, v->st.c0, n_frames, gs, gn,
+                                  plan->max_int, stream), "sampling step");
+        }
+        HIP_TRY(mark(1), "event");
+        if (v->timing > 0) ++v->timed_calls;
+        return DEMON_OK;
+    }
+    // head and stitch, group by group on the caller's stream; the window waveforms are planar [channel][all rows]
+    const long long total_rows = plan->total_frames * r;
     for (int gi = 0; gi < plan->n_groups; ++gi) {
         select_group(gi, stream);
         const void* x = final_base + goff() * hbytes;
@@ -532,21 +573,18 @@ demon_status run_decode(demon_vae* v, const Workspace& ws, const Plan* plan, con
     for (int gi = 0; gi < plan->n_groups; ++gi) {
         select_group(gi, stream);
         const float* y = ws.head_out + plan->g_frame0[gi] * r;
-        if (d_pcm)
-            HIP_TRY(launch_stitch_pcm16(y, d_pcm, v->st.out_channels, r, n_frames, total_rows, gs, gn, plan->max_int, stream), "stitch");
+        if (io.d_pcm)
+            HIP_TRY(launch_stitch_pcm16(y, io.d_pcm, v->st.out_channels, r, n_frames, total_rows, gs, gn, plan->max_int, stream), "stitch");
         else
-            HIP_TRY(launch_stitch(y, d_out, v->st.out_channels, r, n_frames, total_rows, gs, gn, plan->max_int, stream), "stitch");
+            HIP_TRY(launch_stitch(y, io.d_out, v->st.out_channels, r, n_frames, total_rows, gs, gn, plan->max_int, stream), "stitch");
     }
     HIP_TRY(mark(1), "event");
     if (v->timing > 0) ++v->timed_calls;
     return DEMON_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_weights, size_t n_floats, demon_vae** out)
+// Builds a decoder (encoder = false) or its mirror, the encoder (true), on the current device.
+demon_status create_impl(const demon_vae_config* cfg, const float* host_weights, size_t n_floats, bool encoder, demon_vae** out)
 {
     clear_error();
     if (!out) return fail(DEMON_ERR_INVALID_ARG, "out is NULL");
@@ -557,7 +595,7 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
     if (rc != DEMON_OK) return rc;
     if (cfg->dtype != DEMON_F32 && cfg->dtype != DEMON_BF16) return fail(DEMON_ERR_INVALID_ARG, "unknown dtype %d", (int)cfg->dtype);
     if (cfg->max_frames < 1 || cfg->max_clips < 1) return fail(DEMON_ERR_INVALID_ARG, "max_frames and max_clips must be >= 1");
-    const size_t need = stack_weight_count(st);
+    const size_t need = encoder ? stack_encoder_weight_count(st) : stack_weight_count(st);
     if (n_floats != need) return fail(DEMON_ERR_INVALID_ARG, "got %zu weights, the layer stack needs %zu", n_floats, need);
     const bool bf = cfg->dtype == DEMON_BF16;
     if (cfg->wide_operands < 0 || cfg->wide_operands > 2) return fail(DEMON_ERR_INVALID_ARG, "wide_operands must be 0, 1 or 2");
@@ -573,8 +611,11 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
         for (int d : st.dilations)
             if ((st.res_kernel - 1) * d > 64)
                 return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: kernel %d with dilation %d spans more than 64 samples", st.res_kernel, d);
+        if (encoder && g_wide_fmt == OP_BF16X2)
+            return fail(DEMON_ERR_UNSUPPORTED, "the encoder's strided convolutions take one operand plane: wide_operands = 2 is for decoders");
     }
     if (st.head_kernel > 15) return fail(DEMON_ERR_UNSUPPORTED, "head_kernel %d exceeds 15", st.head_kernel);
+    if (encoder && st.widths.back() % 8) return fail(DEMON_ERR_UNSUPPORTED, "encoder: the stem's width %d is not a multiple of 8", st.widths.back());
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(DEMON_ERR_HIP, "no HIP device available");
@@ -583,9 +624,11 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
     if (!v) return fail(DEMON_ERR_HIP, "out of host memory");
 
     v->st = st; v->dtype = cfg->dtype; v->max_frames = cfg->max_frames; v->max_clips = cfg->max_clips;
+    v->encoder = encoder;
     if (cfg->max_extended_frames < 0) return fail(DEMON_ERR_INVALID_ARG, "max_extended_frames must be >= 0");
     v->cap_frames = cfg->max_extended_frames > 0 ? cfg->max_extended_frames : 3ll * cfg->max_frames * cfg->max_clips;
-    stack_receptive_field(st, &v->rf_left, &v->rf_right);
+    if (encoder) stack_encoder_receptive_field(st, &v->rf_left, &v->rf_right, nullptr, nullptr);
+    else stack_receptive_field(st, &v->rf_left, &v->rf_right);
     v->small_tile_wgs = cfg->small_tile_wgs > 0 ? cfg->small_tile_wgs : cfg->small_tile_wgs < 0 ? 0 : g_env_small_tile_wgs;
     if (hipGetDevice(&v->device) != hipSuccess) return fail(DEMON_ERR_HIP, "hipGetDevice failed");
     {
@@ -600,122 +643,200 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
     std::vector<Pending> pend;
     struct FusedFix { ResUnit* U; size_t off; };
     std::vector<FusedFix> fused_fix;
-    v->blocks.resize(st.strides.size());
-    for (size_t l = 0; l < st.strides.size(); ++l) v->blocks[l].res.resize(st.dilations.size());
+    const int nb = (int)st.strides.size(), nres = (int)st.dilations.size();
+    v->blocks.resize(nb);
+    for (int b = 0; b < nb; ++b) v->blocks[b].res.resize(nres);
 
     const float* w = host_weights;
-    int cin = st.c0;
+    // one residual unit of width c whose output goes, as an operand, to a layer of format `next_fmt`
+    auto pack_unit = [&](ResUnit& U, int c, int j, int next_fmt) -> demon_status {
+        ConvLayer& D = U.dilated;
+        D.cin = c; D.cout = c; D.ntaps = st.res_kernel; D.dil = st.dilations[j];
+        ConvLayer& P = U.pointwise;
+        P.cin = c; P.cout = c; P.ntaps = 1; P.dil = 1;
+        const bool wide_ops = bf && c >= kSplitWidth;
+        P.in_fmt = wide_ops ? g_wide_fmt : (int)OP_BF16;
+        if (P.in_fmt == OP_BF16X2) v->has_split_operands = true;
+        D.in_fmt = (wide_ops && g_wide_fmt == OP_F16) ? (int)OP_F16 : (int)OP_BF16;
+        if (bf) {
+            D.variant = choose_variant_bf16(c, c);
+            P.variant = choose_variant_bf16(c, c);
+            if (D.variant < 0 || P.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for %d channels", c);
+        }
+        // a fused unit writes plain bf16 operands: a unit stays on the two-kernel path when the layer after it wants
+        // its input in a wider format
+        const bool feeds_split = next_fmt != OP_BF16;
+        U.fused = bf && (c == 64 || c == 128) && (st.res_kernel - 1) * st.dilations[j] <= 64 && !wide_ops && g_allow_fused && !feeds_split;
+        if (U.fused) { D.variant = (c == 64) ? 1 : 0; D.generic = false; }     // weight blocks of C x 64
+        U.wide = bf && c == 256 && (st.res_kernel - 1) * st.dilations[j] <= 64 && !wide_ops && g_allow_fused && !feeds_split;
+        if (U.wide) { D.variant = 3; D.generic = false; }                      // weight blocks of 256 x 32
+        Pending pd{&D, 0, 0, {}, {}, true, true};
+        pd.in = pack_snake(ar, w, w + c, c, bf);     w += 2 * c;
+        pd.w = pack_conv(ar, w, D, bf);              w += (size_t)c * c * st.res_kernel;
+        pd.bias = pack_floats(ar, w, c);             w += c;
+        pd.outp = pack_snake(ar, w, w + c, c, bf);   w += 2 * c;      // Snake between the two convolutions
+        Pending pp{&P, 0, 0, {}, {}, false, false};
+        if (U.fused || U.wide) {
+            const size_t off = ar.reserve((size_t)c * c * 2);
+            if (U.wide) pack_w1_wide(w, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
+            else pack_w1_fused(w, c, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
+            fused_fix.push_back({&U, off});
+        }
+        pp.w = pack_conv(ar, w, P, bf);              w += (size_t)c * c;
+        pp.bias = pack_floats(ar, w, c);             w += c;
+        pend.push_back(pd);
+        pend.push_back(pp);
+        return DEMON_OK;
+    };
+    auto wide_fmt_of = [&](int width) { return (bf && width >= kSplitWidth) ? g_wide_fmt : (int)OP_BF16; };
+
     long long per_frame = st.c0, rate = 1;
-    for (size_t l = 0; l < st.strides.size(); ++l) {
-        const int s = st.strides[l], c = st.widths[l];
-        Block& B = v->blocks[l];
+    size_t stem_w_off = 0, stem_b_off = 0;
+    SnakeOff hs{};  size_t hw = 0, hwf = 0, hb = 0;  bool head_mfma = false;
+    const int oc = st.out_channels, hk = st.head_kernel;
+    if (!encoder) {
+        int cin = st.c0;
+        for (int l = 0; l < nb; ++l) {
+            const int s = st.strides[l], c = st.widths[l];
+            Block& B = v->blocks[l];
+            {
+                ConvLayer& L = B.up;
+                L.cin = cin; L.cout = c; L.ntaps = 2; L.stride = s;
+                L.in_fmt = wide_fmt_of(c);
+                if (L.in_fmt == OP_BF16X2) v->has_split_operands = true;
+                if (bf) {
+                    L.variant = choose_variant_bf16(cin, s * c);
+                    if (L.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for a %d -> %d stride-%d upsampling", cin, c, s);
+                }
+                Pending p{&L, 0, 0, {}, {}, true, false};
+                p.in = pack_snake(ar, w, w + cin, cin, bf);  w += 2 * cin;
+                p.w = pack_conv(ar, w, L, bf);               w += (size_t)cin * c * 2 * s;
+                p.bias = pack_floats(ar, w, c);              w += c;
+                pend.push_back(p);
+            }
+            for (int j = 0; j < nres; ++j) {
+                // the last unit of a block feeds the next block's transposed conv
+                const int next_fmt = (j + 1 == nres && l + 1 < nb) ? wide_fmt_of(st.widths[l + 1]) : (int)OP_BF16;
+                rc = pack_unit(B.res[j], c, j, next_fmt);
+                if (rc != DEMON_OK) return rc;
+            }
+            cin = c;
+            rate *= s;
+            per_frame = std::max(per_frame, rate * c);
+        }
+        // Rows each layer must produce beyond a window's interior (the receptive-field cone, walked from the
+        // head back to the first block): a k-tap conv of dilation d reads d(k-1)/2 rows further out than it
+        // writes; a transposed conv writing margin m reads inputs up to (m + p)/s + 1 rows out.
         {
-            ConvLayer& L = B.up;
-            L.cin = cin; L.cout = c; L.ntaps = 2; L.stride = s;
-            L.in_fmt = (bf && c >= kSplitWidth) ? g_wide_fmt : (int)OP_BF16;
-            if (L.in_fmt == OP_BF16X2) v->has_split_operands = true;
+            int m = (st.head_kernel - 1) / 2;
+            for (int l = nb - 1; l >= 0; --l) {
+                Block& B = v->blocks[l];
+                for (int j = nres - 1; j >= 0; --j) {
+                    B.res[j].pointwise.margin = m;
+                    B.res[j].dilated.margin = m;
+                    m += st.dilations[j] * ((st.res_kernel - 1) / 2);
+                }
+                B.up.margin = m;
+                m = (m + st.strides[l] / 2) / st.strides[l] + 1;
+            }
+        }
+        // head: weights as [tap][cin][out_channel] fp32
+        hs = pack_snake(ar, w, w + cin, cin, bf);  w += 2 * cin;
+        hw = ar.reserve(sizeof(float) * (size_t)hk * cin * oc);
+        {
+            float* dst = reinterpret_cast<float*>(ar.bytes.data() + hw);
+            for (int o = 0; o < oc; ++o)
+                for (int i = 0; i < cin; ++i)
+                    for (int t = 0; t < hk; ++t) {
+                        float val = w[((size_t)o * cin + i) * hk + t];
+                        if (bf) { const uint32_t u = (uint32_t)f32_to_bf16_rne(val) << 16; memcpy(&val, &u, 4); }
+                        dst[((size_t)t * cin + i) * oc + o] = val;
+                    }
+        }
+        w += (size_t)oc * cin * hk;
+        head_mfma = bf && (cin == 64 || cin == 32) && head_mfma_frag_count(cin, hk) <= 40;
+        if (head_mfma) {
+            // from the bf16-rounded weights, like every other weight of this path
+            std::vector<float> wr((size_t)oc * cin * hk);
+            for (size_t i = 0; i < wr.size(); ++i) { const uint32_t u = (uint32_t)f32_to_bf16_rne((w - (size_t)oc * cin * hk)[i]) << 16; memcpy(&wr[i], &u, 4); }
+            hwf = ar.reserve(head_mfma_frag_count(cin, hk) * 64 * 16);
+            pack_head_mfma(wr.data(), cin, oc, hk, reinterpret_cast<uint16_t*>(ar.bytes.data() + hwf));
+        }
+        hb = pack_floats(ar, w, oc);
+        w += oc;
+        v->head_cin = cin;
+    } else {
+        // ---- encoder: stem from the waveform, then per block (from the audio rate down) the units and the strided conv
+        for (int s : st.strides) rate *= s;
+        const int cs = st.widths[nb - 1];
+        v->stem_cout = cs;
+        stem_w_off = ar.reserve(sizeof(float) * (size_t)hk * oc * cs);
+        {
+            // [C][channels][k] -> [k][channels][C]
+            float* dst = reinterpret_cast<float*>(ar.bytes.data() + stem_w_off);
+            for (int o = 0; o < cs; ++o)
+                for (int i = 0; i < oc; ++i)
+                    for (int t = 0; t < hk; ++t) {
+                        float val = w[((size_t)o * oc + i) * hk + t];
+                        if (bf) { const uint32_t u = (uint32_t)f32_to_bf16_rne(val) << 16; memcpy(&val, &u, 4); }
+                        dst[((size_t)t * oc + i) * cs + o] = val;
+                    }
+        }
+        w += (size_t)cs * oc * hk;
+        stem_b_off = pack_floats(ar, w, cs);  w += cs;
+        per_frame = rate * cs;
+        for (int b = 0; b < nb; ++b) {
+            const int l = nb - 1 - b;
+            const int s = st.strides[l], c = st.widths[l];
+            const int cn = l > 0 ? st.widths[l - 1] : 2 * st.c0;
+            Block& B = v->blocks[b];
+            per_frame = std::max(per_frame, rate * c);
+            ConvLayer& L = B.up;               // the strided conv after the units
+            L.cin = c; L.cout = cn; L.ntaps = 2 * s; L.stride = 0; L.down = s;
+            L.in_fmt = (bf && c >= kSplitWidth) ? (int)OP_F16 : (int)OP_BF16;
+            for (int j = 0; j < nres; ++j) {
+                // the last unit of a block feeds the block's strided conv
+                rc = pack_unit(B.res[j], c, j, j + 1 == nres ? L.in_fmt : (int)OP_BF16);
+                if (rc != DEMON_OK) return rc;
+            }
             if (bf) {
-                L.variant = choose_variant_bf16(cin, s * c);
-                if (L.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for a %d -> %d stride-%d upsampling", cin, c, s);
+                L.variant = choose_variant_bf16(c * (s / 2), cn);
+                if (L.variant == 1) L.variant = cn % 32 == 0 ? 2 : -1;      // the 256-column tile has no strided form
+                if (L.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for a %d -> %d stride-%d downsampling", c, cn, s);
             }
             Pending p{&L, 0, 0, {}, {}, true, false};
-            p.in = pack_snake(ar, w, w + cin, cin, bf);  w += 2 * cin;
-            p.w = pack_conv(ar, w, L, bf);               w += (size_t)cin * c * 2 * s;
-            p.bias = pack_floats(ar, w, c);              w += c;
+            p.in = pack_snake(ar, w, w + c, c, bf);  w += 2 * c;
+            p.w = pack_conv(ar, w, L, bf);           w += (size_t)cn * c * 2 * s;
+            p.bias = pack_floats(ar, w, cn);         w += cn;
             pend.push_back(p);
+            rate /= s;
+            per_frame = std::max(per_frame, rate * cn);
         }
-        for (size_t j = 0; j < st.dilations.size(); ++j) {
-            ResUnit& U = B.res[j];
-            ConvLayer& D = U.dilated;
-            D.cin = c; D.cout = c; D.ntaps = st.res_kernel; D.dil = st.dilations[j];
-            ConvLayer& P = U.pointwise;
-            P.cin = c; P.cout = c; P.ntaps = 1; P.dil = 1;
-            const bool wide_ops = bf && c >= kSplitWidth;
-            P.in_fmt = wide_ops ? g_wide_fmt : (int)OP_BF16;
-            if (P.in_fmt == OP_BF16X2) v->has_split_operands = true;
-            D.in_fmt = (wide_ops && g_wide_fmt == OP_F16) ? (int)OP_F16 : (int)OP_BF16;
-            if (bf) {
-                D.variant = choose_variant_bf16(c, c);
-                P.variant = choose_variant_bf16(c, c);
-                if (D.variant < 0 || P.variant < 0) return fail(DEMON_ERR_UNSUPPORTED, "bf16 path: no kernel for %d channels", c);
-            }
-            // a fused unit writes plain bf16 operands: the last unit of a block stays on the two-kernel path when the
-            // next block's transposed conv wants its input in a wider format
-            const bool feeds_split = j + 1 == st.dilations.size() && l + 1 < st.strides.size() && st.widths[l + 1] >= kSplitWidth;
-            U.fused = bf && (c == 64 || c == 128) && (st.res_kernel - 1) * st.dilations[j] <= 64 && !wide_ops && g_allow_fused && !feeds_split;
-            if (U.fused) { D.variant = (c == 64) ? 1 : 0; D.generic = false; }     // weight blocks of C x 64
-            U.wide = bf && c == 256 && (st.res_kernel - 1) * st.dilations[j] <= 64 && !wide_ops && g_allow_fused && !feeds_split;
-            if (U.wide) { D.variant = 3; D.generic = false; }                      // weight blocks of 256 x 32
-            Pending pd{&D, 0, 0, {}, {}, true, true};
-            pd.in = pack_snake(ar, w, w + c, c, bf);     w += 2 * c;
-            pd.w = pack_conv(ar, w, D, bf);              w += (size_t)c * c * st.res_kernel;
-            pd.bias = pack_floats(ar, w, c);             w += c;
-            pd.outp = pack_snake(ar, w, w + c, c, bf);   w += 2 * c;      // Snake between the two convolutions
-            Pending pp{&P, 0, 0, {}, {}, false, false};
-            if (U.fused || U.wide) {
-                const size_t off = ar.reserve((size_t)c * c * 2);
-                if (U.wide) pack_w1_wide(w, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
-                else pack_w1_fused(w, c, reinterpret_cast<uint16_t*>(ar.bytes.data() + off));
-                fused_fix.push_back({&U, off});
-            }
-            pp.w = pack_conv(ar, w, P, bf);              w += (size_t)c * c;
-            pp.bias = pack_floats(ar, w, c);             w += c;
-            pend.push_back(pd);
-            pend.push_back(pp);
-        }
-        cin = c;
-        rate *= s;
-        per_frame = std::max(per_frame, rate * c);
-    }
-    // Rows each layer must produce beyond a window's interior (the receptive-field cone, walked from the
-    // head back to the first block): a k-tap conv of dilation d reads d(k-1)/2 rows further out than it
-    // writes; a transposed conv writing margin m reads inputs up to (m + p)/s + 1 rows out.
-    {
-        int m = (st.head_kernel - 1) / 2;
-        for (int l = (int)st.strides.size() - 1; l >= 0; --l) {
-            Block& B = v->blocks[l];
-            for (int j = (int)st.dilations.size() - 1; j >= 0; --j) {
-                B.res[j].pointwise.margin = m;
-                B.res[j].dilated.margin = m;
-                m += st.dilations[j] * ((st.res_kernel - 1) / 2);
-            }
-            B.up.margin = m;
-            m = (m + st.strides[l] / 2) / st.strides[l] + 1;
-        }
-    }
-    // head: weights as [tap][cin][out_channel] fp32
-    const SnakeOff hs = pack_snake(ar, w, w + cin, cin, bf);  w += 2 * cin;
-    const int oc = st.out_channels, hk = st.head_kernel;
-    const size_t hw = ar.reserve(sizeof(float) * (size_t)hk * cin * oc);
-    {
-        float* dst = reinterpret_cast<float*>(ar.bytes.data() + hw);
-        for (int o = 0; o < oc; ++o)
-            for (int i = 0; i < cin; ++i)
-                for (int t = 0; t < hk; ++t) {
-                    float val = w[((size_t)o * cin + i) * hk + t];
-                    if (bf) { const uint32_t u = (uint32_t)f32_to_bf16_rne(val) << 16; memcpy(&val, &u, 4); }
-                    dst[((size_t)t * cin + i) * oc + o] = val;
+        // Rows each layer must produce beyond a window's interior, walked from the moments back to the stem: a strided
+        // conv writing margin m reads inputs up to m s + s/2 rows out, a k-tap conv of dilation d d(k-1)/2 rows further.
+        {
+            int m = 0;
+            for (int b = nb - 1; b >= 0; --b) {
+                Block& B = v->blocks[b];
+                const int s = st.strides[nb - 1 - b];
+                B.up.margin = m;
+                m = m * s + s / 2;
+                for (int j = nres - 1; j >= 0; --j) {
+                    B.res[j].pointwise.margin = m;
+                    B.res[j].dilated.margin = m;
+                    m += st.dilations[j] * ((st.res_kernel - 1) / 2);
                 }
+            }
+            v->stem_margin = m;
+        }
+        rate = 1;                              // no window waveforms to hold
     }
-    w += (size_t)oc * cin * hk;
-    size_t hwf = 0;
-    const bool head_mfma = bf && (cin == 64 || cin == 32) && head_mfma_frag_count(cin, hk) <= 40;
-    if (head_mfma) {
-        // from the bf16-rounded weights, like every other weight of this path
-        std::vector<float> wr((size_t)oc * cin * hk);
-        for (size_t i = 0; i < wr.size(); ++i) { const uint32_t u = (uint32_t)f32_to_bf16_rne((w - (size_t)oc * cin * hk)[i]) << 16; memcpy(&wr[i], &u, 4); }
-        hwf = ar.reserve(head_mfma_frag_count(cin, hk) * 64 * 16);
-        pack_head_mfma(wr.data(), cin, oc, hk, reinterpret_cast<uint16_t*>(ar.bytes.data() + hwf));
-    }
-    const size_t hb = pack_floats(ar, w, oc);
-    w += oc;
-    v->head_cin = cin;
 
     // ---- device memory
     const size_t act_elems = (size_t)v->cap_frames * (size_t)per_frame;
     v->ws.act_elems = act_elems;
     v->per_frame = per_frame;
-    const size_t head_bytes = (size_t)v->cap_frames * (size_t)rate * oc * sizeof(float);
+    const size_t head_bytes = encoder ? 256 : (size_t)v->cap_frames * (size_t)rate * oc * sizeof(float);
     auto cleanup = [&]() {
         if (v->d_params) (void)hipFree(v->d_params);
         for (void* b : v->ws.buf) if (b) (void)hipFree(b);
@@ -738,7 +859,7 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
         if (e == hipSuccess) e = hipEventCreateWithFlags(&v->ev_join, hipEventDisableTiming);
     }
     if (e == hipSuccess) e = hipMemcpy(v->d_params, ar.bytes.data(), ar.bytes.size(), hipMemcpyHostToDevice);
-    if (e != hipSuccess) { cleanup(); return hip_fail(e, "allocating decoder memory"); }
+    if (e != hipSuccess) { cleanup(); return hip_fail(e, "allocating device memory"); }
 
     const unsigned char* base = static_cast<const unsigned char*>(v->d_params);
     auto fptr = [&](size_t off) { return reinterpret_cast<const float*>(base + off); };
@@ -749,12 +870,46 @@ demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_wei
         if (p.has_out) { p.L->out_alpha = fptr(p.outp.alpha); p.L->out_inv_beta = fptr(p.outp.inv_beta); }
     }
     for (const FusedFix& f : fused_fix) f.U->w1_fused = reinterpret_cast<const uint16_t*>(base + f.off);
-    v->head_alpha = fptr(hs.alpha); v->head_inv_beta = fptr(hs.inv_beta);
-    v->head_w = fptr(hw); v->head_bias = fptr(hb);
-    if (head_mfma) v->head_wfrag = reinterpret_cast<const uint16_t*>(base + hwf);
+    if (encoder) {
+        v->stem_w = fptr(stem_w_off); v->stem_bias = fptr(stem_b_off);
+    } else {
+        v->head_alpha = fptr(hs.alpha); v->head_inv_beta = fptr(hs.inv_beta);
+        v->head_w = fptr(hw); v->head_bias = fptr(hb);
+        if (head_mfma) v->head_wfrag = reinterpret_cast<const uint16_t*>(base + hwf);
+    }
+
+    // ---- the layer sequence in processing order, each step with the layer that takes its output as an MFMA operand
+    // (bf16 path): the next step's resampling conv or the dilated conv of its unit, unless that unit reads the residual
+    // stream itself (narrow fused unit) or nothing follows (head, sampling step)
+    for (int b = 0; b < nb; ++b) {
+        Block& B = v->blocks[b];
+        if (!encoder) { Step t; t.conv = &B.up; v->steps.push_back(t); }
+        for (int j = 0; j < nres; ++j) { Step t; t.unit = &B.res[j]; v->steps.push_back(t); }
+        if (encoder) { Step t; t.conv = &B.up; v->steps.push_back(t); }
+    }
+    auto operand_layer = [](const Step& t) -> const ConvLayer* {
+        if (t.conv) return t.conv;
+        return t.unit->fused ? nullptr : &t.unit->dilated;
+    };
+    for (size_t i = 0; i + 1 < v->steps.size(); ++i) v->steps[i].consumer = operand_layer(v->steps[i + 1]);
+    v->first_consumer = operand_layer(v->steps[0]);
 
     *out = v.release();
     return DEMON_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+demon_status demon_vae_create(const demon_vae_config* cfg, const float* host_weights, size_t n_floats, demon_vae** out)
+{
+    return create_impl(cfg, host_weights, n_floats, false, out);
+}
+
+demon_status demon_vae_create_encoder(const demon_vae_config* cfg, const float* host_weights, size_t n_floats, demon_vae** out)
+{
+    return create_impl(cfg, host_weights, n_floats, true, out);
 }
 
 void demon_vae_destroy(demon_vae* v)
@@ -785,6 +940,7 @@ static demon_status decode_checked(demon_vae* v, const void* d_latent, int n_cli
 {
     clear_error();
     if (!v || !d_latent || (!d_out && !d_pcm)) return fail(DEMON_ERR_INVALID_ARG, "NULL argument");
+    if (v->encoder) return fail(DEMON_ERR_INVALID_ARG, "this handle is an encoder (demon_vae_create_encoder): use demon_vae_encode_windowed");
     if (n_clips < 1) return fail(DEMON_ERR_INVALID_ARG, "n_clips must be >= 1");
     if (n_frames < 1) return fail(DEMON_ERR_INVALID_ARG, "n_frames must be >= 1");
     if (frame_begin < 0) return fail(DEMON_ERR_INVALID_ARG, "frame_begin must be >= 0");
@@ -798,7 +954,9 @@ static demon_status decode_checked(demon_vae* v, const void* d_latent, int n_cli
     Plan* plan = nullptr;
     const demon_status rc = get_plan(v, n_clips, n_frames, frame_begin, frame_end, window, halo, wants_two_groups(v), (hipStream_t)stream, &plan);
     if (rc != DEMON_OK) return rc;
-    return run_decode(v, v->ws, plan, d_latent, n_frames, d_skip, d_out, d_pcm, (hipStream_t)stream);
+    Io io;
+    io.d_latent = d_latent; io.d_skip = d_skip; io.d_out = d_out; io.d_pcm = d_pcm; io.n_frames = n_frames;
+    return run_pass(v, v->ws, plan, io, (hipStream_t)stream);
 }
 
 demon_status demon_vae_decode_windowed(demon_vae* v, const void* d_latent, int n_clips, int n_frames,
@@ -832,6 +990,7 @@ demon_status demon_vae_decode_windowed_static(demon_vae* v, const void* d_latent
     clear_error();
     hipStream_t stream = (hipStream_t)stream_;
     if (!v || !d_latent || !d_out) return fail(DEMON_ERR_INVALID_ARG, "NULL argument");
+    if (v->encoder) return fail(DEMON_ERR_INVALID_ARG, "this handle is an encoder (demon_vae_create_encoder): use demon_vae_encode_windowed");
     if (n_clips < 1) return fail(DEMON_ERR_INVALID_ARG, "n_clips must be >= 1");
     if (n_frames < 1) return fail(DEMON_ERR_INVALID_ARG, "n_frames must be >= 1");
     if (frame_begin < 0) return fail(DEMON_ERR_INVALID_ARG, "frame_begin must be >= 0");
@@ -882,7 +1041,42 @@ demon_status demon_vae_decode_windowed_static(demon_vae* v, const void* d_latent
     HIP_TRY(launch_plan_slots(plan.d_slots, n_clips, (int)per_clip, (int)clip_frames, n_frames, frame_begin, frame_end, window, halo,
                               plan.n_slots, 0, stream),
             "window table");
-    return run_decode(v, ws, &plan, d_latent, n_frames, nullptr, d_out, nullptr, stream);
+    Io io;
+    io.d_latent = d_latent; io.d_out = d_out; io.n_frames = n_frames;
+    return run_pass(v, ws, &plan, io, stream);
+}
+
+demon_status demon_vae_encode_windowed(demon_vae* v, const float* d_wave, int n_clips, int n_frames,
+                                       int frame_begin, int frame_end, int window, int halo,
+                                       const float* d_eps, float* d_moments, void* d_latent, void* stream)
+{
+    clear_error();
+    if (!v || !d_wave || (!d_moments && !d_latent)) return fail(DEMON_ERR_INVALID_ARG, "NULL argument");
+    if (!v->encoder) return fail(DEMON_ERR_INVALID_ARG, "this handle is a decoder (demon_vae_create): use demon_vae_decode_windowed");
+    if (n_clips < 1) return fail(DEMON_ERR_INVALID_ARG, "n_clips must be >= 1");
+    if (n_frames < 1) return fail(DEMON_ERR_INVALID_ARG, "n_frames must be >= 1");
+    if (frame_begin < 0) return fail(DEMON_ERR_INVALID_ARG, "frame_begin must be >= 0");
+    if (frame_end > n_frames) return fail(DEMON_ERR_INVALID_ARG, "frame_end %d exceeds n_frames %d", frame_end, n_frames);
+    if (frame_begin >= frame_end) return fail(DEMON_ERR_INVALID_ARG, "empty frame range [%d, %d)", frame_begin, frame_end);
+    if (window < 1) return fail(DEMON_ERR_INVALID_ARG, "window must be >= 1");
+    if (halo < -1) return fail(DEMON_ERR_INVALID_ARG, "halo must be >= -1");
+    if (n_frames > v->max_frames) return fail(DEMON_ERR_WORKSPACE, "n_frames %d exceeds max_frames %d", n_frames, v->max_frames);
+    if (n_clips > v->max_clips) return fail(DEMON_ERR_WORKSPACE, "n_clips %d exceeds max_clips %d", n_clips, v->max_clips);
+    if ((long long)n_frames * v->st.total_stride() > 0x7fffffffll) return fail(DEMON_ERR_UNSUPPORTED, "clips longer than 2^31 samples");
+    if (halo == -1) halo = std::max(v->rf_left, v->rf_right);
+    Plan* plan = nullptr;
+    const demon_status rc = get_plan(v, n_clips, n_frames, frame_begin, frame_end, window, halo, wants_two_groups(v), (hipStream_t)stream, &plan);
+    if (rc != DEMON_OK) return rc;
+    Io io;
+    io.d_wave = d_wave; io.d_eps = d_eps; io.d_moments = d_moments; io.d_zout = d_latent; io.n_frames = n_frames;
+    return run_pass(v, v->ws, plan, io, (hipStream_t)stream);
+}
+
+demon_status demon_vae_encode(demon_vae* v, const float* d_wave, int n_clips, int n_frames, const float* d_eps,
+                              float* d_moments, void* d_latent, void* stream)
+{
+    // one window per clip covering [0, n_frames), no halo: the same kernels as the windowed encode
+    return demon_vae_encode_windowed(v, d_wave, n_clips, n_frames, 0, n_frames, n_frames > 0 ? n_frames : 1, 0, d_eps, d_moments, d_latent, stream);
 }
 
 demon_status demon_vae_decode(demon_vae* v, const void* d_latent, int n_clips, int n_frames, float* d_out, void* stream)

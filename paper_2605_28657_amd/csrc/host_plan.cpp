@@ -68,6 +68,21 @@ size_t stack_weight_count(const Stack& st)
     return n;
 }
 
+// Encoder (the decoder's mirror): stem conv [C_nb, channels, k] + bias; per block, from the audio rate down, the residual
+// units of width C_l and Snake + strided conv [C_out, C_l, 2 s_l] + bias, C_out = C_{l-1}, and 2 C0 (the moments) for l = 1.
+size_t stack_encoder_weight_count(const Stack& st)
+{
+    const size_t nb = st.strides.size();
+    size_t n = (size_t)st.widths[nb - 1] * st.out_channels * st.head_kernel + (size_t)st.widths[nb - 1];
+    for (size_t l = nb; l-- > 0;) {
+        const size_t c = (size_t)st.widths[l], s = (size_t)st.strides[l];
+        const size_t cn = l > 0 ? (size_t)st.widths[l - 1] : 2 * (size_t)st.c0;
+        n += st.dilations.size() * (2 * c + c * c * (size_t)st.res_kernel + c + 2 * c + c * c + c);
+        n += 2 * c + cn * c * 2 * s + cn;
+    }
+    return n;
+}
+
 static long long floor_div(long long a, long long b) { long long q = a / b; return (a % b != 0 && ((a < 0) != (b < 0))) ? q - 1 : q; }
 static long long ceil_div(long long a, long long b) { return -floor_div(-a, b); }
 
@@ -99,6 +114,37 @@ void stack_receptive_field(const Stack& st, int* left, int* right)
     *right = (int)(hi - f);
 }
 
+// Waveform samples [*lo, *hi] that latent frames [a, b] of the encoder depend on: backwards from the moments, a strided
+// conv (kernel 2s, stride s, padding s/2) reads inputs n s - s/2 .. n s + 3s/2 - 1 for output n, an odd conv of
+// dilation d reaches d (k-1)/2 further on both sides.
+static void encoder_backward(const Stack& st, long long a, long long b, long long* lo, long long* hi)
+{
+    for (size_t l = 0; l < st.strides.size(); ++l) {
+        const long long s = st.strides[l];
+        a = a * s - s / 2;
+        b = b * s + 3 * s / 2 - 1;
+        for (int d : st.dilations) {
+            const long long r = (long long)d * ((st.res_kernel - 1) / 2);
+            a -= r; b += r;
+        }
+    }
+    const long long rh = (st.head_kernel - 1) / 2;
+    *lo = a - rh; *hi = b + rh;
+}
+
+void stack_encoder_receptive_field(const Stack& st, int* left, int* right, long long* samples_left, long long* samples_right)
+{
+    const long long S = st.total_stride();
+    const long long f = 4096;
+    long long lo, hi;
+    encoder_backward(st, f, f, &lo, &hi);
+    const long long sl = f * S - lo, sr = hi - (f * S + S - 1);       // samples before the frame's first / after its last
+    if (samples_left) *samples_left = sl;
+    if (samples_right) *samples_right = sr;
+    *left = (int)((sl + S - 1) / S);
+    *right = (int)((sr + S - 1) / S);
+}
+
 void stack_forward_support(const Stack& st, long long a, long long b, long long* lo, long long* hi)
 {
     for (size_t l = 0; l < st.strides.size(); ++l) {
@@ -127,6 +173,24 @@ size_t demon_vae_weight_count(const demon_vae_config* cfg)
     Stack st;
     if (stack_from_config(cfg, &st) != DEMON_OK) return 0;
     return stack_weight_count(st);
+}
+
+size_t demon_vae_encoder_weight_count(const demon_vae_config* cfg)
+{
+    Stack st;
+    if (stack_from_config(cfg, &st) != DEMON_OK) return 0;
+    return stack_encoder_weight_count(st);
+}
+
+demon_status demon_vae_encoder_rf_from_config(const demon_vae_config* cfg, int* halo_left, int* halo_right,
+                                              long long* samples_left, long long* samples_right)
+{
+    if (!halo_left || !halo_right) return fail(DEMON_ERR_INVALID_ARG, "output pointer is NULL");
+    Stack st;
+    demon_status rc = stack_from_config(cfg, &st);
+    if (rc != DEMON_OK) return rc;
+    stack_encoder_receptive_field(st, halo_left, halo_right, samples_left, samples_right);
+    return DEMON_OK;
 }
 
 demon_status demon_vae_rf_from_config(const demon_vae_config* cfg, int* halo_left, int* halo_right)

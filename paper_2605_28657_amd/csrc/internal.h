@@ -29,6 +29,9 @@ demon_status stack_from_config(const demon_vae_config* cfg, Stack* out);
 size_t stack_weight_count(const Stack& st);
 void stack_receptive_field(const Stack& st, int* left, int* right);
 void stack_forward_support(const Stack& st, long long a, long long b, long long* lo, long long* hi);
+size_t stack_encoder_weight_count(const Stack& st);
+// halo of the windowed encode in latent frames and (optional) the cone in samples before / after a frame
+void stack_encoder_receptive_field(const Stack& st, int* left, int* right, long long* samples_left, long long* samples_right);
 
 // ---- windows ---------------------------------------------------------------------------------
 // One extended window ("slot") as the kernels see it.  Frames are latent frames; at a level with
@@ -72,6 +75,7 @@ struct ConvArgs {
     int ntaps;            // conv: kernel size; convT: 2
     int dil;              // conv: dilation; convT: unused
     int stride;           // 0 = Conv1d; s > 0 = ConvTranspose1d(kernel 2s, stride s, padding s/2)
+    int down = 0;         // s > 0 = strided Conv1d(kernel 2s, stride s, padding s/2) (the encoder); ntaps = 2s, stride = 0
     // bf16 path only: format of the MFMA operand read (x) and of the one emitted (ya), see kernels_bf16.hip
     int in_fmt = OP_BF16, out_fmt = OP_BF16;
     long long in_lo_off = 0, out_lo_off = 0;     // OP_BF16X2: element offset of the lo plane
@@ -91,8 +95,9 @@ int  choose_variant_bf16(int cin, int m);   // -1 if unsupported
 size_t packed_bf16_count(int cin, int cout, int ntaps, int stride, int variant);
 // `as_half`: the 16-bit weights are IEEE half (for a layer whose activation operand is OP_F16), else bf16.
 // `permute_rows`: row order of launch_conv_bf16's accumulator tiles (not for the layouts the fused units read).
+// `down` = s > 0: a strided Conv1d [cout, cin, 2s] in its merged-row form (see kernels_bf16.hip); ntaps, stride unused.
 void pack_bf16(const float* w_src, int cin, int cout, int ntaps, int stride, int variant, bool as_half, bool permute_rows,
-               uint16_t* dst);
+               uint16_t* dst, int down = 0);
 uint16_t f32_to_bf16_rne(float v);
 uint16_t f32_to_f16_rne(float v);
 
@@ -135,6 +140,16 @@ hipError_t launch_gather(const void* latent, float* x0, int c0, int n_frames, bo
                          const Slot* slots, int n_slots, int max_len, hipStream_t stream,
                          uint16_t* xa = nullptr, int xa_fmt = OP_BF16, long long xa_lo_off = 0,
                          const float* alpha = nullptr, const float* inv_beta = nullptr);
+// encoder stem: Conv1d(k, ch -> C) + bias from the planar fp32 waveform [n_clips, ch, n_frames * S] into the residual
+// stream y (half or fp32) of the rows each window needs (interior widened by `margin`); with ya (half path only) also
+// the activated operand snake(y; alpha, inv_beta) in format ya_fmt.  w: fp32 [k][ch][C].
+hipError_t launch_stem(const float* wave, void* y, bool y_half, uint16_t* ya, int ya_fmt, const float* w, const float* bias,
+                       const float* alpha, const float* inv_beta, int ch, int C, int k, int S, int n_frames, int margin,
+                       const Slot* slots, int n_slots, int max_len, int max_int, hipStream_t stream);
+// encoder: moments of the windows' interior frames -> moments_out fp32 [n_clips, 2 C0, n_frames] and the sampled latent
+// [n_clips, C0, n_frames] (bf16 for the half path, fp32 otherwise); eps fp32 [n_clips, C0, n_frames] or nullptr (z = mean)
+hipError_t launch_sample(const void* m, bool m_half, const float* eps, float* moments_out, void* latent_out, bool latent_bf16,
+                         int C0, int n_frames, const Slot* slots, int n_slots, int max_int, hipStream_t stream);
 // head: Snake -> Conv1d(k, cin -> oc) -> tanh; output planar fp32 [oc, total_rows]
 // `fast` selects the hardware-sine Snake (alpha given in revolutions) used by the bf16 path.
 // `x_half`: the input is the bf16 path's half-precision residual stream, else fp32.

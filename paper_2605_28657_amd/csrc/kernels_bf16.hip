@@ -6,6 +6,11 @@
 //                                     taps j in {0,1} with off_j = -j and weight W[i, o, phi + j s];
 //                                     column m, row mu lands on output sample m s - p + phi, channel o,
 //                                     i.e. on the contiguous run ((m s - p) cout + mu) of the time-major output.
+//   strided Conv1d(2s, s, p = s/2):   (the encoder's downsampling) the s/2 input rows n s/2 .. n s/2 + s/2 - 1 of the
+//                                     time-major input are ONE row of (s/2) cin channels; output n then reads the four
+//                                     merged rows 2n - 1 .. 2n + 2: mu = output channel, taps u in {0..3} with
+//                                     off_u = u - 1 on columns that advance two merged rows per output, and weight
+//                                     W[o, i, u s/2 + rho] for merged channel rho cin + i.
 //
 // Data flow.  The residual stream h is IEEE half in HBM (rounding it to bf16 after every layer alone would
 // use up the error budget of the bf16 path; all arithmetic on it is fp32).  MFMA operands are bf16 and are produced exactly once, by
@@ -48,8 +53,9 @@ constexpr int MAXSPAN = 64;    // largest (max tap offset - min tap offset) the 
 
 enum { MODE_ACT = 0,   // bias + Snake, bf16 out only                     (dilated conv of a residual unit)
        MODE_RES = 1,   // bias + residual add in fp32, half out in place  (1x1 conv of a residual unit)
-       MODE_UP  = 2 }; // bias, polyphase scatter, half out               (ConvTranspose1d)
-// MODE_RES and MODE_UP may in addition emit the activated operand of the next layer: EMIT = 0 none, else the
+       MODE_UP  = 2,   // bias, polyphase scatter, half out               (ConvTranspose1d)
+       MODE_DOWN = 3 };// bias, half out; columns step two input rows     (strided Conv1d on merged rows)
+// MODE_RES, MODE_UP and MODE_DOWN may in addition emit the activated operand of the next layer: EMIT = 0 none, else the
 // operand format + 1 (1 bf16, 2 bf16 hi + lo, 3 half).  IN is the operand format of the input.
 
 struct MfmaParams {
@@ -127,21 +133,27 @@ static inline int slot_to_row(int r, bool permute)
 }
 
 void pack_bf16(const float* w, int cin, int cout, int ntaps, int stride, int variant, bool as_half, bool permute_rows,
-               uint16_t* dst)
+               uint16_t* dst, int down)
 {
     const Variant v = kVariants[variant];
     const bool perm = permute_rows && v.MT % 64 == 0;
     const int M = stride > 0 ? stride * cout : cout;
-    const int nch = cin / v.KC;
+    // strided conv (down = s): merged channel rho cin + i of merged tap u is W[o, i, u s/2 + rho]
+    const int merge = down > 0 ? down / 2 : 1;
+    const int kcin = cin * merge, ktaps = down > 0 ? 4 : ntaps;
+    const int nch = kcin / v.KC;
     size_t pos = 0;
     for (int mt = 0; mt < M / v.MT; ++mt)
         for (int c = 0; c < nch; ++c)
-            for (int t = 0; t < ntaps; ++t)
+            for (int t = 0; t < ktaps; ++t)
                 for (int i = 0; i < v.MT; ++i)
                     for (int e = 0; e < v.KC; ++e) {
                         const int mu = mt * v.MT + slot_to_row(i, perm), ci = c * v.KC + e;
                         float val;
-                        if (stride == 0) {
+                        if (down > 0) {
+                            const int rho = ci / cin, ii = ci - rho * cin;
+                            val = w[((size_t)mu * cin + ii) * (2 * down) + t * merge + rho];
+                        } else if (stride == 0) {
                             val = w[((size_t)mu * cin + ci) * ntaps + t];
                         } else {
                             const int phi = mu / cout, o = mu - phi * cout;
@@ -168,7 +180,8 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     constexpr int LDK = KC + 8;                 // padded LDS row (bf16 elements): 16-byte multiple, bank-spread
     // rows of the activation tile: the dilated conv reaches MAXSPAN rows past its NT columns, the 1x1 conv
     // none and the transposed conv one; a smaller tile lets more workgroups share a CU
-    constexpr int XR_MAX = NT + (MODE == MODE_ACT ? MAXSPAN : 8);
+    constexpr int XS = (MODE == MODE_DOWN) ? 2 : 1;        // input rows per GEMM column
+    constexpr int XR_MAX = XS * NT + (MODE == MODE_ACT ? MAXSPAN : 8);
     constexpr int WTM = MT / WM, WTN = NT / WN; // tile of one wave
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int SEGS = KC / 8;                // 16-byte segments per row
@@ -181,6 +194,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     static_assert(WM * WN == 2 || WM * WN == 4 || WM * WN == 8, "two, four or eight waves per workgroup");
     static_assert(TM == 1 || TM == 2, "a lane owns one or two consecutive output channels");
     static_assert(MODE != MODE_ACT || EMIT > 0, "the dilated conv only has the activated output");
+    static_assert(MODE != MODE_DOWN || IN != OP_BF16X2, "the strided conv takes one operand plane");
 
     // Three workgroups per CU hide each other's barriers and load latencies markedly better than two (-10 to -28 % per
     // launch), and the 128 x 128 tile gets there with one weight buffer in LDS instead of two (46 KB with the dilated
@@ -198,7 +212,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     const Slot s = p.slots[blockIdx.y];
     const int nrows = s.len * p.r_in;                       // valid input rows of this window
     // output rows that later layers read: the interior widened by `margin`, clamped to the window
-    const int r_out = (MODE == MODE_UP) ? p.r_in * p.stride : p.r_in;
+    const int r_out = (MODE == MODE_UP) ? p.r_in * p.stride : (MODE == MODE_DOWN) ? p.r_in / 2 : p.r_in;
     const int nrows_o = s.len * r_out;
     const int out_lo = max(0, s.crop * r_out - p.margin);
     const int out_hi = min(nrows_o, (s.crop + s.n_int) * r_out + p.margin);
@@ -229,7 +243,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
 
     const int last_off = p.tap0 + (p.ntaps - 1) * p.tap_step;
     const int minoff = min(p.tap0, last_off);
-    const int XR = NT + max(p.tap0, last_off) - minoff;
+    const int XR = XS * (NT - 1) + 1 + max(p.tap0, last_off) - minoff;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -248,7 +262,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     const unsigned w_blk = (unsigned)p.pack_ratio * (A_CH * 16u);
     const unsigned w_tile0 = (unsigned)(mtile / p.pack_ratio) * nstages * w_blk + (unsigned)(mtile % p.pack_ratio) * (A_CH * 16u);
     const unsigned a_voff = tid * 16u;
-    const unsigned x_voff = ((unsigned)((n0 + minoff + xr0) * p.cin) + seg * 8u) * 2u;    // may wrap "negative": out of range
+    const unsigned x_voff = ((unsigned)((XS * n0 + minoff + xr0) * p.cin) + seg * 8u) * 2u;    // may wrap "negative": out of range
     const unsigned x_row_step = (unsigned)(RPP * p.cin) * 2u;
 
     u32x4 ra[A_ITERS], rb[A_ITERS];        // rb: second set, only with PF2
@@ -346,7 +360,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     auto mma = [&](int stage) __attribute__((always_inline)) {
         const int off = p.tap0 + tap * p.tap_step - minoff;
         const uint16_t* abase = &As[NBUF == 2 ? (stage & 1) : 0][(wm * WTM + j) * LDK + h * 8];
-        const int xoff = (wn * WTN + j + off) * LDK + h * 8;
+        const int xoff = ((wn * WTN + j) * XS + off) * LDK + h * 8;
 #pragma unroll
         for (int ks = 0; ks < KC / 16; ++ks) {
             u32x4 af[TM], bfr[NP][TN];
@@ -356,7 +370,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
             for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
                 for (int ni = 0; ni < TN; ++ni)
-                    bfr[pl][ni] = *reinterpret_cast<const u32x4*>(&Xs[pl][xoff + ni * 32 * LDK + ks * 16]);
+                    bfr[pl][ni] = *reinterpret_cast<const u32x4*>(&Xs[pl][xoff + ni * 32 * XS * LDK + ks * 16]);
 #pragma unroll
             for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
@@ -494,6 +508,11 @@ static hipError_t launch_variant(const MfmaParams& p, int mode, int in_fmt, int 
         DEMON_CASE(MODE_RES, OP_BF16, 0) DEMON_CASE(MODE_RES, OP_BF16, 1) DEMON_CASE(MODE_RES, OP_BF16, 2) DEMON_CASE(MODE_RES, OP_BF16, 3)
         DEMON_CASE(MODE_RES, OP_BF16X2, 0) DEMON_CASE(MODE_RES, OP_BF16X2, 1) DEMON_CASE(MODE_RES, OP_BF16X2, 2)
         DEMON_CASE(MODE_RES, OP_F16, 0) DEMON_CASE(MODE_RES, OP_F16, 1) DEMON_CASE(MODE_RES, OP_F16, 3)
+    } else if (mode == MODE_DOWN) {
+        if constexpr (NT <= 128) {       // its activation tile holds two input rows per column
+            DEMON_CASE(MODE_DOWN, OP_BF16, 0) DEMON_CASE(MODE_DOWN, OP_BF16, 1) DEMON_CASE(MODE_DOWN, OP_BF16, 3)
+            DEMON_CASE(MODE_DOWN, OP_F16, 0) DEMON_CASE(MODE_DOWN, OP_F16, 1) DEMON_CASE(MODE_DOWN, OP_F16, 3)
+        }
     } else {
         DEMON_CASE(MODE_UP, OP_BF16, 0) DEMON_CASE(MODE_UP, OP_BF16, 1) DEMON_CASE(MODE_UP, OP_BF16, 2) DEMON_CASE(MODE_UP, OP_BF16, 3)
         DEMON_CASE(MODE_UP, OP_BF16X2, 1) DEMON_CASE(MODE_UP, OP_BF16X2, 2)
@@ -512,31 +531,36 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     if (variant < 0 || variant > 2) return hipErrorInvalidValue;
     Variant v = kVariants[variant];
     const int M = a.stride > 0 ? a.stride * a.cout : a.cout;
+    // strided conv: the kernel sees merged input rows of (s/2) cin channels, four taps, two rows per column
+    const int merge = a.down > 0 ? a.down / 2 : 1;
+    if (a.down > 0 && (a.down % 2 != 0 || a.stride != 0 || a.ntaps != 2 * a.down || a.r_in % a.down != 0 || a.res)) return hipErrorInvalidValue;
+    const int cin = a.cin * merge, r_in = a.r_in / merge, ntaps = a.down > 0 ? 4 : a.ntaps;
     MfmaParams p;
     p.xa = (const uint16_t*)a.x; p.w = (const uint16_t*)a.w; p.bias = a.bias;
     p.y = (hres_t*)a.y; p.ya = (uint16_t*)a.ya;
     p.out_alpha = a.out_alpha; p.out_inv_beta = a.out_inv_beta;
     p.slots = a.slots;
-    p.r_in = a.r_in; p.cin = a.cin; p.cout = a.cout; p.ntaps = a.ntaps; p.stride = a.stride;
-    p.nchunks = a.cin / v.KC; p.margin = a.margin;
+    p.r_in = r_in; p.cin = cin; p.cout = a.cout; p.ntaps = ntaps; p.stride = a.stride;
+    p.nchunks = cin / v.KC; p.margin = a.margin;
     p.in_lo_off = a.in_lo_off; p.out_lo_off = a.out_lo_off;
-    const size_t wb = (size_t)M * a.ntaps * a.cin * 2;
+    const size_t wb = (size_t)M * ntaps * cin * 2;
     if (wb > 0xffffffffull) return hipErrorInvalidValue;
     p.w_bytes = (unsigned)wb;
     int mode;
-    if (a.stride > 0) { p.tap0 = 0; p.tap_step = -1; mode = MODE_UP; }
+    if (a.down > 0) { p.tap0 = -1; p.tap_step = 1; mode = MODE_DOWN; }
+    else if (a.stride > 0) { p.tap0 = 0; p.tap_step = -1; mode = MODE_UP; }
     else { p.tap0 = -((a.ntaps - 1) / 2) * a.dil; p.tap_step = a.dil; mode = a.res ? MODE_RES : MODE_ACT; }
     if (a.in_fmt < OP_BF16 || a.in_fmt > OP_F16 || a.out_fmt < OP_BF16 || a.out_fmt > OP_F16) return hipErrorInvalidValue;
     const int emit = a.ya ? a.out_fmt + 1 : 0;
-    const int span = (a.ntaps - 1) * (a.stride > 0 ? 1 : a.dil);
+    const int span = (ntaps - 1) * ((a.stride > 0 || a.down > 0) ? 1 : a.dil);
     // shape checks: everything the kernel's indexing assumes
-    if (span > (mode == MODE_ACT ? MAXSPAN : 8) || M % v.MT != 0 || a.cin % v.KC != 0 || a.cout % 4 != 0 || a.margin < 0) return hipErrorInvalidValue;
+    if (span > (mode == MODE_ACT ? MAXSPAN : 8) || M % v.MT != 0 || cin % v.KC != 0 || a.cout % 4 != 0 || a.margin < 0) return hipErrorInvalidValue;
     if (mode == MODE_ACT && emit == 0) return hipErrorInvalidValue;
     if (emit > 0 && (!a.out_alpha || !a.out_inv_beta)) return hipErrorInvalidValue;
     if (mode != MODE_ACT && !a.y) return hipErrorInvalidValue;
     if (mode == MODE_RES && a.res != a.y) return hipErrorInvalidValue;            // the residual add is in place
     // one window's activation plane must fit a 32-bit byte offset (buffer descriptors)
-    const long long r_out = (long long)a.r_in * (a.stride > 0 ? a.stride : 1);
+    const long long r_out = a.down > 0 ? (long long)a.r_in / a.down : (long long)a.r_in * (a.stride > 0 ? a.stride : 1);
     const long long max_in_bytes = (long long)a.max_len * a.r_in * a.cin * 2;
     const long long max_out_bytes = (long long)a.max_len * r_out * a.cout * (long long)sizeof(hres_t);
     if (max_in_bytes > 0xf0000000ll || max_out_bytes > 0xf0000000ll) return hipErrorInvalidValue;

@@ -2,6 +2,7 @@
 // Same layer semantics as the bf16 path (decoder layers of the benchmark description):
 //   conv  : y[n, o] = b[o] + sum_t sum_i W[o,i,t] x[n + (t - (k-1)/2) d, i]      (x = 0 outside the slot)
 //   convT : y[m s - p + phi, o] = b[o] + sum_j sum_i W[i,o,phi + j s] x[m - j, i],  j in {0,1}, p = s/2
+//   convS : y[n, o] = b[o] + sum_t sum_i W[o,i,t] x[n s - p + t, i],  t in 0..2s-1, p = s/2   (the encoder's strided conv)
 #include <algorithm>
 
 #include "device_common.h"
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(ConvArgs a)
     const int M = a.stride > 0 ? a.stride * a.cout : a.cout;
     const long long nrows_in = (long long)s.len * a.r_in;
     // output rows that later layers read: the interior widened by `margin`, clamped to the window
-    const long long r_out = a.stride > 0 ? (long long)a.r_in * a.stride : a.r_in;
+    const long long r_out = a.stride > 0 ? (long long)a.r_in * a.stride : a.down > 0 ? a.r_in / a.down : a.r_in;
     const long long out_lo = max(0ll, s.crop * r_out - a.margin);
     const long long out_hi = min(s.len * r_out, (s.crop + s.n_int) * r_out + a.margin);
     if (out_hi <= out_lo) return;                        // an empty window (a gated clip)
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(ConvArgs a)
     float acc = 0.f;
     const int half = (a.ntaps - 1) / 2;
     for (int t = 0; t < a.ntaps; ++t) {
-        const long long r = a.stride > 0 ? col - t : col + (long long)(t - half) * a.dil;
+        const long long r = a.stride > 0 ? col - t : a.down > 0 ? col * a.down - a.down / 2 + t : col + (long long)(t - half) * a.dil;
         if (r < 0 || r >= nrows_in) continue;
         const float* xr = x + (size_t)(rowbase_in + r) * a.cin;
         const float* wt = w + (size_t)t * a.cin * M + mu;
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(ConvArgs a)
 
     int o = mu;
     long long n = col;
-    long long rowbase_out = rowbase_in;
+    long long rowbase_out = a.down > 0 ? (long long)s.row0 * r_out : rowbase_in;
     if (a.stride > 0) {
         const int phi = mu / a.cout;
         o = mu - phi * a.cout;
@@ -102,7 +103,8 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(ConvArgs a)
 hipError_t launch_conv_f32(const ConvArgs& a, hipStream_t stream)
 {
     const long long M = a.stride > 0 ? (long long)a.stride * a.cout : a.cout;
-    const long long r_out = (long long)a.r_in * (a.stride > 0 ? a.stride : 1);
+    if (a.down > 0 && (a.stride != 0 || a.ntaps != 2 * a.down || a.r_in % a.down != 0 || a.res)) return hipErrorInvalidValue;
+    const long long r_out = a.down > 0 ? (long long)a.r_in / a.down : (long long)a.r_in * (a.stride > 0 ? a.stride : 1);
     const long long out_rows = std::min((long long)a.max_int * r_out + 2ll * a.margin, (long long)a.max_len * r_out);
     const long long ncols = a.stride > 0 ? out_rows / a.stride + 2 : out_rows;
     const long long blocks = (ncols * M + 255) / 256;

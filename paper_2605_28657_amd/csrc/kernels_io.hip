@@ -5,6 +5,8 @@
 // head   : Snake -> Conv1d(k, C -> out_channels) -> tanh, the last layer of the decoder.
 // stitch : step 3 (trim the margins, keep the frame-aligned interior) plus the side-by-side write
 //          of the interiors into the clip's waveform.
+#include <algorithm>
+
 #include "device_common.h"
 
 namespace demon {
@@ -63,6 +65,128 @@ hipError_t launch_gather(const void* latent, float* x0, int c0, int n_frames, bo
         hipLaunchKernelGGL(gather_kernel<uint16_t>, grid, dim3(256), 0, stream, (const uint16_t*)latent, x0, c0, n_frames, slots);
     else
         hipLaunchKernelGGL(gather_kernel<float>, grid, dim3(256), 0, stream, (const float*)latent, x0, c0, n_frames, slots);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------- encoder stem
+// First layer of the encoder (the mirror of the head): Conv1d(k, channels -> C) + bias straight from the planar fp32
+// waveform of every extended window into the time-major residual stream, and with `ya` the activated operand of the
+// next layer as well.  Samples outside the window read as zero (the convolution's zero padding: the window is encoded
+// as if it were a whole clip).  A thread owns 8 consecutive output channels of one row; K = k x channels is tiny
+// (14 for stereo, k = 7), so this is plain FMA work bound by the store of the C-channel rows.
+template <typename TY, bool FAST>
+__global__ __launch_bounds__(256) void stem_kernel(const float* __restrict__ wave, TY* __restrict__ y, uint16_t* __restrict__ ya,
+                                                   int ya_fmt, const float* __restrict__ w /*[k][ch][C]*/,
+                                                   const float* __restrict__ bias, const float* __restrict__ alpha,
+                                                   const float* __restrict__ inv_beta, int ch, int C, int k, int S,
+                                                   int n_frames, int margin, const Slot* __restrict__ slots)
+{
+    if (sizeof(TY) == 2) fp16_saturate_on();
+    const Slot s = slots[blockIdx.y];
+    const long long nrows = (long long)s.len * S;
+    const long long out_lo = max(0ll, (long long)s.crop * S - margin);
+    const long long out_hi = min(nrows, (long long)(s.crop + s.n_int) * S + margin);
+    const int groups = C / 8;                                   // threads per row
+    const int rows_per_block = 256 / groups;
+    const int g = threadIdx.x % groups;
+    const long long n = out_lo + (long long)blockIdx.x * rows_per_block + threadIdx.x / groups;
+    if (threadIdx.x / groups >= rows_per_block || n >= out_hi) return;
+    const int half = (k - 1) / 2;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = bias[8 * g + e];
+    const float* clip = wave + (size_t)s.clip * ch * ((size_t)n_frames * S) + (long long)s.lo * S;
+    for (int t = 0; t < k; ++t) {
+        const long long m = n + t - half;
+        if (m < 0 || m >= nrows) continue;
+        for (int c = 0; c < ch; ++c) {
+            const float xv = clip[(size_t)c * ((size_t)n_frames * S) + m];
+            const float* wt = w + ((size_t)t * ch + c) * C + 8 * g;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(wt[e], xv, acc[e]);
+        }
+    }
+    const size_t idx = ((size_t)s.row0 * S + n) * C + 8 * g;
+    if constexpr (sizeof(TY) == 4) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) y[idx + e] = acc[e];
+    } else {
+        f16x8 hv;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) hv[e] = (_Float16)acc[e];
+        *reinterpret_cast<f16x8*>(&y[idx]) = hv;
+        if (ya) {
+            // the next layer's operand is Snake of the STORED value
+            u32x4 o;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float a0 = keep_f32(snake_fast((float)hv[2 * q], alpha[8 * g + 2 * q], inv_beta[8 * g + 2 * q]));
+                const float a1 = keep_f32(snake_fast((float)hv[2 * q + 1], alpha[8 * g + 2 * q + 1], inv_beta[8 * g + 2 * q + 1]));
+                o[q] = ya_fmt == OP_F16 ? pack_f16x2(a0, a1) : pack_bf16x2(a0, a1);
+            }
+            *reinterpret_cast<u32x4*>(&ya[idx]) = o;
+        }
+    }
+}
+
+hipError_t launch_stem(const float* wave, void* y, bool y_half, uint16_t* ya, int ya_fmt, const float* w, const float* bias,
+                       const float* alpha, const float* inv_beta, int ch, int C, int k, int S, int n_frames, int margin,
+                       const Slot* slots, int n_slots, int max_len, int max_int, hipStream_t stream)
+{
+    if (C % 8 != 0 || C / 8 > 256 || k < 1 || (k & 1) == 0 || margin < 0) return hipErrorInvalidValue;
+    if (ya && (ya_fmt == OP_BF16X2 || !alpha || !inv_beta || !y_half)) return hipErrorInvalidValue;
+    const long long rows = std::min((long long)max_int * S + 2ll * margin, (long long)max_len * S);
+    const int rows_per_block = 256 / (C / 8);
+    dim3 grid((unsigned)((rows + rows_per_block - 1) / rows_per_block), (unsigned)n_slots);
+    if (y_half)
+        hipLaunchKernelGGL((stem_kernel<hres_t, true>), grid, dim3(256), 0, stream, wave, (hres_t*)y, ya, ya_fmt, w, bias, alpha, inv_beta,
+                           ch, C, k, S, n_frames, margin, slots);
+    else
+        hipLaunchKernelGGL((stem_kernel<float, false>), grid, dim3(256), 0, stream, wave, (float*)y, nullptr, 0, w, bias, alpha, inv_beta,
+                           ch, C, k, S, n_frames, margin, slots);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------- encoder: sampling step + trim + scatter
+// Last step of the windowed encode: of every window's moments [rows = frames, 2 C0] (mean | log-variance) keep the
+// interior frames, write them to moments_out [clip, 2 C0, n_frames] (fp32) and the sampled latent
+// z = mean + exp(logvar / 2) eps (the sampling step on the output moments of Table III; eps drawn by the caller, z = mean
+// without eps) to latent_out [clip, C0, n_frames] in the path's latent type.  Either output may be absent.
+template <typename TM, typename TZ>
+__global__ __launch_bounds__(256) void sample_kernel(const TM* __restrict__ m, const float* __restrict__ eps,
+                                                     float* __restrict__ moments_out, TZ* __restrict__ latent_out,
+                                                     int C0, int n_frames, const Slot* __restrict__ slots)
+{
+    const Slot s = slots[blockIdx.y];
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= s.n_int * C0) return;
+    const int fi = e / C0, c = e - fi * C0;
+    const size_t row = (size_t)s.row0 + s.crop + fi;
+    const int f = s.begin + fi;
+    const float mean = load_act<TM>(m + row * (2 * C0) + c);
+    const float lv = load_act<TM>(m + row * (2 * C0) + C0 + c);
+    if (moments_out) {
+        moments_out[((size_t)s.clip * 2 * C0 + c) * n_frames + f] = mean;
+        moments_out[((size_t)s.clip * 2 * C0 + C0 + c) * n_frames + f] = lv;
+    }
+    if (latent_out) {
+        const size_t zi = ((size_t)s.clip * C0 + c) * n_frames + f;
+        const float z = eps ? fmaf(expf(0.5f * lv), eps[zi], mean) : mean;
+        if constexpr (sizeof(TZ) == 2) latent_out[zi] = f32_to_bf16_bits(z);
+        else latent_out[zi] = z;
+    }
+}
+
+hipError_t launch_sample(const void* m, bool m_half, const float* eps, float* moments_out, void* latent_out, bool latent_bf16,
+                         int C0, int n_frames, const Slot* slots, int n_slots, int max_int, hipStream_t stream)
+{
+    dim3 grid((unsigned)(((size_t)max_int * C0 + 255) / 256), (unsigned)n_slots);
+    if (m_half && latent_bf16)
+        hipLaunchKernelGGL((sample_kernel<_Float16, uint16_t>), grid, dim3(256), 0, stream, (const _Float16*)m, eps, moments_out, (uint16_t*)latent_out, C0, n_frames, slots);
+    else if (!m_half && !latent_bf16)
+        hipLaunchKernelGGL((sample_kernel<float, float>), grid, dim3(256), 0, stream, (const float*)m, eps, moments_out, (float*)latent_out, C0, n_frames, slots);
+    else
+        return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

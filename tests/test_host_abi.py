@@ -19,7 +19,8 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "demon_vae.h")).read()
     names = set(re.findall(r"\b(demon_vae_[a-z0-9_]+)\s*\(", header))
     assert {"demon_vae_create", "demon_vae_destroy", "demon_vae_decode", "demon_vae_decode_windowed", "demon_vae_decode_windowed_pcm16",
-            "demon_vae_decode_windowed_gated", "demon_vae_decode_windowed_static", "demon_vae_latent_similarity", "demon_vae_crossfade",
+            "demon_vae_decode_windowed_gated", "demon_vae_decode_windowed_static", "demon_vae_create_encoder", "demon_vae_encode", "demon_vae_encode_windowed",
+            "demon_vae_encoder_weight_count", "demon_vae_encoder_rf_from_config", "demon_vae_latent_similarity", "demon_vae_crossfade",
             "demon_vae_receptive_field", "demon_vae_rf_from_config", "demon_vae_plan_windows",
             "demon_vae_weight_count", "demon_vae_last_error"} <= names
     lib = pa.load_library()
@@ -30,6 +31,17 @@ def test_library_exports_every_declared_symbol():
 def test_weight_count_matches_layout():
     for spec in (di.TINY, di.FULL, di.DecoderSpec(8, (2, 6), (16, 8), (1, 2, 4, 8), 5, 3, 1)):
         assert pa.demon_vae_weight_count(spec) == di.n_weights(spec)
+
+
+def test_encoder_weight_count_and_receptive_field_match_the_oracle():
+    for spec in (di.TINY, di.FULL, di.DecoderSpec(32, (6, 2), (64, 32), (2, 5), 5, 3, 3), di.DecoderSpec(32, (2, 4), (256, 128), ())):
+        assert pa.demon_vae_encoder_weight_count(spec) == sum(int(np.prod(sh)) for _, sh in di.encoder_weight_layout(spec))
+        hl, hr, sl, sr = pa.demon_vae_encoder_rf_from_config(spec)
+        assert (hl, hr) == oracle.encoder_receptive_field(spec)
+        lo, hi = oracle.encoder_backward_interval(spec, 0, 0)
+        assert (sl, sr) == (-lo, hi - (spec.total_stride - 1))
+    assert pa.demon_vae_encoder_rf_from_config(di.FULL) == (6, 6, 10245, 12164 - 1919)
+    assert pa.demon_vae_encoder_rf_from_config(di.TINY)[:2] == (15, 15)
 
 
 def test_receptive_field_matches_oracle_derivation():
@@ -104,6 +116,8 @@ def test_null_handle_calls_return_invalid_arg():
     assert lib.demon_vae_decode_windowed_pcm16(None, None, 1, 1, 0, 1, 1, 0, None, None) == pa.DEMON_ERR_INVALID_ARG
     assert lib.demon_vae_decode_windowed_gated(None, None, 1, 1, 0, 1, 1, 0, None, None, None) == pa.DEMON_ERR_INVALID_ARG
     assert lib.demon_vae_decode_windowed_static(None, None, 1, 1, 0, 1, 1, 0, None, None) == pa.DEMON_ERR_INVALID_ARG
+    assert lib.demon_vae_encode_windowed(None, None, 1, 1, 0, 1, 1, 0, None, None, None, None) == pa.DEMON_ERR_INVALID_ARG
+    assert lib.demon_vae_encode(None, None, 1, 1, None, None, None, None) == pa.DEMON_ERR_INVALID_ARG
     l = ctypes.c_int()
     assert lib.demon_vae_receptive_field(None, ctypes.byref(l), ctypes.byref(l)) == pa.DEMON_ERR_INVALID_ARG
     lib.demon_vae_destroy(None)      # ignored
