@@ -20,8 +20,40 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-# measured with rocprofv3 --pmc (see profiles/full_60s_bf16_hbm_traffic.txt); not collectable inside this process
-TRAFFIC_BYTES_PER_STEP = {"full_60s_bf16": 15355420041}
+
+
+def measured_traffic(workload):
+    """HBM bytes per step of the convolution kernels from the committed rocprofv3 counter summary of this workload
+    (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy; not collectable inside this process), or None.  The summary
+    names the source revision it was measured on; a kernel change makes it stale until the profile is taken again."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("MFMA convolution kernels, bytes per step:"):
+                return int(line.split(":")[1].split()[0])
+    except (OSError, ValueError):
+        pass
+    return None
+
+
+def mfma_probe_rates(seconds=1.0):
+    """What the MFMA units of this GPU sustain on operands that toggle like activations (the probe beside the library):
+    on register operands, and in the stage loop of the 128 x 128 tile (weights global -> LDS, barriers, fragment reads).
+    The published peak is only reached on constant operands; the board's power limit caps everything else."""
+    import re
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2605_28657_amd", "mfma_probe")
+    out = {}
+    if not os.path.exists(exe):
+        return None
+    for name, mode in (("register_operands", "0"), ("stage_loop_128x128", "5")):
+        try:
+            r = subprocess.run([exe, mode, str(seconds), "1"], capture_output=True, text=True, timeout=60)
+            m = re.search(r"sustained\s+([0-9.]+)\s+TFLOP/s", r.stdout)
+            out[name] = {"TFLOP/s": float(m.group(1)), "frac_of_published_peak": float(m.group(1)) / PEAK_BF16_TFLOPS} if m else None
+        except (OSError, subprocess.SubprocessError):
+            out[name] = None
+    return out
 
 
 def conv_flops_per_frame(spec):
@@ -34,6 +66,31 @@ def conv_flops_per_frame(spec):
         cin = c
     head = rate * spec.head_kernel * cin * spec.out_channels
     return 2 * conv, 2 * head
+
+
+def layer_table(spec, wl, launch_ms):
+    """Per layer of the decoder (a residual unit = its two convolutions, whichever kernels run them): serialized time of
+    one step on one stream, algorithmic FLOPs (2 x MAC, halo-free), algorithmic HBM bytes of a one-kernel-per-layer data
+    flow (read the input tensor once, write the output tensor once, 16-bit activations), and both as fractions of peak."""
+    frames = wl.n_clips * wl.n_frames
+    rows, cin, rate = [], spec.latent_channels, 1
+    for l, (s_, c) in enumerate(zip(spec.strides, spec.widths)):
+        t = launch_ms.get(f"b{l}.up", 0.0)
+        rate_in, rate = rate, rate * s_
+        rows.append((f"b{l}.up {cin}->{c} x{s_}", t, 2.0 * rate * 2 * cin * c * frames, 2.0 * (rate_in * cin + rate * c) * frames))
+        for j in range(len(spec.dilations)):
+            t = launch_ms.get(f"b{l}.r{j}.conv{spec.res_kernel}", 0.0) + launch_ms.get(f"b{l}.r{j}.conv1", 0.0)
+            rows.append((f"b{l}.r{j} C={c} d={spec.dilations[j]}", t, 2.0 * rate * (spec.res_kernel + 1) * c * c * frames,
+                         2.0 * 2 * rate * c * frames))
+        cin = c
+    out = []
+    for name, ms, flop, byt in rows:
+        if ms <= 0:
+            continue
+        out.append({"layer": name, "ms": round(ms, 4), "GFLOP": round(flop / 1e9, 1), "MB": round(byt / 1e6, 1),
+                    "mfma_frac": round(flop / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 3),
+                    "hbm_frac": round(byt / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3)})
+    return out
 
 
 def sustained_power(step, torch, seconds=3.0):
@@ -180,13 +237,13 @@ def main():
                                 "channels on (f16 MFMA); fp32 accumulation; residual stream stored as IEEE half")
                    if wl.bf16 else "fp32"},
         "roofline": {
-            "kernel": "MFMA convolution kernels (conv_mfma_kernel + res_unit_fused_kernel: all convolution launches of a step, "
-                      "%d layers)" % n_conv_launches,
+            "kernel": "MFMA convolution kernels (conv_mfma_kernel, res_unit_wide_kernel, res_unit_fused_kernel): all %d "
+                      "convolution layers of a step, launched once per window group (two groups on two streams)" % n_conv_launches,
             "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": achieved / PEAK_BF16_TFLOPS,
             # L2 miss traffic of these kernels per step from rocprofv3 FETCH_SIZE + WRITE_SIZE (bytes, scaled by a plain
-            # copy; profiles/full_60s_bf16_hbm_traffic.txt); only measured for the 60 s workload
-            "traffic": TRAFFIC_BYTES_PER_STEP.get(args.workload),
+            # copy), read from profiles/<workload>_hbm_traffic.txt; null where no such profile is committed
+            "traffic": measured_traffic(args.workload),
             "algorithmic_flop": conv_f * frames,
             "time_ms": conv_ms,
         },
@@ -215,6 +272,7 @@ def main():
                 names += [f"b{l}.r{j}.conv{spec.res_kernel}", f"b{l}.r{j}.conv1"]
         names += ["head", "stitch"]
         result["launch_ms"] = dict(zip(names, [round(x, 4) for x in t]))
+        result["layers"] = layer_table(spec, wl, result["launch_ms"])
     vae.set_timing(0)
 
     if not args.no_extras:
@@ -306,26 +364,109 @@ def main():
             small[name + "_ms"] = (time.perf_counter() - q0) * 1e3 / reps
         result["playback_window"].update(small)
 
+    if not args.no_extras and wl.bf16:
+        # the alternative that stays within bf16 operands on the wide levels (hi + lo pairs, two MFMAs per k-step there)
+        v2 = DemonVAE(spec, weights, dtype=dtype, max_frames=wl.n_frames, max_clips=wl.n_clips,
+                      max_extended_frames=max(ext, wl.n_frames * wl.n_clips), wide_operands=2)
+        v2.set_timing(1)
+        for _ in range(3):
+            v2.decode_windowed(z, window=wl.window, halo=-1, out=out)
+        torch.cuda.synchronize()
+        v2.get_timing()
+        q0 = time.perf_counter()
+        for _ in range(args.steps):
+            v2.decode_windowed(z, window=wl.window, halo=-1, out=out)
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - q0) * 1e3 / args.steps
+        conv2 = float(v2.get_timing()[1])
+        result["operands_bf16x2"] = {"ms_per_step": ms2, "conv_ms": conv2,
+                                     "roofline_frac": conv_f * frames / (conv2 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                                     "note": "wide_operands = 2: hi + lo bf16 pairs instead of IEEE half operands from 512 channels on"}
+        v2.close()
+        step(); torch.cuda.synchronize()               # `out` holds the default path's waveform again
+
+        # the mirror path: windowed encode of the same shape (waveform -> moments + sampled latent), section 3.7 / Table III
+        from paper_2605_28657_amd import DemonVAEEncoder
+        enc_w = di.make_encoder_weights(spec, bf16=True)
+        enc = DemonVAEEncoder(spec, enc_w, dtype=dtype, max_frames=wl.n_frames, max_clips=wl.n_clips,
+                              max_extended_frames=max(ext, wl.n_frames * wl.n_clips))
+        wave = torch.from_numpy(np.stack([di.make_waveform(spec.out_channels, wl.n_frames * S, 40 + i) for i in range(wl.n_clips)])).to("cuda:0")
+        eps = torch.from_numpy(np.stack([di.make_noise(spec.latent_channels, wl.n_frames, 70 + i) for i in range(wl.n_clips)])).to("cuda:0")
+        mom = torch.empty((wl.n_clips, 2 * spec.latent_channels, wl.n_frames), dtype=torch.float32, device="cuda:0")
+        zl = torch.empty((wl.n_clips, spec.latent_channels, wl.n_frames), dtype=enc.latent_dtype, device="cuda:0")
+        enc.set_timing(1)
+        for _ in range(3):
+            enc.encode_windowed(wave, window=wl.window, halo=-1, eps=eps, moments=mom, latent=zl)
+        torch.cuda.synchronize()
+        enc.get_timing()
+        q0 = time.perf_counter()
+        for _ in range(args.steps):
+            enc.encode_windowed(wave, window=wl.window, halo=-1, eps=eps, moments=mom, latent=zl)
+        torch.cuda.synchronize()
+        ems = (time.perf_counter() - q0) * 1e3 / args.steps
+        eg = enc.get_timing()
+        # the encoder's convolutions: the decoder's, with the first transposed conv (C0 -> C1) replaced by a strided conv to 2 C0
+        enc_f = conv_f + 2 * spec.strides[0] * 2 * spec.latent_channels * spec.widths[0]
+        result["encode"] = {"ms_per_step": ems, "audio_s_per_s": audio_s / (ems * 1e-3),
+                            "stage_ms": {"stem": float(eg[0]), "convolutions": float(eg[1]), "sampling_step": float(eg[2])},
+                            "roofline_frac": enc_f * frames / (float(eg[1]) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                            "algorithmic_flop": enc_f * frames,
+                            "config": "windowed encode of the same shape: %d windows of %d frames + halo 6, one batch" % (n_windows, wl.window)}
+        if args.detail:
+            enc.set_timing(2)
+            enc.encode_windowed(wave, window=wl.window, halo=-1, eps=eps, moments=mom, latent=zl)
+            torch.cuda.synchronize()
+            names = ["stem"]
+            for l in range(len(spec.strides) - 1, -1, -1):
+                for j in range(len(spec.dilations)):
+                    names += [f"e{l}.r{j}.conv{spec.res_kernel}", f"e{l}.r{j}.conv1"]
+                names.append(f"e{l}.down")
+            names.append("sampling_step")
+            result["encode"]["launch_ms"] = dict(zip(names, [round(x, 4) for x in enc.get_timing()]))
+        enc.close()
+        del wave, eps, mom, zl
+
+    if not args.no_extras:
+        result["mfma_probe"] = mfma_probe_rates()
+
     if args.power:
         result["power"] = sustained_power(step, torch)
 
     if not args.no_cpu_baseline:
-        # The oracle (fp32 build, as it stands) on a bounded sample: the first windows with their halo.
+        # The oracle (fp32 build, as it stands) beside the GPU, on a bounded sample of this workload's own inputs: the
+        # whole 10 s clip of the same decoder (configs[1]) on all host cores, and a 2 s clip on one thread.
         import oracle
-        e = min(8 * wl.window, wl.n_frames)
-        hi = min(wl.n_frames, e + halo)
-        zs = lat[0][:, :hi]
+        os.environ.pop("OMP_DYNAMIC", None)
+        wl1 = di.WORKLOADS["full_10s_bf16"] if spec is di.FULL else wl
+        w1, lat1 = di.workload_inputs(wl1)
         c0 = time.perf_counter()
-        ref = oracle.decode(spec, weights, zs, dtype=np.float32)
+        ref = oracle.decode(wl1.spec, w1, lat1[0], dtype=np.float32)
         c1 = time.perf_counter()
-        g = out[0, :, :e * S].cpu().numpy()
-        err = float(np.abs(g - ref[:, :e * S]).max())
-        result["cpu_baseline"] = {
-            "value": (hi / 25.0) / (c1 - c0), "unit": "audio-s/s", "cores": oracle.omp_threads(), "kind": "oracle",
-            "sample": f"fp32 oracle, full decode of the first 8 windows with the halo (latent frames 0..{hi - 1}, "
-                      f"{hi / 25.0:.2f} s of audio) in {c1 - c0:.2f} s",
-            "gpu_vs_oracle_max_abs_on_sample": err,
-        }
+        secs = wl1.n_frames / 25.0
+        cb = {"value": secs / (c1 - c0), "unit": "audio-s/s", "cores": oracle.omp_threads(), "kind": "oracle",
+              "sample": f"fp32 oracle, full decode of the whole {secs:.0f} s clip ({wl1.name}: latent {wl1.spec.latent_channels} x "
+                        f"{wl1.n_frames}) in {c1 - c0:.2f} s on {oracle.omp_threads()} threads",
+              "GFLOP/s": (conv_flops_per_frame(wl1.spec)[0] + conv_flops_per_frame(wl1.spec)[1]) * wl1.n_frames / (c1 - c0) / 1e9}
+        if wl1 is not wl and wl.n_clips == 1:
+            # the GPU's result on the same frames of this run's clip differs from the 10 s clip's (another latent): compare on
+            # the first second of THIS workload instead
+            e1 = min(25, wl.n_frames)
+            r1 = oracle.decode(spec, weights, lat[0][:, :min(wl.n_frames, e1 + halo)], dtype=np.float32)
+            cb["gpu_vs_oracle_max_abs_on_first_second"] = float(np.abs(out[0, :, :e1 * S].cpu().numpy() - r1[:, :e1 * S]).max())
+        # one thread, 2 s of audio (ctypes releases the GIL but the loops are OpenMP: a fresh process with one thread)
+        import subprocess
+        code = ("import time, numpy as np, demon_inputs as di, oracle\n"
+                f"wl = di.WORKLOADS[{wl1.name!r}]; w, lat = di.workload_inputs(wl)\n"
+                "z = lat[0][:, :50]\n"
+                "t = time.perf_counter(); oracle.decode(wl.spec, w, z, dtype=np.float32); print(time.perf_counter() - t)\n")
+        try:
+            r = subprocess.run([sys.executable, "-c", code], cwd=ROOT, env=dict(os.environ, OMP_NUM_THREADS="1"),
+                               capture_output=True, text=True, timeout=300)
+            t1 = float(r.stdout.strip().splitlines()[-1])
+            cb["one_thread"] = {"value": 2.0 / t1, "unit": "audio-s/s", "sample": f"the first 2 s of the same clip in {t1:.2f} s on 1 thread"}
+        except Exception as ex:                                       # noqa: BLE001 -- the baseline is a report, not a gate
+            cb["one_thread"] = {"error": str(ex)[:200]}
+        result["cpu_baseline"] = cb
     vae.close()
     print(json.dumps(result))
 

@@ -17,54 +17,59 @@ template <> __device__ __forceinline__ float load_act<uint16_t>(const uint16_t* 
 template <> __device__ __forceinline__ float load_act<_Float16>(const _Float16* p) { return (float)*p; }
 
 // ---------------------------------------------------------------------------------- gather
+// The latent is [clip, channel, frame] (frames fastest), the slots are time-major [frame, channel]: a workgroup moves a
+// tile of 64 frames x 64 channels through LDS, reading runs of consecutive frames of one channel and writing runs of
+// consecutive channels of one frame, so both sides are coalesced.  With `xa` (bf16 path) it writes the first layer's
+// MFMA operand directly, snake(latent) in operand format fmt, instead of the fp32 copy.
+constexpr int GATHER_TILE = 64;
+
 template <typename T>
 __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ latent, float* __restrict__ x0,
+                                                     uint16_t* __restrict__ xa, int fmt, long long lo_off,
+                                                     const float* __restrict__ alpha, const float* __restrict__ inv_beta,
                                                      int c0, int n_frames, const Slot* __restrict__ slots)
 {
-    const Slot s = slots[blockIdx.y];
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= s.len * c0) return;
-    const int r = e / c0, c = e - r * c0;
-    x0[((size_t)s.row0 + r) * c0 + c] = load_act<T>(latent + ((size_t)s.clip * c0 + c) * n_frames + s.lo + r);
-}
-
-// bf16 path: the first layer's MFMA operand directly, snake(latent) in operand format fmt
-template <typename T>
-__global__ __launch_bounds__(256) void gather_act_kernel(const T* __restrict__ latent, uint16_t* __restrict__ xa,
-                                                         int fmt, long long lo_off, const float* __restrict__ alpha,
-                                                         const float* __restrict__ inv_beta, int c0, int n_frames,
-                                                         const Slot* __restrict__ slots)
-{
     fp16_saturate_on();
+    __shared__ float tile[GATHER_TILE][GATHER_TILE + 1];
     const Slot s = slots[blockIdx.y];
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= s.len * c0) return;
-    const int r = e / c0, c = e - r * c0;
-    const float v = snake_fast(load_act<T>(latent + ((size_t)s.clip * c0 + c) * n_frames + s.lo + r), alpha[c], inv_beta[c]);
-    const size_t idx = ((size_t)s.row0 + r) * c0 + c;
-    if (fmt == OP_F16) {
-        xa[idx] = __builtin_bit_cast(uint16_t, (_Float16)v);
-        return;
+    const int r0 = blockIdx.x * GATHER_TILE, cbase = blockIdx.z * GATHER_TILE;
+    if (r0 >= s.len) return;
+    const int lane = threadIdx.x % GATHER_TILE, sub = threadIdx.x / GATHER_TILE;      // 4 rows of 64 threads
+    for (int cc = sub; cc < GATHER_TILE; cc += 256 / GATHER_TILE) {
+        const int c = cbase + cc, r = r0 + lane;
+        if (c < c0 && r < s.len) tile[cc][lane] = load_act<T>(latent + ((size_t)s.clip * c0 + c) * n_frames + s.lo + r);
     }
-    const uint16_t hi = f32_to_bf16_bits(v);
-    xa[idx] = hi;
-    if (fmt == OP_BF16X2) xa[lo_off + idx] = f32_to_bf16_bits(v - bf16_bits_to_f32(hi));
+    __syncthreads();
+    const int c = cbase + lane;
+    if (c >= c0) return;
+    const float al = xa ? alpha[c] : 0.f, ib = xa ? inv_beta[c] : 0.f;
+    for (int rr = sub; rr < GATHER_TILE; rr += 256 / GATHER_TILE) {
+        const int r = r0 + rr;
+        if (r >= s.len) break;
+        const float raw = tile[lane][rr];
+        const size_t idx = ((size_t)s.row0 + r) * c0 + c;
+        if (!xa) { x0[idx] = raw; continue; }
+        const float v = snake_fast(raw, al, ib);
+        if (fmt == OP_F16) {
+            xa[idx] = __builtin_bit_cast(uint16_t, (_Float16)v);
+        } else {
+            const uint16_t hi = f32_to_bf16_bits(v);
+            xa[idx] = hi;
+            if (fmt == OP_BF16X2) xa[lo_off + idx] = f32_to_bf16_bits(v - bf16_bits_to_f32(hi));
+        }
+    }
 }
 
 hipError_t launch_gather(const void* latent, float* x0, int c0, int n_frames, bool bf16,
                          const Slot* slots, int n_slots, int max_len, hipStream_t stream,
                          uint16_t* xa, int xa_fmt, long long xa_lo_off, const float* alpha, const float* inv_beta)
 {
-    dim3 grid((unsigned)(((size_t)max_len * c0 + 255) / 256), (unsigned)n_slots);
-    if (xa) {
-        if (bf16)
-            hipLaunchKernelGGL(gather_act_kernel<uint16_t>, grid, dim3(256), 0, stream, (const uint16_t*)latent, xa, xa_fmt, xa_lo_off, alpha, inv_beta, c0, n_frames, slots);
-        else
-            hipLaunchKernelGGL(gather_act_kernel<float>, grid, dim3(256), 0, stream, (const float*)latent, xa, xa_fmt, xa_lo_off, alpha, inv_beta, c0, n_frames, slots);
-    } else if (bf16)
-        hipLaunchKernelGGL(gather_kernel<uint16_t>, grid, dim3(256), 0, stream, (const uint16_t*)latent, x0, c0, n_frames, slots);
+    if (xa && (!alpha || !inv_beta)) return hipErrorInvalidValue;
+    dim3 grid((unsigned)((max_len + GATHER_TILE - 1) / GATHER_TILE), (unsigned)n_slots, (unsigned)((c0 + GATHER_TILE - 1) / GATHER_TILE));
+    if (bf16)
+        hipLaunchKernelGGL(gather_kernel<uint16_t>, grid, dim3(256), 0, stream, (const uint16_t*)latent, x0, xa, xa_fmt, xa_lo_off, alpha, inv_beta, c0, n_frames, slots);
     else
-        hipLaunchKernelGGL(gather_kernel<float>, grid, dim3(256), 0, stream, (const float*)latent, x0, c0, n_frames, slots);
+        hipLaunchKernelGGL(gather_kernel<float>, grid, dim3(256), 0, stream, (const float*)latent, x0, xa, xa_fmt, xa_lo_off, alpha, inv_beta, c0, n_frames, slots);
     return hipGetLastError();
 }
 
@@ -72,9 +77,12 @@ hipError_t launch_gather(const void* latent, float* x0, int c0, int n_frames, bo
 // First layer of the encoder (the mirror of the head): Conv1d(k, channels -> C) + bias straight from the planar fp32
 // waveform of every extended window into the time-major residual stream, and with `ya` the activated operand of the
 // next layer as well.  Samples outside the window read as zero (the convolution's zero padding: the window is encoded
-// as if it were a whole clip).  A thread owns 8 consecutive output channels of one row; K = k x channels is tiny
-// (14 for stereo, k = 7), so this is plain FMA work bound by the store of the C-channel rows.
-template <typename TY, bool FAST>
+// as if it were a whole clip).  A thread owns one row: it loads its k x channels samples once (consecutive threads,
+// consecutive samples) and walks the C output channels in groups of 8, whose weights are the same for every thread
+// (scalar loads); K = k x channels is tiny (14 for stereo, k = 7), so this is bound by the store of the C-channel rows.
+constexpr int STEM_MAXK = 15 * 8;                 // taps x channels held in registers
+
+template <typename TY, int KCH>
 __global__ __launch_bounds__(256) void stem_kernel(const float* __restrict__ wave, TY* __restrict__ y, uint16_t* __restrict__ ya,
                                                    int ya_fmt, const float* __restrict__ w /*[k][ch][C]*/,
                                                    const float* __restrict__ bias, const float* __restrict__ alpha,
@@ -86,45 +94,49 @@ __global__ __launch_bounds__(256) void stem_kernel(const float* __restrict__ wav
     const long long nrows = (long long)s.len * S;
     const long long out_lo = max(0ll, (long long)s.crop * S - margin);
     const long long out_hi = min(nrows, (long long)(s.crop + s.n_int) * S + margin);
-    const int groups = C / 8;                                   // threads per row
-    const int rows_per_block = 256 / groups;
-    const int g = threadIdx.x % groups;
-    const long long n = out_lo + (long long)blockIdx.x * rows_per_block + threadIdx.x / groups;
-    if (threadIdx.x / groups >= rows_per_block || n >= out_hi) return;
+    const long long n = out_lo + (long long)blockIdx.x * 256 + threadIdx.x;
+    if (n >= out_hi) return;
     const int half = (k - 1) / 2;
-    float acc[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = bias[8 * g + e];
     const float* clip = wave + (size_t)s.clip * ch * ((size_t)n_frames * S) + (long long)s.lo * S;
-    for (int t = 0; t < k; ++t) {
+    float xv[KCH];                                 // [tap][channel]
+#pragma unroll
+    for (int q = 0; q < KCH; ++q) {
+        const int t = q / ch, c = q - t * ch;
         const long long m = n + t - half;
-        if (m < 0 || m >= nrows) continue;
-        for (int c = 0; c < ch; ++c) {
-            const float xv = clip[(size_t)c * ((size_t)n_frames * S) + m];
-            const float* wt = w + ((size_t)t * ch + c) * C + 8 * g;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] = fmaf(wt[e], xv, acc[e]);
-        }
+        xv[q] = (q < k * ch && m >= 0 && m < nrows) ? clip[(size_t)c * ((size_t)n_frames * S) + m] : 0.f;
     }
-    const size_t idx = ((size_t)s.row0 * S + n) * C + 8 * g;
-    if constexpr (sizeof(TY) == 4) {
+    const size_t row = ((size_t)s.row0 * S + n) * C;
+    for (int g = 0; g < C / 8; ++g) {
+        float acc[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) y[idx + e] = acc[e];
-    } else {
-        f16x8 hv;
+        for (int e = 0; e < 8; ++e) acc[e] = bias[8 * g + e];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) hv[e] = (_Float16)acc[e];
-        *reinterpret_cast<f16x8*>(&y[idx]) = hv;
-        if (ya) {
-            // the next layer's operand is Snake of the STORED value
-            u32x4 o;
+        for (int q = 0; q < KCH; ++q) {
+            if (q >= k * ch) break;                // uniform
+            const float* wt = w + (size_t)q * C + 8 * g;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float a0 = keep_f32(snake_fast((float)hv[2 * q], alpha[8 * g + 2 * q], inv_beta[8 * g + 2 * q]));
-                const float a1 = keep_f32(snake_fast((float)hv[2 * q + 1], alpha[8 * g + 2 * q + 1], inv_beta[8 * g + 2 * q + 1]));
-                o[q] = ya_fmt == OP_F16 ? pack_f16x2(a0, a1) : pack_bf16x2(a0, a1);
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(wt[e], xv[q], acc[e]);
+        }
+        const size_t idx = row + 8 * g;
+        if constexpr (sizeof(TY) == 4) {
+            *reinterpret_cast<float4*>(&y[idx]) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            *reinterpret_cast<float4*>(&y[idx + 4]) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        } else {
+            f16x8 hv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) hv[e] = (_Float16)acc[e];
+            *reinterpret_cast<f16x8*>(&y[idx]) = hv;
+            if (ya) {
+                // the next layer's operand is Snake of the STORED value
+                u32x4 o;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float a0 = keep_f32(snake_fast((float)hv[2 * q], alpha[8 * g + 2 * q], inv_beta[8 * g + 2 * q]));
+                    const float a1 = keep_f32(snake_fast((float)hv[2 * q + 1], alpha[8 * g + 2 * q + 1], inv_beta[8 * g + 2 * q + 1]));
+                    o[q] = ya_fmt == OP_F16 ? pack_f16x2(a0, a1) : pack_bf16x2(a0, a1);
+                }
+                *reinterpret_cast<u32x4*>(&ya[idx]) = o;
             }
-            *reinterpret_cast<u32x4*>(&ya[idx]) = o;
         }
     }
 }
@@ -133,17 +145,16 @@ hipError_t launch_stem(const float* wave, void* y, bool y_half, uint16_t* ya, in
                        const float* alpha, const float* inv_beta, int ch, int C, int k, int S, int n_frames, int margin,
                        const Slot* slots, int n_slots, int max_len, int max_int, hipStream_t stream)
 {
-    if (C % 8 != 0 || C / 8 > 256 || k < 1 || (k & 1) == 0 || margin < 0) return hipErrorInvalidValue;
+    if (C % 8 != 0 || k < 1 || (k & 1) == 0 || margin < 0 || k * ch > STEM_MAXK) return hipErrorInvalidValue;
     if (ya && (ya_fmt == OP_BF16X2 || !alpha || !inv_beta || !y_half)) return hipErrorInvalidValue;
     const long long rows = std::min((long long)max_int * S + 2ll * margin, (long long)max_len * S);
-    const int rows_per_block = 256 / (C / 8);
-    dim3 grid((unsigned)((rows + rows_per_block - 1) / rows_per_block), (unsigned)n_slots);
-    if (y_half)
-        hipLaunchKernelGGL((stem_kernel<hres_t, true>), grid, dim3(256), 0, stream, wave, (hres_t*)y, ya, ya_fmt, w, bias, alpha, inv_beta,
-                           ch, C, k, S, n_frames, margin, slots);
-    else
-        hipLaunchKernelGGL((stem_kernel<float, false>), grid, dim3(256), 0, stream, wave, (float*)y, nullptr, 0, w, bias, alpha, inv_beta,
-                           ch, C, k, S, n_frames, margin, slots);
+    dim3 grid((unsigned)((rows + 255) / 256), (unsigned)n_slots);
+    // stereo with a 7-tap stem holds 14 samples per thread; anything up to 15 taps x 8 channels takes the large form
+#define DEMON_STEM(TY_, KCH_) hipLaunchKernelGGL((stem_kernel<TY_, KCH_>), grid, dim3(256), 0, stream, wave, (TY_*)y, ya, ya_fmt, w, bias, alpha, \
+                                                 inv_beta, ch, C, k, S, n_frames, margin, slots)
+    if (y_half) { if (k * ch <= 16) DEMON_STEM(hres_t, 16); else DEMON_STEM(hres_t, STEM_MAXK); }
+    else { if (k * ch <= 16) DEMON_STEM(float, 16); else DEMON_STEM(float, STEM_MAXK); }
+#undef DEMON_STEM
     return hipGetLastError();
 }
 
