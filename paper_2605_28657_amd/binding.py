@@ -454,6 +454,10 @@ class DemonVAEEncoder:
     def get_timing(self) -> List[float]:
         return demon_vae_get_timing(self.handle)
 
+    def tap(self, layer: int, dst=None):
+        demon_vae_debug_tap(self.handle, layer, dst.data_ptr() if dst is not None else 0,
+                            dst.numel() if dst is not None else 0)
+
     def encode_windowed(self, wave, window: int, halo: int = -1, frame_begin: int = 0, frame_end: Optional[int] = None,
                         eps=None, moments=None, latent=None):
         """wave: fp32 [n_clips, channels, T * S] (or [channels, T * S]).  Returns (moments, latent); pass the tensors

@@ -76,6 +76,10 @@ struct Plan {
     // A call on this grid was recorded into a HIP graph: the graph holds the address of this entry's table (and the
     // grid's launch shapes), so the entry is never evicted while the handle lives.
     bool pinned = false;
+    // The kernel that writes this entry's table has only been recorded into a graph so far, not executed: the next call
+    // on this grid launches it again (eagerly, or into the graph being recorded, which must not depend on another graph
+    // having been replayed first).
+    bool table_pending = false;
 };
 
 // The device memory a decode call works in besides its inputs and outputs: the handle's own (allocated at create) or,
@@ -261,6 +265,12 @@ demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, i
             p.window == window && p.halo == halo && (p.n_groups == 2) == (two_groups && p.n_slots >= 2)) {
             p.last_use = v->use_counter;
             if (capturing) p.pinned = true;
+            if (p.table_pending) {
+                const int split = p.n_groups == 2 ? p.g_first[1] : p.n_slots;
+                HIP_TRY(launch_plan_slots(p.d_slots, p.n_clips, p.n_slots / p.n_clips, (int)(p.total_frames / p.n_clips), p.n_frames,
+                                          p.frame_begin, p.frame_end, p.window, p.halo, split, (int)p.g_frame0[1], stream), "window table");
+                if (!capturing) p.table_pending = false;
+            }
             *out = &p;
             return DEMON_OK;
         }
@@ -300,6 +310,7 @@ demon_status get_plan(demon_vae* v, int n_clips, int n_frames, int fb, int fe, i
             "window table");
     victim->valid = true;
     victim->pinned = capturing;
+    victim->table_pending = capturing;
     victim->n_clips = n_clips; victim->n_frames = n_frames; victim->frame_begin = fb; victim->frame_end = fe;
     victim->window = window; victim->halo = halo;
     victim->n_slots = (int)n_slots; victim->max_len = gc.max_len; victim->max_int = gc.max_int;

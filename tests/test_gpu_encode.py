@@ -145,6 +145,73 @@ def test_edge_cases(dtype, spec):
     enc.close()
 
 
+def oracle_encoder_layers(spec, w, x):
+    """Activations after every residual unit and strided conv of the encoder, from the oracle's primitives, [rows, channels]."""
+    p = di.split_encoder_weights(spec, np.asarray(w, dtype=np.float64))
+    h = oracle.conv1d(np.asarray(x, dtype=np.float64), p["stem.weight"], p["stem.bias"], 1)
+    outs = []
+    for l in range(len(spec.strides) - 1, -1, -1):
+        s = spec.strides[l]
+        for j, d in enumerate(spec.dilations):
+            q = f"e{l}.r{j}"
+            r = oracle.conv1d(oracle.snake(h, p[q + ".a1.alpha"], p[q + ".a1.beta"]), p[q + ".c1.weight"], p[q + ".c1.bias"], d)
+            r = oracle.conv1d(oracle.snake(r, p[q + ".a2.alpha"], p[q + ".a2.beta"]), p[q + ".c2.weight"], p[q + ".c2.bias"], 1)
+            h = h + r
+            outs.append(h.T.copy())
+        h = oracle.conv1d_strided(oracle.snake(h, p[f"e{l}.down.alpha"], p[f"e{l}.down.beta"]), p[f"e{l}.down.weight"],
+                                  p[f"e{l}.down.bias"], s, s // 2)
+        outs.append(h.T.copy())
+    return outs
+
+
+@pytest.mark.parametrize("dtype,spec", [("f32", di.TINY), ("bf16", STACK_V2), ("bf16", STACK_SPLIT), ("bf16", STACK_WIDE),
+                                        ("bf16", di.DecoderSpec(64, (4, 2), (128, 64), (1, 3, 9)))])
+def test_every_layer_against_oracle_primitives(dtype, spec):
+    """Reads each layer's activation back through the debug tap (full encode, one window per clip)."""
+    T = 21
+    enc, w, x, eps = make(spec, dtype, T, snake="uniform")
+    refs = oracle_encoder_layers(spec, w, x[0])
+    xt = dev(x)
+    for i, ref in enumerate(refs):
+        dst = torch.full((ref.size,), float("nan"), device="cuda:0")
+        enc.tap(i, dst)
+        enc.encode(xt)
+        torch.cuda.synchronize()
+        got = dst.cpu().numpy().reshape(ref.shape)
+        ma, rl = errors(got, ref)
+        tol = 1e-5 if dtype == "f32" else 1e-2
+        tol_abs = (1e-4 if dtype == "f32" else 2e-2) * max(1.0, float(np.abs(ref).max()))
+        assert rl <= tol and ma <= tol_abs, f"layer {i}: rel-L2 {rl:.3e} (tol {tol}), max-abs {ma:.3e} (tol {tol_abs:.3e})"
+    enc.tap(-1)
+    enc.close()
+
+
+def test_four_clips_in_one_call_and_graph_replay():
+    """A batch of clips equals clip-by-clip encodes bit for bit; an encode recorded into a HIP graph (two window groups on
+    two streams, a grid never seen before the capture) replays to the eager result, also after the waveform changed in place."""
+    spec, T = di.DecoderSpec(64, (4, 2), (128, 64), (1, 3, 9)), 40
+    enc, w, x, eps = make(spec, "bf16", T, n_clips=4, max_extended_frames=4 * 5 * T)
+    xt, et = dev(x), dev(eps)
+    m_all, z_all = enc.encode_windowed(xt, window=9, halo=-1, eps=et)
+    for c in (0, 3):
+        m1, z1 = enc.encode_windowed(xt[c:c + 1].contiguous(), window=9, halo=-1, eps=et[c:c + 1].contiguous())
+        assert torch.equal(m1[0], m_all[c]) and torch.equal(z1[0], z_all[c])
+    assert_close(m_all.cpu().numpy(), oracle.encode_moments(spec, w, x), "bf16", "four clips")
+    m_g = torch.zeros_like(m_all); z_g = torch.zeros_like(z_all)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        enc.encode_windowed(xt, window=11, halo=-1, eps=et, moments=m_g, latent=z_g)
+    for rep in range(3):
+        if rep == 1:
+            xt.copy_(dev(np.stack([di.make_waveform(2, T * spec.total_stride, 90 + i) for i in range(4)])))
+        m_e, z_e = enc.encode_windowed(xt, window=11, halo=-1, eps=et)
+        m_g.zero_(); z_g.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(m_g, m_e) and torch.equal(z_g, z_e), rep
+    enc.close()
+
+
 def test_argument_errors_and_handle_kinds():
     spec = di.TINY
     enc, w, x, eps = make(spec, "f32", 10)

@@ -610,6 +610,29 @@ def test_a_recorded_grid_survives_any_number_of_other_grids():
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         vae.decode_windowed(zt, out=out_graph, **rec)
+    # a second graph on the same grid must not depend on the first one having been replayed: the kernel that writes the
+    # grid's table has only been recorded so far, so it is recorded again
+    out_graph2 = torch.zeros_like(full)
+    g2 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g2):
+        vae.decode_windowed(zt, out=out_graph2, **rec)
+    g2.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out_graph2[:, :, 11 * S:21 * S], full[:, :, 11 * S:21 * S])
+    # nor may an eager call on the recorded grid rely on a replay having written the table
+    vae2, _, _ = make(spec, "bf16", T, max_extended_frames=2 * T)
+    g3 = torch.cuda.CUDAGraph()
+    out3 = torch.zeros_like(full)
+    with torch.cuda.graph(g3):
+        vae2.decode_windowed(zt, out=out3, **rec)
+    vae2.decode_windowed(zt, out=buf, **rec)
+    torch.cuda.synchronize()
+    assert torch.equal(buf[:, :, 11 * S:21 * S], full[:, :, 11 * S:21 * S])
+    g3.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out3[:, :, 11 * S:21 * S], full[:, :, 11 * S:21 * S])
+    del g3
+    vae2.close()
     for rep in range(3):
         for begin in range(0, T - 3, 3):                                  # 21 other grids, 16 cache entries
             vae.decode_windowed(zt, window=3, halo=-1, frame_begin=begin, frame_end=begin + 3, out=buf)
