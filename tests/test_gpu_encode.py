@@ -145,6 +145,37 @@ def test_edge_cases(dtype, spec):
     enc.close()
 
 
+def test_random_small_stacks():
+    """Ten seeded random encoder stacks (1-3 blocks, strides 2/4/6, widths that are multiples of 32, 1-3 dilations, odd kernels,
+    1-3 waveform channels, 1-2 clips, windows from one frame to longer than the clip): parity with the oracle and
+    windowed == full, in both precisions."""
+    rng = np.random.default_rng(4048)
+    done = 0
+    while done < 10:
+        nb = int(rng.integers(1, 4))
+        strides = tuple(int(rng.choice([2, 4, 6])) for _ in range(nb))
+        widths = tuple(int(rng.choice([32, 64, 96, 128, 160, 192, 256, 320, 512])) for _ in range(nb))
+        c0 = int(rng.choice([16, 32, 48, 64]))
+        dil = tuple(int(v) for v in rng.choice([1, 2, 3, 5, 9], size=int(rng.integers(1, 4))))
+        rk, hk, oc = int(rng.choice([3, 5, 7])), int(rng.choice([3, 7])), int(rng.choice([1, 2, 3]))
+        T, ncl = int(rng.integers(3, 30)), int(rng.integers(1, 3))
+        window = int(rng.integers(1, T + 3))
+        spec = di.DecoderSpec(c0, strides, widths, dil, rk, hk, oc)
+        if (rk - 1) * max(dil) > 64 or T * spec.total_stride * max(widths) > 8e6:
+            continue
+        H = max(oracle.encoder_receptive_field(spec))
+        for dtype in ("bf16", "f32"):
+            enc, w, x, eps = make(spec, dtype, T, n_clips=ncl, snake="uniform",
+                                  max_extended_frames=ncl * (T + 2 * H) * (T // window + 2))
+            xt = dev(x)
+            full, _ = enc.encode(xt)
+            assert_close(full.cpu().numpy(), oracle.encode_moments(spec, w, x), dtype, f"{spec} T={T} clips={ncl}")
+            win, _ = enc.encode_windowed(xt, window=window, halo=-1)
+            assert torch.equal(win, full), (spec, T, window)
+            enc.close()
+        done += 1
+
+
 def oracle_encoder_layers(spec, w, x):
     """Activations after every residual unit and strided conv of the encoder, from the oracle's primitives, [rows, channels]."""
     p = di.split_encoder_weights(spec, np.asarray(w, dtype=np.float64))
