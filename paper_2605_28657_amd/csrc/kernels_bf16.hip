@@ -198,11 +198,12 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
 
     // Three workgroups per CU hide each other's barriers and load latencies markedly better than two (-10 to -28 % per
     // launch), and the 128 x 128 tile gets there with one weight buffer in LDS instead of two (46 KB with the dilated
-    // conv's activation tile; the next block waits in registers and is stored between two barriers) and with the
-    // residual values requested after the K loop instead of before it (146 instead of 205 VGPRs).
+    // conv's activation tile; the next blocks wait in registers and are stored between two barriers) and with the
+    // residual values requested after the K loop instead of before it.
     constexpr int NBUF = (MT == 128) ? 1 : 2;
     constexpr bool LATE_RES = MT == 128;
-    constexpr bool PF2 = MT == 64 && NT == 64;     // the small-grid tile: weight blocks requested two stages ahead
+    constexpr bool PF2 = MT == 64 && NT == 64;     // the small-grid tile: weight blocks requested several stages ahead
+    constexpr int PFD = PF2 ? 4 : 1;               // weight blocks in flight: the block of stage t travels in register set t % PFD
     constexpr int AS_BYTES = NBUF * MT * LDK * 2, XS_BYTES = NP * XR_MAX * LDK * 2;
     constexpr int SMEM_BYTES = AS_BYTES + XS_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
@@ -265,7 +266,8 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     const unsigned x_voff = ((unsigned)((XS * n0 + minoff + xr0) * p.cin) + seg * 8u) * 2u;    // may wrap "negative": out of range
     const unsigned x_row_step = (unsigned)(RPP * p.cin) * 2u;
 
-    u32x4 ra[A_ITERS], rb[A_ITERS];        // rb: second set, only with PF2
+    u32x4 rs[PFD][A_ITERS];
+    u32x4 (&ra)[A_ITERS] = rs[0];
     u32x4 rx[X_ITERS][NP];
 
     auto load_a_to = [&](u32x4 (&r)[A_ITERS], int stage) __attribute__((always_inline)) {
@@ -352,7 +354,8 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     load_a(0);
     load_x(0);
     store_a(0);
-    if (PF2 && nstages > 1) load_a(1);
+#pragma unroll
+    for (int t = 1; t < PFD; ++t) load_a_to(rs[t], t);             // past the last stage: out of range, nothing is read
     store_x();
     __syncthreads();
 
@@ -385,51 +388,41 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
                     }
         }
     };
-    if constexpr (PF2) {
-        // Launches with few workgroups (one wave per SIMD, nothing else to hide a load behind): the weight block of
-        // stage s + 2 is requested before stage s is computed, in two register sets that alternate.
-        auto body = [&](int stage, u32x4 (&rn)[A_ITERS], u32x4 (&ri)[A_ITERS]) __attribute__((always_inline)) {
-            int ntap = tap + 1, nchunk = chunk;
-            if (ntap == p.ntaps) { ntap = 0; ++nchunk; }
-            const bool more = stage + 1 < nstages;
-            const bool new_chunk = more && nchunk != chunk;
-            if (stage + 2 < nstages) load_a_to(ri, stage + 2);
-            if (new_chunk) load_x(nchunk);
-            mma(stage);
-            if (more) {
-                if (new_chunk) {
-                    __syncthreads();              // every wave is done with the old X tile
-                    store_x();
-                }
-                store_a_from(rn, (stage + 1) & 1);
-                __syncthreads();
+    // The weight block of stage s + PFD is requested before stage s is computed, into the register set whose block
+    // (stage s) went to LDS a stage ago.  U = s % PFD is a compile-time constant (the loop is unrolled by PFD), so the sets
+    // stay in registers.  One block in flight is enough where three workgroups share the CU and cover each other's loads
+    // (two blocks: the same step time, 16 more registers); launches with few workgroups (the small-grid tile: one wave per
+    // SIMD, nothing else to hide a load behind) keep four in flight (-3.5 % on a 3 s playback window).  The request is
+    // unconditional -- past the last stage its offset is outside the descriptor and nothing is read -- because behind a
+    // branch the compiler cannot count it, and every wait for an older block would then wait for all loads.
+    auto body = [&](int stage, auto U) __attribute__((always_inline)) {
+        constexpr int u = decltype(U)::value;
+        int ntap = tap + 1, nchunk = chunk;
+        if (ntap == p.ntaps) { ntap = 0; ++nchunk; }
+        const bool more = stage + 1 < nstages;
+        const bool new_chunk = more && nchunk != chunk;
+        load_a_to(rs[u], stage + PFD);
+        if (new_chunk) load_x(nchunk);
+        mma(stage);
+        if (more) {
+            if (new_chunk || NBUF == 1) {
+                __syncthreads();              // every wave is done with the old X tile (and the single weight buffer)
+                if (new_chunk) store_x();
             }
-            tap = ntap; chunk = nchunk;
-        };
-        for (int stage = 0; stage < nstages; stage += 2) {
-            body(stage, ra, rb);
-            if (stage + 1 < nstages) body(stage + 1, rb, ra);
+            store_a_from(rs[(u + 1) % PFD], NBUF == 2 ? ((stage + 1) & 1) : 0);
+            __syncthreads();
         }
-    } else {
-        for (int stage = 0; stage < nstages; ++stage) {
-            int ntap = tap + 1, nchunk = chunk;
-            if (ntap == p.ntaps) { ntap = 0; ++nchunk; }
-            const bool more = stage + 1 < nstages;
-            const bool new_chunk = more && nchunk != chunk;
-            if (more) load_a(stage + 1);
-            if (new_chunk) load_x(nchunk);
-            mma(stage);
-            if (more) {
-                if (new_chunk || NBUF == 1) {
-                    __syncthreads();              // every wave is done with the old X tile (and the single weight buffer)
-                    if (new_chunk) store_x();
-                }
-                store_a(NBUF == 2 ? ((stage + 1) & 1) : 0);
-                __syncthreads();
-            }
-            tap = ntap; chunk = nchunk;
+        tap = ntap; chunk = nchunk;
+    };
+    for (int stage = 0; stage < nstages; stage += PFD) {
+        body(stage, std::integral_constant<int, 0>{});
+        if constexpr (PFD == 4) {
+            if (stage + 1 < nstages) body(stage + 1, std::integral_constant<int, 1 % PFD>{});
+            if (stage + 2 < nstages) body(stage + 2, std::integral_constant<int, 2 % PFD>{});
+            if (stage + 3 < nstages) body(stage + 3, std::integral_constant<int, 3 % PFD>{});
         }
     }
+    static_assert(PFD == 1 || PFD == 4, "the stage loop is unrolled by hand");
 
     if (MODE == MODE_RES && LATE_RES) load_res();
 

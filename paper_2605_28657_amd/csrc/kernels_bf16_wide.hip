@@ -173,20 +173,30 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
             }
         }
     };
-    for (int stage = 0; stage + 1 < nstages; ++stage) {
+    // Weight blocks are requested two stages ahead, alternating between the two register sets (the second set is otherwise
+    // only used by the 1x1 convolution): with one workgroup per CU (a single playback window) nothing else hides the
+    // latency of a block's load, and one stage of MFMAs is shorter than it.  The request is unconditional (past the last
+    // block it is out of the descriptor's range and reads nothing): behind a branch the compiler could not count it, and the
+    // wait for the older block would wait for it as well.
+    auto iter = [&](int stage, u32x4 (&rload)[A_ITERS], const u32x4 (&rstore)[A_ITERS]) __attribute__((always_inline)) {
         int ntap = tap + 1, nchunk = chunk;
         if (ntap == p.ntaps) { ntap = 0; ++nchunk; }
         const bool new_chunk = nchunk != chunk;
-        load_a(rs_w7, stage + 1);
+        load_set(rload, rs_w7, stage + 2);
         if (new_chunk) load_x(nchunk);
         mma_stage(stage);
         if (new_chunk) {
             __syncthreads();
             store_x();
         }
-        store_a((stage + 1) & 1);
+        store_set(rstore, (stage + 1) & 1);
         __syncthreads();
         tap = ntap; chunk = nchunk;
+    };
+    load_set(rb, rs_w7, 1);
+    for (int stage = 0; stage + 1 < nstages; stage += 2) {
+        iter(stage, ra, rb);
+        if (stage + 2 < nstages) iter(stage + 1, rb, ra);
     }
     load_a(rs_w1, 0);
     mma_stage(nstages - 1);
