@@ -163,15 +163,29 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
         const int off = p.tap0 + tap * p.tap_step - minoff;
         const uint16_t* abase = &As[(stage & 1) * CH * LDK + j * LDK + h * 8];
         const uint16_t* xbase = &Xs[(wn * 32 + j + off) * LDK + h * 8];
+        // The stage's 16 MFMAs in the order (k-step, row tile), each weight fragment requested three MFMAs before it is used
+        // (four fragment registers in rotation).  Left to itself the compiler reads the first k-step's fragments one at a time
+        // into one register set, and each of those MFMAs waits out the full LDS latency of its read.
+        static_assert(KC == 32 && TM == 8, "two k-steps of eight row tiles");
+        auto afrag = [&](int i) __attribute__((always_inline)) {
+            return *reinterpret_cast<const bf16x8*>(abase + (i & 7) * 32 * LDK + (i >> 3) * 16);
+        };
+        const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(xbase);
+        const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(xbase + 16);
+        bf16x8 a[4];
+        a[0] = afrag(0); a[1] = afrag(1); a[2] = afrag(2);
 #pragma unroll
-        for (int ks = 0; ks < KC / 16; ++ks) {
-            const bf16x8 bfr = *reinterpret_cast<const bf16x8*>(xbase + ks * 16);
-#pragma unroll
-            for (int mi = 0; mi < TM; ++mi) {
-                const bf16x8 af = *reinterpret_cast<const bf16x8*>(abase + mi * 32 * LDK + ks * 16);
-                acc[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[mi], 0, 0, 0);
-            }
+        for (int i = 0; i < 16; ++i) {
+            if (i + 3 < 16) a[(i + 3) & 3] = afrag(i + 3);
+            acc[i & 7] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], (i >> 3) ? b1 : b0, acc[i & 7], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);            // b0, b1, three fragments, the fourth
+#pragma unroll
+        for (int i = 0; i < 12; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
     };
     // Weight blocks are requested two stages ahead, alternating between the two register sets (the second set is otherwise
     // only used by the 1x1 convolution): with one workgroup per CU (a single playback window) nothing else hides the
