@@ -387,6 +387,18 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
                             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfr[pl][ni]), __builtin_bit_cast(bf16x8, af[mi]), acc[mi][ni], 0, 0, 0);
                     }
         }
+        // Order of the stage's fragment reads and MFMAs: one k-step's reads plus two ahead, then one read per MFMA, so that a
+        // fragment is requested a few MFMAs before it is used instead of right before the MFMAs of its own k-step.
+        constexpr int R = (KC / 16) * (TM + NP * TN), M = (KC / 16) * TM * TN * NP;
+        constexpr int LEAD = (TM + NP * TN + 2) < R ? (TM + NP * TN + 2) : R;
+        constexpr int PAIRS = (R - LEAD) < M ? (R - LEAD) : M;
+        __builtin_amdgcn_sched_group_barrier(0x100, LEAD, 0);
+#pragma unroll
+        for (int i = 0; i < PAIRS; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, M - PAIRS, 0);
     };
     // The weight block of stage s + PFD is requested before stage s is computed, into the register set whose block
     // (stage s) went to LDS a stage ago.  U = s % PFD is a compile-time constant (the loop is unrolled by PFD), so the sets
