@@ -252,6 +252,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
                 for (int ni = 0; ni < TN; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
         }
+        if constexpr (CH == 128) {
+            // order of the stage's fragment reads and MFMAs: one k-step's reads plus two ahead, then one read per MFMA, so
+            // that a fragment is requested a few MFMAs before it is used instead of right before the MFMAs of its own k-step
+            // (the 64-channel form has no registers left for the fragments in flight)
+            constexpr int R = (KC / 16) * (TM + TN), M = (KC / 16) * TM * TN;
+            constexpr int LEAD = (TM + TN + 2) < R ? (TM + TN + 2) : R;
+            constexpr int PAIRS = (R - LEAD) < M ? (R - LEAD) : M;
+            __builtin_amdgcn_sched_group_barrier(0x100, LEAD, 0);
+#pragma unroll
+            for (int i = 0; i < PAIRS; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, M - PAIRS, 0);
+        }
         if (more) {
             __syncthreads();                                  // every wave is done with the weight buffer (and the X tile)
             if (new_chunk) store_x();
