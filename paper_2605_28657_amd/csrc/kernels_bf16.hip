@@ -361,6 +361,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
 
     int chunk = 0, tap = 0;
     auto mma = [&](int stage) __attribute__((always_inline)) {
+        __builtin_amdgcn_s_setprio(1);
         const int off = p.tap0 + tap * p.tap_step - minoff;
         const uint16_t* abase = &As[NBUF == 2 ? (stage & 1) : 0][(wm * WTM + j) * LDK + h * 8];
         const int xoff = ((wn * WTN + j) * XS + off) * LDK + h * 8;
@@ -399,6 +400,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x008, M - PAIRS, 0);
+        __builtin_amdgcn_s_setprio(0);
     };
     // The weight block of stage s + PFD is requested before stage s is computed, into the register set whose block
     // (stage s) went to LDS a stage ago.  U = s % PFD is a compile-time constant (the loop is unrolled by PFD), so the sets

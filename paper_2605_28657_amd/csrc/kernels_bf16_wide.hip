@@ -160,6 +160,7 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
     // fetch of the first block of the 1x1 weights
     int chunk = 0, tap = 0;
     auto mma_stage = [&](int stage) __attribute__((always_inline)) {
+        __builtin_amdgcn_s_setprio(1);
         const int off = p.tap0 + tap * p.tap_step - minoff;
         const uint16_t* abase = &As[(stage & 1) * CH * LDK + j * LDK + h * 8];
         const uint16_t* xbase = &Xs[(wn * 32 + j + off) * LDK + h * 8];
@@ -186,6 +187,7 @@ __global__ __launch_bounds__(256) void res_unit_wide_kernel(WideParams p)
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        __builtin_amdgcn_s_setprio(0);
     };
     // Weight blocks are requested two stages ahead, alternating between the two register sets (the second set is otherwise
     // only used by the 1x1 convolution): with one workgroup per CU (a single playback window) nothing else hides the
