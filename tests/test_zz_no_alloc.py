@@ -53,6 +53,16 @@ def test_static_scratch_decode_equals_the_windowed_decode_twice_in_a_row(dtype, 
     vae.close()
 
 
+def test_static_scratch_decode_with_hi_lo_operand_planes():
+    """wide_operands = 2 carries some operands as two planes: the static array is carved accordingly."""
+    spec = di.DecoderSpec(64, (2, 2), (512, 128), (1, 9))
+    vae, _, z = make(spec, "bf16", 60, max_extended_frames=400, wide_operands=2)
+    zt = to_device(z, "bf16")
+    ref, out = _pair(vae, zt, window=16, halo=-1)
+    assert torch.equal(out, ref)
+    vae.close()
+
+
 def test_static_scratch_decode_rejects_what_does_not_fit():
     vae, _, z = make(di.FULL, "bf16", 8, max_extended_frames=32)
     # the handle's own workspace limits do not apply to the static entry point ...
