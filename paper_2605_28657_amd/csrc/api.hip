@@ -127,6 +127,7 @@ struct demon_vae {
     int device = 0;
     bool has_split_operands = false;   // bf16 path: some layer carries its operand as hi + lo planes
     long long small_tile_wgs = 192;    // bf16 path: launches of at most this many 128 x 128 tiles use 64 x 64 tiles
+    bool wide_tile_ok = true;          // bf16 path: dilated convs with many columns may use the 128 x 256 tile
 
     void* d_params = nullptr;          // one allocation: all packed weights, biases, Snake parameters
     std::vector<Block> blocks;         // in processing order (encoder: from the audio rate down)
@@ -400,6 +401,7 @@ demon_status run_pass(demon_vae* v, const Workspace& ws, const Plan* plan, const
         a.in_fmt = L.in_fmt;
         a.in_lo_off = a.out_lo_off = lo_off;
         a.small_tile_wgs = v->small_tile_wgs;
+        a.wide_tile_ok = v->wide_tile_ok;
         return a;
     };
     // samples per frame after a resampling layer
@@ -610,7 +612,7 @@ demon_status create_impl(const demon_vae_config* cfg, const float* host_weights,
     if (n_floats != need) return fail(DEMON_ERR_INVALID_ARG, "got %zu weights, the layer stack needs %zu", n_floats, need);
     const bool bf = cfg->dtype == DEMON_BF16;
     if (cfg->wide_operands < 0 || cfg->wide_operands > 2) return fail(DEMON_ERR_INVALID_ARG, "wide_operands must be 0, 1 or 2");
-    if (cfg->flags & ~(DEMON_VAE_FLAG_NO_FUSED | DEMON_VAE_FLAG_ONE_STREAM)) return fail(DEMON_ERR_INVALID_ARG, "unknown flag bits 0x%x", (unsigned)cfg->flags);
+    if (cfg->flags & ~(DEMON_VAE_FLAG_NO_FUSED | DEMON_VAE_FLAG_ONE_STREAM | DEMON_VAE_FLAG_NO_WIDE_TILE)) return fail(DEMON_ERR_INVALID_ARG, "unknown flag bits 0x%x", (unsigned)cfg->flags);
     // 0 in a field = the default, which the environment may have changed (see the header)
     const int g_wide_fmt = cfg->wide_operands == 1 ? (int)OP_F16 : cfg->wide_operands == 2 ? (int)OP_BF16X2 : g_env_wide_fmt;
     const bool g_allow_fused = !((cfg->flags & DEMON_VAE_FLAG_NO_FUSED) || g_env_no_fused);
@@ -640,6 +642,7 @@ demon_status create_impl(const demon_vae_config* cfg, const float* host_weights,
     v->cap_frames = cfg->max_extended_frames > 0 ? cfg->max_extended_frames : 3ll * cfg->max_frames * cfg->max_clips;
     if (encoder) stack_encoder_receptive_field(st, &v->rf_left, &v->rf_right, nullptr, nullptr);
     else stack_receptive_field(st, &v->rf_left, &v->rf_right);
+    v->wide_tile_ok = !(cfg->flags & DEMON_VAE_FLAG_NO_WIDE_TILE);
     v->small_tile_wgs = cfg->small_tile_wgs > 0 ? cfg->small_tile_wgs : cfg->small_tile_wgs < 0 ? 0 : g_env_small_tile_wgs;
     if (hipGetDevice(&v->device) != hipSuccess) return fail(DEMON_ERR_HIP, "hipGetDevice failed");
     {

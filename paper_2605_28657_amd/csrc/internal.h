@@ -80,6 +80,7 @@ struct ConvArgs {
     int in_fmt = OP_BF16, out_fmt = OP_BF16;
     long long in_lo_off = 0, out_lo_off = 0;     // OP_BF16X2: element offset of the lo plane
     long long small_tile_wgs = 192;              // bf16 path: a launch of at most this many 128 x 128 tiles uses 64 x 64 tiles (0: never)
+    bool wide_tile_ok = true;                    // bf16 path: dilated convs with many columns may use the 128 x 256 tile
 };
 
 hipError_t launch_conv_f32(const ConvArgs& a, hipStream_t stream);   // in_alpha must be nullptr (see launch_snake_f32)

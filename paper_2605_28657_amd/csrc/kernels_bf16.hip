@@ -192,7 +192,11 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     constexpr bool SPLIT_IN = IN == OP_BF16X2;
     constexpr int NP = SPLIT_IN ? 2 : 1;        // operand planes (hi, lo)
     static_assert(WM * WN == 2 || WM * WN == 4 || WM * WN == 8, "two, four or eight waves per workgroup");
-    static_assert(TM == 1 || TM == 2, "a lane owns one or two consecutive output channels");
+    static_assert(TM == 1 || TM == 2 || TM == 4, "a lane owns one channel, or one or two pairs of consecutive channels");
+    // A wave's 32-row slot tiles come in pairs (the packed order: slot j of tile 2b + k of a wave is GEMM row 64 b + 2 j + k
+    // of the wave's rows): a lane owns the channel pairs mu0 + 64 b + {0, 1}.
+    constexpr int PW = TM >= 2 ? 2 : 1;         // channels per pair
+    constexpr int PR = TM / PW;                 // pairs per lane
     static_assert(MODE != MODE_ACT || EMIT > 0, "the dilated conv only has the activated output");
     static_assert(MODE != MODE_DOWN || IN != OP_BF16X2, "the strided conv takes one operand plane");
 
@@ -308,13 +312,16 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
         }
     };
 
-    // this lane's TM consecutive GEMM rows; the accumulators start at their bias
-    const int mu0 = m0 + wm * WTM + j * TM;
-    const int o0 = (MODE == MODE_UP) ? mu0 % p.cout : mu0;
+    // this lane's GEMM rows: accumulator tile mi holds row mu0 + 64 (mi / 2) + mi % 2; the accumulators start at their bias
+    const int mu0 = m0 + wm * WTM + j * PW;
+    auto chan = [&](int mi) -> int {            // output channel of accumulator tile mi
+        const int mu = mu0 + (mi >> 1) * 64 + (mi & 1);
+        return (MODE == MODE_UP) ? mu % p.cout : mu;
+    };
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi) {
-        const float bv = p.bias[o0 + mi];
+        const float bv = p.bias[chan(mi)];
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
@@ -338,16 +345,19 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     // The residual values this lane will add are requested in one go, before the K loop or (LATE_RES) right after it:
     // issued in the epilogue where they are used, each of the loads would be waited for in turn (they cannot move
     // above the in-place stores), a chain of memory latencies per tile.
-    using pack_t = std::conditional_t<TM == 2, uint32_t, uint16_t>;     // TM 16-bit values
-    pack_t resv[MODE == MODE_RES ? TN : 1][16];
+    using pack_t = std::conditional_t<PW == 2, uint32_t, uint16_t>;     // PW 16-bit values
+    pack_t resv[MODE == MODE_RES ? PR : 1][MODE == MODE_RES ? TN : 1][16];
     auto load_res = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int ni = 0; ni < TN; ++ni)
+        for (int pr = 0; pr < PR; ++pr)
 #pragma unroll
-            for (int gq = 0; gq < 16; ++gq) {
-                if constexpr (TM == 2) resv[ni][gq] = __builtin_amdgcn_raw_buffer_load_b32(rs_y, elem(ni, gq) * 2u, 0, 0);
-                else resv[ni][gq] = __builtin_amdgcn_raw_buffer_load_b16(rs_y, elem(ni, gq) * 2u, 0, 0);
-            }
+            for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+                for (int gq = 0; gq < 16; ++gq) {
+                    const unsigned off = (elem(ni, gq) + 64u * pr) * 2u;
+                    if constexpr (PW == 2) resv[pr][ni][gq] = __builtin_amdgcn_raw_buffer_load_b32(rs_y, off, 0, 0);
+                    else resv[pr][ni][gq] = __builtin_amdgcn_raw_buffer_load_b16(rs_y, off, 0, 0);
+                }
     };
     if (MODE == MODE_RES && !LATE_RES) load_res();
 
@@ -448,25 +458,27 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
     float oa[TM], ob[TM];
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi) {
-        oa[mi] = EMIT > 0 ? p.out_alpha[o0 + mi] : 0.f;
-        ob[mi] = EMIT > 0 ? p.out_inv_beta[o0 + mi] : 0.f;
+        oa[mi] = EMIT > 0 ? p.out_alpha[chan(mi)] : 0.f;
+        ob[mi] = EMIT > 0 ? p.out_inv_beta[chan(mi)] : 0.f;
     }
+#pragma unroll
+    for (int pr = 0; pr < PR; ++pr)
 #pragma unroll
     for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
         for (int gq = 0; gq < 16; ++gq) {
-            const unsigned e = elem(ni, gq);
-            float v[TM];
+            const unsigned e = elem(ni, gq) + 64u * pr;
+            float v[PW];
 #pragma unroll
-            for (int mi = 0; mi < TM; ++mi) v[mi] = acc[mi][ni][gq];
+            for (int k = 0; k < PW; ++k) v[k] = acc[PW * pr + k][ni][gq];
             if (MODE == MODE_RES) {
 #pragma unroll
-                for (int mi = 0; mi < TM; ++mi)
-                    v[mi] += (float)__builtin_bit_cast(_Float16, (uint16_t)(resv[ni][gq] >> (16 * mi)));
+                for (int k = 0; k < PW; ++k)
+                    v[k] += (float)__builtin_bit_cast(_Float16, (uint16_t)(resv[pr][ni][gq] >> (16 * k)));
             }
             if (MODE != MODE_ACT) {
                 // half store of h; the next layer's operand is Snake of the STORED value
-                if constexpr (TM == 2) {
+                if constexpr (PW == 2) {
                     const uint32_t hb = pack_f16x2(v[0], v[1]);           // round to nearest even
                     __builtin_amdgcn_raw_buffer_store_b32(hb, rs_y, e * 2u, 0, 0);
                     const f16x2 hv = __builtin_bit_cast(f16x2, hb);
@@ -478,13 +490,13 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_mfma_kernel(MfmaParams p)
                 }
             }
             if (EMIT > 0) {
-                float a[TM];
+                float a[PW];
 #pragma unroll
-                for (int mi = 0; mi < TM; ++mi) {
-                    a[mi] = snake_fast(v[mi], oa[mi], ob[mi]);
-                    if (EMIT == 3) a[mi] = keep_f32(a[mi]);               // fp32 Snake, then one rounding
+                for (int k = 0; k < PW; ++k) {
+                    a[k] = snake_fast(v[k], oa[PW * pr + k], ob[PW * pr + k]);
+                    if (EMIT == 3) a[k] = keep_f32(a[k]);                 // fp32 Snake, then one rounding
                 }
-                if constexpr (TM == 2) {
+                if constexpr (PW == 2) {
                     const uint32_t ab = EMIT == 3 ? pack_f16x2(a[0], a[1]) : pack_bf16x2(a[0], a[1]);
                     __builtin_amdgcn_raw_buffer_store_b32(ab, rs_a, e * 2u, 0, 0);
                     if (EMIT == 2)                                         // lo plane: what the hi plane's rounding left over
@@ -511,6 +523,8 @@ static hipError_t launch_variant(const MfmaParams& p, int mode, int in_fmt, int 
 #define DEMON_CASE(MODE_, IN_, EM_) if (in_fmt == IN_ && emit == EM_) { DEMON_LAUNCH(MODE_, IN_, EM_); return hipGetLastError(); }
     if (mode == MODE_ACT) {
         DEMON_CASE(MODE_ACT, OP_BF16, 1) DEMON_CASE(MODE_ACT, OP_BF16, 2) DEMON_CASE(MODE_ACT, OP_F16, 3)
+    } else if constexpr (MT == 128 && NT == 256) {
+        return hipErrorInvalidValue;                 // the 128 x 256 tile only runs dilated convs
     } else if (mode == MODE_RES) {
         DEMON_CASE(MODE_RES, OP_BF16, 0) DEMON_CASE(MODE_RES, OP_BF16, 1) DEMON_CASE(MODE_RES, OP_BF16, 2) DEMON_CASE(MODE_RES, OP_BF16, 3)
         DEMON_CASE(MODE_RES, OP_BF16X2, 0) DEMON_CASE(MODE_RES, OP_BF16X2, 1) DEMON_CASE(MODE_RES, OP_BF16X2, 2)
@@ -586,6 +600,14 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
         small_tile = true;
         v.MT = 64; v.NT = 64; p.pack_ratio = 2;
     }
+    // Dilated convs with enough columns run a 128 x 256 tile on the same packed weights (four waves side by side, every
+    // wave all 128 rows of its 64 columns: 0.75 instead of 1 fragment read per MFMA, half the weight staging per column, two
+    // workgroups per CU): -7 % on the 512-channel dilated convs.  Only when the launch still fills every CU twice: with fewer
+    // workgroups the larger tile's last round costs more than the tile saves (+5 % on the 1024-channel level of a 60 s clip).
+    // Same K order, so the results are bit-identical to the 128 x 128 tile's.
+    const bool wide_n = a.wide_tile_ok && variant == 0 && !small_tile && mode == MODE_ACT && a.in_fmt != OP_BF16X2 &&
+                        ((ncols + 255) / 256) * (M / v.MT) * a.n_slots >= 512;
+    if (wide_n) v.NT = 256;
     const long long ntiles = (ncols + v.NT - 1) / v.NT;
     const int mtiles = M / v.MT;
     const long long ntiles8 = (ntiles + 7) / 8 * 8;           // whole groups of 8 column tiles; the surplus exits at once
@@ -595,7 +617,8 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     p.xcd_group = w_fits_l2 ? 1 : 0;
     dim3 grid(m_fastest ? (unsigned)(ntiles8 * mtiles) : (unsigned)ntiles, (unsigned)a.n_slots, m_fastest ? 1u : (unsigned)mtiles);
     switch (variant) {
-        case 0: return small_tile ? launch_variant<64, 64, 64, 1, 2>(p, mode, a.in_fmt, emit, grid, stream)
+        case 0: if (wide_n) return launch_variant<128, 256, 64, 1, 4>(p, mode, a.in_fmt, emit, grid, stream);
+                return small_tile ? launch_variant<64, 64, 64, 1, 2>(p, mode, a.in_fmt, emit, grid, stream)
                                   : launch_variant<128, 128, 64, 2, 2>(p, mode, a.in_fmt, emit, grid, stream);
         case 1: return launch_variant<64, 256, 64, 1, 4>(p, mode, a.in_fmt, emit, grid, stream);
         default: return launch_variant<32, 128, 16, 1, 4>(p, mode, a.in_fmt, emit, grid, stream);

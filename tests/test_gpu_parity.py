@@ -350,6 +350,24 @@ print("ok")
     assert np.all(np.isfinite(got["small"])) and np.abs(got["small"]).max() > 1e-3
 
 
+def test_wide_column_tile_is_bit_identical_to_the_square_tile():
+    """Dilated convs with many columns run a 128 x 256 tile on the same packed weights, in the same K order: a long clip
+    on a stack with a 512-channel level selects it (one window: 2 x 17000 rows, 4 row tiles), the flag switches it off."""
+    spec = di.DecoderSpec(64, (2, 2), (512, 64), (1, 9))
+    T = 17000
+    vae, w, z = make(spec, "bf16", T, max_extended_frames=T)
+    ref_vae = pa.DemonVAE(spec, w, dtype="bf16", max_frames=T, max_extended_frames=T, flags=pa.DEMON_VAE_FLAG_NO_WIDE_TILE)
+    zt = to_device(z, "bf16")
+    a = vae.decode(zt)
+    b = ref_vae.decode(zt)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    # and against the oracle on the first frames (a clip edge and the interior of the first tiles)
+    ref = oracle.decode_windowed(spec, w, z[0], window=24, halo=max(oracle.receptive_field(spec)), frame_begin=0, frame_end=24)
+    assert_close(a[0, :, :24 * spec.total_stride].cpu().numpy(), ref, "bf16", "first frames")
+    vae.close(); ref_vae.close()
+
+
 def test_wide_levels_with_hi_lo_bf16_operands_in_a_subprocess():
     """DEMON_VAE_WIDE_OPERANDS=bf16x2 (read when the library loads) carries the operands of the levels that are at least
     512 channels wide as hi + lo bf16 pairs instead of half; same parity bar, bit-identical windowed == full, also on
