@@ -524,7 +524,9 @@ static hipError_t launch_variant(const MfmaParams& p, int mode, int in_fmt, int 
     if (mode == MODE_ACT) {
         DEMON_CASE(MODE_ACT, OP_BF16, 1) DEMON_CASE(MODE_ACT, OP_BF16, 2) DEMON_CASE(MODE_ACT, OP_F16, 3)
     } else if constexpr (MT == 128 && NT == 256) {
-        return hipErrorInvalidValue;                 // the 128 x 256 tile only runs dilated convs
+        if (mode != MODE_UP) return hipErrorInvalidValue;         // the 128 x 256 tile runs dilated and transposed convs
+        DEMON_CASE(MODE_UP, OP_BF16, 0) DEMON_CASE(MODE_UP, OP_BF16, 1) DEMON_CASE(MODE_UP, OP_BF16, 2) DEMON_CASE(MODE_UP, OP_BF16, 3)
+        DEMON_CASE(MODE_UP, OP_F16, 1) DEMON_CASE(MODE_UP, OP_F16, 3)
     } else if (mode == MODE_RES) {
         DEMON_CASE(MODE_RES, OP_BF16, 0) DEMON_CASE(MODE_RES, OP_BF16, 1) DEMON_CASE(MODE_RES, OP_BF16, 2) DEMON_CASE(MODE_RES, OP_BF16, 3)
         DEMON_CASE(MODE_RES, OP_BF16X2, 0) DEMON_CASE(MODE_RES, OP_BF16X2, 1) DEMON_CASE(MODE_RES, OP_BF16X2, 2)
@@ -605,7 +607,10 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     // workgroups per CU): -7 % on the 512-channel dilated convs.  Only when the launch still fills every CU twice: with fewer
     // workgroups the larger tile's last round costs more than the tile saves (+5 % on the 1024-channel level of a 60 s clip).
     // Same K order, so the results are bit-identical to the 128 x 128 tile's.
-    const bool wide_n = a.wide_tile_ok && variant == 0 && !small_tile && mode == MODE_ACT && a.in_fmt != OP_BF16X2 &&
+    // Transposed convs too where the weight matrix is small (at most four row tiles: -8 ... -12 % at 128 and 256 input
+    // channels; with more row tiles the square tile is as fast or faster).
+    const bool wide_n = a.wide_tile_ok && variant == 0 && !small_tile && a.in_fmt != OP_BF16X2 &&
+                        (mode == MODE_ACT || (mode == MODE_UP && M / v.MT <= 4)) &&
                         ((ncols + 255) / 256) * (M / v.MT) * a.n_slots >= 512;
     if (wide_n) v.NT = 256;
     const long long ntiles = (ncols + v.NT - 1) / v.NT;
