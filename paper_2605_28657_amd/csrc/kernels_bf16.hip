@@ -604,14 +604,14 @@ hipError_t launch_conv_bf16(const ConvArgs& a, int variant, hipStream_t stream)
     }
     // Dilated convs with enough columns run a 128 x 256 tile on the same packed weights (four waves side by side, every
     // wave all 128 rows of its 64 columns: 0.75 instead of 1 fragment read per MFMA, half the weight staging per column, two
-    // workgroups per CU): -7 % on the 512-channel dilated convs.  Only when the launch still fills every CU twice: with fewer
-    // workgroups the larger tile's last round costs more than the tile saves (+5 % on the 1024-channel level of a 60 s clip).
+    // workgroups per CU): -7 % on the 512-channel dilated convs.  Only when the launch still has 768 such workgroups (three per CU):
+    // with fewer the larger tile's last round costs more than the tile saves (+5 % on the 1024-channel level of a 60 s clip).
     // Same K order, so the results are bit-identical to the 128 x 128 tile's.
     // Transposed convs too where the weight matrix is small (at most four row tiles: -8 ... -12 % at 128 and 256 input
     // channels; with more row tiles the square tile is as fast or faster).
     const bool wide_n = a.wide_tile_ok && variant == 0 && !small_tile && a.in_fmt != OP_BF16X2 &&
                         (mode == MODE_ACT || (mode == MODE_UP && M / v.MT <= 4)) &&
-                        ((ncols + 255) / 256) * (M / v.MT) * a.n_slots >= 512;
+                        ((ncols + 255) / 256) * (M / v.MT) * a.n_slots >= 768;
     if (wide_n) v.NT = 256;
     const long long ntiles = (ncols + v.NT - 1) / v.NT;
     const int mtiles = M / v.MT;
