@@ -76,6 +76,7 @@ typedef enum {
 #define DEMON_VAE_FLAG_NO_FUSED   1   /* every residual unit as two kernels (no fused units)          */
 #define DEMON_VAE_FLAG_ONE_STREAM 2   /* no internal second stream: all launches on the given stream  */
 #define DEMON_VAE_FLAG_NO_WIDE_TILE 4 /* dilated convs never use the 128 x 256 tile (bit-identical results) */
+#define DEMON_VAE_FLAG_NO_HEAD_FUSION 8 /* the head always runs as its own kernel (bit-identical results) */
 
 /* Layer stack and workspace limits.  Arrays are read during the call only. */
 typedef struct {

@@ -9,4 +9,4 @@ from .binding import (DemonVAE, DemonVAEEncoder, DemonError, demon_vae_create_en
                       demon_vae_set_timing, demon_vae_get_timing, demon_vae_latent_similarity, demon_vae_crossfade,
                       latent_similarity, crossfade,
                       DEMON_OK, DEMON_ERR_INVALID_ARG, DEMON_ERR_UNSUPPORTED, DEMON_ERR_WORKSPACE, DEMON_ERR_HIP,
-                      DEMON_F32, DEMON_BF16, DEMON_VAE_FLAG_NO_FUSED, DEMON_VAE_FLAG_ONE_STREAM, DEMON_VAE_FLAG_NO_WIDE_TILE)
+                      DEMON_F32, DEMON_BF16, DEMON_VAE_FLAG_NO_FUSED, DEMON_VAE_FLAG_ONE_STREAM, DEMON_VAE_FLAG_NO_WIDE_TILE, DEMON_VAE_FLAG_NO_HEAD_FUSION)

@@ -36,7 +36,7 @@ class _Config(ctypes.Structure):
                 ("max_extended_frames", ctypes.c_longlong),
                 ("wide_operands", ctypes.c_int), ("flags", ctypes.c_int), ("small_tile_wgs", ctypes.c_int)]
 
-DEMON_VAE_FLAG_NO_FUSED, DEMON_VAE_FLAG_ONE_STREAM, DEMON_VAE_FLAG_NO_WIDE_TILE = 1, 2, 4
+DEMON_VAE_FLAG_NO_FUSED, DEMON_VAE_FLAG_ONE_STREAM, DEMON_VAE_FLAG_NO_WIDE_TILE, DEMON_VAE_FLAG_NO_HEAD_FUSION = 1, 2, 4, 8
 
 
 class _Window(ctypes.Structure):

@@ -128,6 +128,7 @@ struct demon_vae {
     bool has_split_operands = false;   // bf16 path: some layer carries its operand as hi + lo planes
     long long small_tile_wgs = 192;    // bf16 path: launches of at most this many 128 x 128 tiles use 64 x 64 tiles
     bool wide_tile_ok = true;          // bf16 path: dilated convs with many columns may use the 128 x 256 tile
+    bool head_fusable = false;         // bf16 path: the last layer is a fused 64-channel unit that can run the head in its kernel
 
     void* d_params = nullptr;          // one allocation: all packed weights, biases, Snake parameters
     std::vector<Block> blocks;         // in processing order (encoder: from the audio rate down)
@@ -346,6 +347,8 @@ demon_status run_pass(demon_vae* v, const Workspace& ws, const Plan* plan, const
     const bool bf = v->dtype == DEMON_BF16;
     const bool enc = v->encoder;
     const bool dual = wants_two_groups(v);
+    // the head inside the last unit's kernel, unless the debug tap wants that unit's output in memory
+    const bool head_in_unit = v->head_fusable && !(v->tap_layer >= 0 && v->tap_dst);
     const int n_frames = io.n_frames;
     const Slot* slots = plan->d_slots;
     const int ns = plan->n_slots, ml = plan->max_len;
@@ -499,6 +502,11 @@ demon_status run_pass(demon_vae* v, const Workspace& ws, const Plan* plan, const
                 f.slots = gs; f.n_slots = gn; f.max_len = ml; f.max_int = plan->max_int; f.margin = U.pointwise.margin;
                 f.r = r; f.c = U.dilated.cin; f.ntaps = U.dilated.ntaps; f.dil = U.dilated.dil;
                 if (C && C->in_fmt != OP_BF16) return fail(DEMON_ERR_UNSUPPORTED, "a fused unit cannot feed a layer with wide operands");
+                if (last && head_in_unit) {
+                    f.hw = v->head_wfrag; f.hb = v->head_bias; f.ha = v->head_alpha; f.hib = v->head_inv_beta;
+                    f.hy = ws.head_out + plan->g_frame0[g] * r; f.total_rows = plan->total_frames * r;
+                    f.oc = v->st.out_channels; f.hk = v->st.head_kernel;
+                }
                 HIP_TRY(launch_res_unit_fused(f, gst), "fused residual unit");
                 std::swap(cur, other);
                 HIP_TRY(mark(2), "event");
@@ -570,7 +578,7 @@ demon_status run_pass(demon_vae* v, const Workspace& ws, const Plan* plan, const
     }
     // head and stitch, group by group on the caller's stream; the window waveforms are planar [channel][all rows]
     const long long total_rows = plan->total_frames * r;
-    for (int gi = 0; gi < plan->n_groups; ++gi) {
+    for (int gi = 0; gi < plan->n_groups && !head_in_unit; ++gi) {
         select_group(gi, stream);
         const void* x = final_base + goff() * hbytes;
         float* y = ws.head_out + plan->g_frame0[gi] * r;
@@ -612,7 +620,7 @@ demon_status create_impl(const demon_vae_config* cfg, const float* host_weights,
     if (n_floats != need) return fail(DEMON_ERR_INVALID_ARG, "got %zu weights, the layer stack needs %zu", n_floats, need);
     const bool bf = cfg->dtype == DEMON_BF16;
     if (cfg->wide_operands < 0 || cfg->wide_operands > 2) return fail(DEMON_ERR_INVALID_ARG, "wide_operands must be 0, 1 or 2");
-    if (cfg->flags & ~(DEMON_VAE_FLAG_NO_FUSED | DEMON_VAE_FLAG_ONE_STREAM | DEMON_VAE_FLAG_NO_WIDE_TILE)) return fail(DEMON_ERR_INVALID_ARG, "unknown flag bits 0x%x", (unsigned)cfg->flags);
+    if (cfg->flags & ~(DEMON_VAE_FLAG_NO_FUSED | DEMON_VAE_FLAG_ONE_STREAM | DEMON_VAE_FLAG_NO_WIDE_TILE | DEMON_VAE_FLAG_NO_HEAD_FUSION)) return fail(DEMON_ERR_INVALID_ARG, "unknown flag bits 0x%x", (unsigned)cfg->flags);
     // 0 in a field = the default, which the environment may have changed (see the header)
     const int g_wide_fmt = cfg->wide_operands == 1 ? (int)OP_F16 : cfg->wide_operands == 2 ? (int)OP_BF16X2 : g_env_wide_fmt;
     const bool g_allow_fused = !((cfg->flags & DEMON_VAE_FLAG_NO_FUSED) || g_env_no_fused);
@@ -907,6 +915,12 @@ demon_status create_impl(const demon_vae_config* cfg, const float* host_weights,
     };
     for (size_t i = 0; i + 1 < v->steps.size(); ++i) v->steps[i].consumer = operand_layer(v->steps[i + 1]);
     v->first_consumer = operand_layer(v->steps[0]);
+    // the head can run inside the last residual unit's kernel when that unit is the fused 64-channel form
+    if (!encoder && head_mfma && !(cfg->flags & DEMON_VAE_FLAG_NO_HEAD_FUSION) && !v->steps.empty()) {
+        const Step& last = v->steps.back();
+        v->head_fusable = last.unit && last.unit->fused && last.unit->dilated.cin == 64 && oc <= 8 && hk <= 7 &&
+                          last.unit->pointwise.margin == (hk - 1) / 2;
+    }
 
     *out = v.release();
     return DEMON_OK;

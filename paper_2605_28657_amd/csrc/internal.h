@@ -113,6 +113,11 @@ struct FusedArgs {
     const float* a1; const float* ib1; const float* a2; const float* ib2;
     const Slot* slots; int n_slots, max_len, max_int, margin;
     int r, c, ntaps, dil;
+    // optional: the decoder's head in the same kernel (64 channels, the unit feeds nothing else; y is then not written).
+    // hw: half-precision MFMA fragments (pack_head_mfma), hb bias, ha / hib the head's Snake, hy planar window waveforms
+    // [oc][total_rows] (rows counted like the unit's), hk the head's kernel size (odd, <= 7)
+    const uint16_t* hw = nullptr; const float* hb = nullptr; const float* ha = nullptr; const float* hib = nullptr;
+    float* hy = nullptr; long long total_rows = 0; int oc = 0, hk = 0;
 };
 hipError_t launch_res_unit_fused(const FusedArgs& a, hipStream_t stream);
 void pack_w1_fused(const float* w, int C, uint16_t* dst);

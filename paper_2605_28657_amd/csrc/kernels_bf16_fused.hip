@@ -37,6 +37,12 @@ struct FusedParams {
     const float* a3; const float* ib3;    // Snake of the consumer (EMIT)
     const Slot* slots;
     int r, ntaps, tap0, tap_step, nchunks, margin;
+    // HEAD: the decoder's head (Snake -> Conv1d(hk) -> tanh) on this unit's output, in the same kernel
+    const uint16_t* hw;          // half-precision MFMA fragments of the head weights (pack_head_mfma)
+    const float* hb; const float* ha; const float* hib;
+    float* hy;                   // planar window waveforms [oc][total_rows]
+    long long total_rows;
+    int oc, hk;
 };
 
 // channel that k-slot kp (0..C-1) of the permuted 1x1 weight matrix multiplies
@@ -55,9 +61,18 @@ void pack_w1_fused(const float* w /*[C][C]*/, int C, uint16_t* dst)
     }
 }
 
-template <int CH, int TN, bool EMIT>
+// HEAD (64 channels, no EMIT): the unit is the decoder's last layer before the head.  Its output rows do not go to memory:
+// Snake with the head's parameters, rounded to half, they fill an LDS tile (the activation tile's space, free after the K
+// loop), the head's weight fragments take the weight buffer, and every wave runs the head's k x 4 k-steps on its 64
+// columns exactly as head_mfma_kernel does (same operands, same order: the same bits).  A tile's head outputs need the
+// unit's outputs (k-1)/2 columns to both sides, so tiles advance by NT - (k-1) columns and the first and last (k-1)/2
+// columns of a tile only serve as context.  Saves the unit's 128-byte-per-row store, the head's read of it and a launch.
+constexpr int FUSED_HEAD_MAXK = 7;      // k x 64 weight pieces of 16 bytes travel in two registers per thread
+
+template <int CH, int TN, bool EMIT, bool HEAD = false>
 __global__ __launch_bounds__(256, (CH == 128 && TN == 2) ? 2 : 3) void res_unit_fused_kernel(FusedParams p)
 {
+    static_assert(!HEAD || (CH == 64 && !EMIT), "the head follows a 64-channel unit that feeds nothing else");
     fp16_saturate_on();
     constexpr int KC = 64;
     constexpr int LDK = KC + 8;
@@ -101,8 +116,11 @@ __global__ __launch_bounds__(256, (CH == 128 && TN == 2) ? 2 : 3) void res_unit_
     // XCD at about the same time.  The eighths rotate with the window index (the last one may be short).
     const int tiles8 = (int)(gridDim.x >> 3);
     const int tile = (int)((blockIdx.x + blockIdx.y) & 7u) * tiles8 + (int)(blockIdx.x >> 3);
-    const int n0 = out_lo + tile * NT;
-    if (n0 >= out_hi) return;
+    const int hhalf = HEAD ? (p.hk - 1) / 2 : 0;
+    // HEAD: the unit's columns start (k-1)/2 before the interior also at a clip edge (rows before the window are zero)
+    const int n0 = HEAD ? s.crop * p.r - hhalf + tile * (NT - 2 * hhalf) : out_lo + tile * NT;
+    const int h_lo = s.crop * p.r, h_hi = (s.crop + s.n_int) * p.r;     // HEAD: the interior rows the head produces
+    if (HEAD ? (n0 + hhalf >= h_hi) : (n0 >= out_hi)) return;
     const long long rowbase = (long long)s.row0 * p.r;
 
     const int last_off = p.tap0 + (p.ntaps - 1) * p.tap_step;
@@ -346,6 +364,30 @@ __global__ __launch_bounds__(256, (CH == 128 && TN == 2) ? 2 : 3) void res_unit_
         a3v[mo] = EMIT ? p.a3[j * TM + mo] : 0.f;
         i3v[mo] = EMIT ? p.ib3[j * TM + mo] : 0.f;
     }
+    // HEAD: the tile of head operands takes the activation tile's space (nothing reads that after the K loop; every wave
+    // has passed the barriers that staged the 1x1 weights), rows shifted by (k-1)/2 so that a tap is a row offset >= 0
+    constexpr int LDH = CH + 8;
+    _Float16* Hs = reinterpret_cast<_Float16*>(smem + AS_BYTES);
+    static_assert(!HEAD || (NT + FUSED_HEAD_MAXK - 1) * LDH * 2 <= XS_BYTES, "the head's operand tile fits the activation tile's space");
+    float hav[TM], hiv[TM];
+    u32x4 rhw[2];                 // the head's weight fragments on their way to LDS (at most 2 x 256 pieces of 16 bytes)
+    const int n_hw = HEAD ? p.hk * (CH / 16) * 2 * 8 : 0;
+    if constexpr (HEAD) {
+#pragma unroll
+        for (int mo = 0; mo < TM; ++mo) { hav[mo] = p.ha[j * TM + mo]; hiv[mo] = p.hib[j * TM + mo]; }
+        const u32x4* src = reinterpret_cast<const u32x4*>(p.hw);          // [fragment][lane = h * 32 + channel][8 halves]
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int q = tid + it * 256;
+            rhw[it] = q < n_hw ? src[(q / 8) * 32 + q % 8] : u32x4{0, 0, 0, 0};
+        }
+        // rows of the operand tile past the unit's columns (context of columns that are not produced): defined, unused
+        for (int q = tid; q < 2 * hhalf * (CH / 2); q += 256) {
+            const int rr = q / (CH / 2), cc = q % (CH / 2);
+            const int row = rr < hhalf ? rr : NT + rr;
+            *reinterpret_cast<uint32_t*>(&Hs[row * LDH + 2 * cc]) = 0u;
+        }
+    }
 #pragma unroll
     for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
@@ -360,6 +402,19 @@ __global__ __launch_bounds__(256, (CH == 128 && TN == 2) ? 2 : 3) void res_unit_
             for (int mo = 0; mo < TM; ++mo) {
                 v[mo] = acc[mo][ni][gq] + (float)r[mo];
                 o[mo] = (_Float16)v[mo];                         // round to nearest even
+            }
+            if constexpr (HEAD) {
+                // the head's operand: Snake of the (half) value the unit would have stored, in fp32, rounded once to half;
+                // rows outside the window are the head conv's zero padding
+                const int col = wn * WTN + ni * 32 + 8 * (gq >> 2) + 4 * h + (gq & 3);
+                const int n = n0 + col;
+                f16x2 av = {(_Float16)0.f, (_Float16)0.f};
+                if (n >= 0 && n < nrows) {
+                    av[0] = (_Float16)keep_f32(snake_fast((float)o[0], hav[0], hiv[0]));
+                    av[1] = (_Float16)keep_f32(snake_fast((float)o[1], hav[1], hiv[1]));
+                }
+                *reinterpret_cast<f16x2*>(&Hs[(col + hhalf) * LDH + j * TM]) = av;
+                continue;
             }
             if constexpr (TM == 2) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, o), rs_y, off, 0, 2);
             else __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), rs_y, off, 0, 2);
@@ -376,6 +431,52 @@ __global__ __launch_bounds__(256, (CH == 128 && TN == 2) ? 2 : 3) void res_unit_
                 else { const u32x2 s2 = {sh[0], sh[1]}; __builtin_amdgcn_raw_buffer_store_b64(s2, rs_a, off, 0, 2); }
             }
         }
+    if constexpr (HEAD) {
+        // ---- the head on this tile: weights -> LDS (over the 1x1 weights), then per wave 2 column tiles x k taps x 4 k-steps
+        uint16_t* Ws = reinterpret_cast<uint16_t*>(smem);          // [fragment][h][channel < 8][8 halves]
+        __syncthreads();                                   // the operand tile is complete; nobody reads the 1x1 weights any more
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int q = tid + it * 256;
+            if (q < n_hw) reinterpret_cast<u32x4*>(Ws)[q] = rhw[it];
+        }
+        __syncthreads();
+        typedef _Float16 f16x8v __attribute__((ext_vector_type(8)));
+        constexpr int KS = CH / 16;
+        float hbv[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) hbv[q] = (4 * h + q < p.oc) ? p.hb[4 * h + q] : 0.f;
+        f32x16 hacc[2];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) hacc[mi][q] = q < 4 ? hbv[q] : 0.f;
+        for (int t = 0; t < p.hk; ++t) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                f16x8v bw = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (j < 8) bw = *reinterpret_cast<const f16x8v*>(&Ws[(((t * KS + ks) * 2 + h) * 8 + j) * 8]);
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) {
+                    const f16x8v av = *reinterpret_cast<const f16x8v*>(&Hs[(wn * WTN + mi * 32 + j + t) * LDH + ks * 16 + h * 8]);
+                    // weights as the row operand: the accumulator tile is [output channel][time]
+                    hacc[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bw, av, hacc[mi], 0, 0, 0);
+                }
+            }
+        }
+        // lane (j, h) holds time column j and output channels 4 h + {0..3} in its first four registers
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+            const int col = wn * WTN + mi * 32 + j;
+            const int n = n0 + col;
+            if (col < hhalf || col >= NT - hhalf || n < h_lo || n >= h_hi) continue;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = 4 * h + q;
+                if (c < p.oc) p.hy[(size_t)c * p.total_rows + rowbase + n] = tanhf(hacc[mi][q]);
+            }
+        }
+    }
 }
 
 hipError_t launch_res_unit_fused(const FusedArgs& a, hipStream_t stream)
@@ -392,6 +493,19 @@ hipError_t launch_res_unit_fused(const FusedArgs& a, hipStream_t stream)
     if ((long long)a.max_len * a.r * a.c * (long long)sizeof(hres_t) > 0xf0000000ll) return hipErrorInvalidValue;
     const long long out_rows = std::min((long long)a.max_int * a.r + 2ll * a.margin, (long long)a.max_len * a.r);
     const bool emit = a.ya != nullptr;
+    if (a.hw) {
+        // the unit before the head, with the head in the same kernel: tiles advance by NT - (k - 1) interior columns
+        if (a.c != 64 || a.ya || !a.hy || !a.hb || !a.ha || !a.hib || a.hk < 1 || (a.hk & 1) == 0 || a.hk > FUSED_HEAD_MAXK ||
+            a.oc < 1 || a.oc > 8 || a.margin < (a.hk - 1) / 2) return hipErrorInvalidValue;
+        p.hw = a.hw; p.hb = a.hb; p.ha = a.ha; p.hib = a.hib; p.hy = a.hy; p.total_rows = a.total_rows; p.oc = a.oc; p.hk = a.hk;
+        constexpr int NT = 4 * 32 * 2;
+        const long long interior = (long long)a.max_int * a.r;
+        const long long per_tile = NT - (a.hk - 1);
+        dim3 grid((unsigned)((interior + per_tile - 1) / per_tile + 7) / 8 * 8, (unsigned)a.n_slots);
+        hipLaunchKernelGGL((res_unit_fused_kernel<64, 2, false, true>), grid, dim3(256), 0, stream, p);
+        return hipGetLastError();
+    }
+    p.hw = nullptr; p.hb = p.ha = p.hib = nullptr; p.hy = nullptr; p.total_rows = 0; p.oc = p.hk = 0;
     if (a.c == 64) {
         constexpr int NT = 4 * 32 * 2;
         dim3 grid((unsigned)((out_rows + NT - 1) / NT + 7) / 8 * 8, (unsigned)a.n_slots);       // whole groups of 8 tiles; the surplus exits at once

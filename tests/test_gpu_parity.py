@@ -719,3 +719,28 @@ def test_transposed_conv_feeding_wide_operands_without_residual_units():
         assert_close(full, ref, "bf16", f"wide_operands={wide}")
         assert np.array_equal(win, full)
         vae.close()
+
+
+@pytest.mark.parametrize("spec,T,window", [(di.DecoderSpec(64, (4, 2), (128, 64), (1, 3, 9)), 45, 11), (STACK_V1, 150, 37),
+                                           (di.DecoderSpec(64, (2,), (64,), (1, 3, 9), 7, 5, 1), 200, 64)])
+def test_head_inside_the_last_unit_is_bit_identical_to_the_head_kernel(spec, T, window):
+    """When the last layer is the fused 64-channel unit, the head runs inside its kernel (the unit's output never goes
+    to memory): the same operands in the same order as the head kernel, so the same bits -- full and windowed, at clip
+    edges, with ragged windows, two clips, partial ranges -- and the oracle's values."""
+    vae, w, z = make(spec, "bf16", T, n_clips=2, max_extended_frames=100 * T)
+    ref_vae = pa.DemonVAE(spec, w, dtype="bf16", max_frames=T, max_clips=2, max_extended_frames=100 * T,
+                          flags=pa.DEMON_VAE_FLAG_NO_HEAD_FUSION)
+    zt = to_device(z, "bf16")
+    S = spec.total_stride
+    for kw in (dict(window=T, halo=0), dict(window=window, halo=-1), dict(window=7, halo=-1, frame_begin=5, frame_end=T - 3), dict(window=1, halo=-1)):
+        a = torch.full((2, spec.out_channels, T * S), -5.0, device="cuda:0")
+        b = torch.full((2, spec.out_channels, T * S), -5.0, device="cuda:0")
+        vae.decode_windowed(zt, out=a, **kw)
+        ref_vae.decode_windowed(zt, out=b, **kw)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b), kw
+    assert_close(vae.decode(zt).cpu().numpy(), oracle.decode(spec, w, z), "bf16", "head inside the unit")
+    pcm_a = vae.decode_windowed_pcm16(zt, window=window, halo=-1)
+    pcm_b = ref_vae.decode_windowed_pcm16(zt, window=window, halo=-1)
+    assert torch.equal(pcm_a, pcm_b)
+    vae.close(); ref_vae.close()
