@@ -256,9 +256,14 @@ def main():
     head_bytes = rows * spec.widths[-1] * (2 if wl.bf16 else 4) + rows * spec.out_channels * 4
     stitch_bytes = 2 * rows * spec.out_channels * 4
     result["hbm_kernels"] = {
-        "head": {"GB/s": head_bytes / (groups[2] * 1e-3) / 1e9, "frac": head_bytes / (groups[2] * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "stitch": {"GB/s": stitch_bytes / (groups[3] * 1e-3) / 1e9, "frac": stitch_bytes / (groups[3] * 1e-3) / 1e9 / PEAK_HBM_GBS},
     }
+    if groups[2] > 2e-2:
+        result["hbm_kernels"]["head"] = {"GB/s": head_bytes / (groups[2] * 1e-3) / 1e9,
+                                         "frac": head_bytes / (groups[2] * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    else:
+        # calls of a few windows run the head inside the last residual unit's kernel: no launch of its own
+        result["hbm_kernels"]["head"] = {"note": "ran inside the last 64-channel unit's kernel (counted under convolutions)"}
 
     if args.detail:
         vae.set_timing(2)

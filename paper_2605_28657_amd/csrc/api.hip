@@ -25,6 +25,7 @@ constexpr int kTimingRing = 32;        // decode calls whose events are kept for
 // wide_operands) carries hi + lo bf16 pairs instead, for the inputs of the block's transposed conv and of its 1x1
 // convs (two MFMAs per k-step there; the dilated convs then take plain bf16).
 constexpr int kSplitWidth = 512;
+constexpr long long kHeadFusionFrames = 256;   // calls with at most this many extended frames run the head inside the last unit
 // Defaults of the config fields wide_operands / flags / small_tile_wgs where they are left at 0, from the environment
 // (read once when the library is loaded; for A/B timing of a whole program without touching its configs).
 const int g_env_wide_fmt = [] {
@@ -348,7 +349,9 @@ demon_status run_pass(demon_vae* v, const Workspace& ws, const Plan* plan, const
     const bool enc = v->encoder;
     const bool dual = wants_two_groups(v);
     // the head inside the last unit's kernel, unless the debug tap wants that unit's output in memory
-    const bool head_in_unit = v->head_fusable && !(v->tap_layer >= 0 && v->tap_dst);
+    // (bit-identical either way).  Only for calls of a few windows, where a launch less is what counts: for a whole clip
+    // the fused launch takes as long as the two it replaces.
+    const bool head_in_unit = v->head_fusable && !(v->tap_layer >= 0 && v->tap_dst) && plan->total_frames <= kHeadFusionFrames;
     const int n_frames = io.n_frames;
     const Slot* slots = plan->d_slots;
     const int ns = plan->n_slots, ml = plan->max_len;
