@@ -1,5 +1,5 @@
 /*
- * demon_vae.h -- C ABI of the windowed VAE decode for AMD MI355X (gfx950).
+ * demon_vae.h -- C ABI of the windowed VAE decode, and of its mirror the windowed encode, for AMD MI355X (gfx950).
  *
  * The operation is the windowed decode of paper section 3.6: a temporal audio
  * latent (25 Hz) is cut into windows, every window is extended by a halo of
