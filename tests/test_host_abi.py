@@ -44,6 +44,28 @@ def test_encoder_weight_count_and_receptive_field_match_the_oracle():
     assert pa.demon_vae_encoder_rf_from_config(di.TINY)[:2] == (15, 15)
 
 
+def test_receptive_fields_of_random_stacks_match_the_oracle():
+    """The host calculators (decoder and encoder) against the oracle's independent interval propagation on 200 seeded
+    random layer stacks: strides, widths, dilations and kernel sizes the benchmark stacks do not have."""
+    rng = np.random.default_rng(7)
+    for _ in range(200):
+        nb = int(rng.integers(1, 6))
+        spec = di.DecoderSpec(int(rng.choice([1, 4, 16, 64])), tuple(int(rng.choice([2, 4, 6, 8, 10, 12])) for _ in range(nb)),
+                              tuple(int(rng.choice([1, 8, 32, 64])) for _ in range(nb)),
+                              tuple(int(v) for v in rng.integers(1, 12, size=int(rng.integers(0, 5)))),
+                              int(rng.choice([1, 3, 5, 7, 9])), int(rng.choice([1, 3, 7, 11])), int(rng.integers(1, 4)))
+        assert pa.demon_vae_rf_from_config(spec) == oracle.receptive_field(spec), spec
+        hl, hr, sl, sr = pa.demon_vae_encoder_rf_from_config(spec)
+        assert (hl, hr) == oracle.encoder_receptive_field(spec), spec
+        lo, hi = oracle.encoder_backward_interval(spec, 0, 0)
+        assert (sl, sr) == (-lo, hi - (spec.total_stride - 1)), spec
+        a, b = int(rng.integers(0, 50)), int(rng.integers(0, 50))
+        a, b = min(a, b), max(a, b)
+        assert pa.demon_vae_forward_support(spec, a, b) == oracle.forward_interval(spec, a, b), spec
+        assert pa.demon_vae_weight_count(spec) == di.n_weights(spec)
+        assert pa.demon_vae_encoder_weight_count(spec) == sum(int(np.prod(sh)) for _, sh in di.encoder_weight_layout(spec))
+
+
 def test_receptive_field_matches_oracle_derivation():
     specs = [di.TINY, di.FULL, di.DecoderSpec(4, (4, 2), (8, 6), (1, 3), 7),
              di.DecoderSpec(4, (2, 2, 2), (8, 8, 8), (1, 2, 4), 5, 9), di.DecoderSpec(4, (10,), (8,), (), 7, 1)]
